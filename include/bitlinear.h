@@ -1,0 +1,138 @@
+/*
+ * bitlinear.h - C ABI of the MI355X (gfx950) BitLinear library.
+ *
+ * BitLinear is the 1-bit-weight, 8-bit-activation linear layer of BitNet
+ * (arXiv 2310.11453, Section 2.1):
+ *
+ *     y = W~ Quant(LN(x)) * beta * gamma / Q_b                       (Eq. 11)
+ *     W~ = Sign(W - alpha), alpha = mean(W), Sign(0) = -1             (Eq. 1-3)
+ *     beta = mean(|W|)                                                (Eq. 12)
+ *     Quant(x) = Clip(x * Q_b / gamma, ...), gamma = ||x||_inf        (Eq. 4-5)
+ *     Q_b = 2^(b-1) = 128 for the paper's b = 8.
+ *
+ * Conventions (all entry points)
+ *   - Every data pointer is a DEVICE pointer owned by the caller, 16-byte
+ *     aligned, unless marked "host".  The library allocates nothing, never
+ *     synchronises and never copies a scalar to the host: alpha, beta and
+ *     gamma stay in device memory.  Work is enqueued on `stream` (a
+ *     hipStream_t passed as void*; NULL = the default stream) and the call
+ *     returns at once.
+ *   - W is fp32 [N,K] row-major (K = fan-in, contiguous), X is fp32 [M,K],
+ *     Y is fp32 [M,N].  K must be a multiple of 32.
+ *   - Return value: BL_OK or a negative bl_status.  Argument errors are found
+ *     on the host before any launch.  M == 0 is a successful no-op.
+ *   - Inputs are never written; outputs must not alias inputs.  NaN/Inf in W
+ *     or X is undefined behaviour.  Results are deterministic run to run.
+ *   - Scratch memory is passed in as `workspace` (size from
+ *     bitlinear_workspace_bytes); calls sharing one workspace must be ordered
+ *     on one stream.
+ */
+#ifndef BITLINEAR_H
+#define BITLINEAR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    BL_OK = 0,
+    BL_ERR_NULL = -1,        /* a required pointer is NULL */
+    BL_ERR_SHAPE = -2,       /* M,N,K out of range, K % 32 != 0, size overflow */
+    BL_ERR_UNSUPPORTED = -3, /* unknown granularity / flag combination */
+    BL_ERR_WORKSPACE = -4,   /* workspace NULL or smaller than required */
+    BL_ERR_HIP = -5          /* a HIP launch reported an error */
+} bl_status;
+
+/* Granularity of the activation scale gamma.  The paper quantises per tensor
+ * while training and per token at inference (end of the paragraph after Eq. 6). */
+typedef enum { BL_GAMMA_PER_TOKEN = 0, BL_GAMMA_PER_TENSOR = 1 } bl_granularity;
+
+enum {
+    BL_FLAG_SKIP_LN = 1u,       /* input is already normalised: skip LN of Eq. 12 */
+    BL_FLAG_OUT_ACC_I32 = 2u,   /* forward/matmul: write the int32 accumulator of Eq. 7
+                                   into Y (reinterpreted as int32 [M,N]) instead of Eq. 11 */
+    BL_FLAG_BETA_CENTERED = 4u, /* pack: beta = mean|W - alpha| (prose above Eq. 1)
+                                   instead of the literal mean|W| of Eq. 12 */
+    BL_FLAG_PACK_TRANSPOSE = 8u /* pack: also store the bits with N as the fast axis,
+                                   which the dX contraction of the backward reads */
+};
+
+/* Operation selector for bitlinear_workspace_bytes. */
+typedef enum { BL_OP_PACK = 0, BL_OP_QUANT = 1, BL_OP_FORWARD = 2, BL_OP_BACKWARD = 3 } bl_op;
+
+/* host: size in bytes of the packed-weight blob for an [N,K] matrix (0 on bad
+ * shape).  The blob is the library's own tiled 1-bit layout (1 bit per weight,
+ * N padded to 16 and K to 512); with BL_FLAG_PACK_TRANSPOSE it holds a second
+ * copy tiled the other way. */
+size_t bitlinear_packed_bytes(int64_t N, int64_t K, unsigned flags);
+
+/* host: scratch bytes the given operation needs (never 0 for valid shapes). */
+size_t bitlinear_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int granularity,
+                                 unsigned flags);
+
+/* Eq. 1-3 and Eq. 12: binarise and pack a latent weight.
+ *   W       in   fp32 [N,K]
+ *   packed  out  blob of bitlinear_packed_bytes(N,K,flags) bytes
+ *   alpha   out  fp32 [1], mean of W (fp64 accumulation, rounded once)
+ *   beta    out  fp32 [1], mean |W| (or mean |W - alpha| with BL_FLAG_BETA_CENTERED)
+ * A weight's bit is 1 iff W[n,k] > alpha (so Sign(0) = -1). */
+int bitlinear_pack_weights(const float* W, int64_t N, int64_t K, unsigned flags, void* packed,
+                           float* alpha, float* beta, void* workspace, size_t workspace_bytes,
+                           void* stream);
+
+/* Inspection / interchange: blob -> canonical uint32 [N, K/32], where bit (k % 32)
+ * of word [n, k/32] is 1 iff W~[n,k] = +1 (Eq. 1). */
+int bitlinear_packed_to_canonical(const void* packed, int64_t N, int64_t K, uint32_t* canonical,
+                                  void* stream);
+
+/* Eq. 12 (LN) + Eq. 4-5: normalise each token over K, take gamma, round and clip.
+ *   X          in   fp32 [M,K]
+ *   ln_gain    in   fp32 [K] or NULL (no affine is shown in Eq. 12)
+ *   ln_bias    in   fp32 [K] or NULL
+ *   ln_eps          epsilon inside the square root of Eq. 12
+ *   codes      out  int8 [M,K], round-half-even of x^ * (128/gamma), clamped to [-128,127]
+ *   gamma      out  fp32 [M] (per token) or [1] (per tensor), floored at 1e-5
+ *   rowsum     out  int32 [M] = sum_k codes[m,k], or NULL
+ *   xhat_dump  out  fp32 [M,K] normalised input before quantisation, or NULL */
+int bitlinear_quant_act(const float* X, int64_t M, int64_t K, const float* ln_gain,
+                        const float* ln_bias, float ln_eps, int granularity, unsigned flags,
+                        int8_t* codes, float* gamma, int32_t* rowsum, float* xhat_dump,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
+/* Eq. 7 + Eq. 11 on already-quantised activations:
+ *   Y[m,n] = (sum_k codes[m,k] * W~[n,k]) * (beta * gamma_m / 128).
+ *   rowsum  in  int32 [M] as produced by bitlinear_quant_act (required)
+ *   Y       out fp32 [M,N] (int32 accumulators with BL_FLAG_OUT_ACC_I32) */
+int bitlinear_matmul(const int8_t* codes, const float* gamma, const int32_t* rowsum, int64_t M,
+                     int64_t K, const void* packed, int64_t N, const float* beta, int granularity,
+                     unsigned flags, float* Y, void* stream);
+
+/* Eq. 11, the whole layer: bitlinear_quant_act into the workspace, then
+ * bitlinear_matmul.  Arguments as above. */
+int bitlinear_forward(const float* X, int64_t M, int64_t K, const void* packed, int64_t N,
+                      const float* beta, const float* ln_gain, const float* ln_bias, float ln_eps,
+                      int granularity, unsigned flags, float* Y, void* workspace,
+                      size_t workspace_bytes, void* stream);
+
+/* Section 2.2, straight-through estimator: Sign, Clip and rounding are treated
+ * as identity, alpha/beta/gamma as constants.
+ *   dY     in   fp32 [M,N], rounded to bf16 as the MFMA operand
+ *   codes, gamma  in  as saved by the forward
+ *   packed in   blob packed with BL_FLAG_PACK_TRANSPOSE (needed when dX != NULL)
+ *   dX     out  fp32 [M,K] = beta * dY W~           (gradient w.r.t. LN(x)), or NULL
+ *   dW     out  fp32 [N,K] = dY^T (codes * gamma/128), or NULL */
+int bitlinear_backward_ste(const float* dY, int64_t M, int64_t N, int64_t K, const int8_t* codes,
+                           const float* gamma, int granularity, const void* packed,
+                           const float* beta, float* dX, float* dW, void* workspace,
+                           size_t workspace_bytes, void* stream);
+
+/* host: static description of a status code. */
+const char* bitlinear_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BITLINEAR_H */

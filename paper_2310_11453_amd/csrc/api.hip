@@ -1,0 +1,198 @@
+// C ABI of the BitLinear library: argument checks on the host, then launches.
+// Declarations and argument semantics: include/bitlinear.h.
+#include "../../include/bitlinear.h"
+#include "common.h"
+#include "kernels.h"
+
+using namespace bl;
+
+namespace {
+
+constexpr int64_t kMaxDim = (int64_t)1 << 30;
+constexpr unsigned kKnownFlags = BL_FLAG_SKIP_LN | BL_FLAG_OUT_ACC_I32 | BL_FLAG_BETA_CENTERED |
+                                 BL_FLAG_PACK_TRANSPOSE;
+
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+bool shape_ok(int64_t N, int64_t K) {
+    return N > 0 && K > 0 && N <= kMaxDim && K <= kMaxDim && K % 32 == 0 &&
+           N * K <= ((int64_t)1 << 40);
+}
+bool gran_ok(int g) { return g == BL_GAMMA_PER_TOKEN || g == BL_GAMMA_PER_TENSOR; }
+
+size_t tiles_bytes(int64_t rows, int64_t cols) { return (size_t)(tiles_n(rows) * tiles_k(cols)) * 1024; }
+
+// workspace layouts ------------------------------------------------------------
+struct QuantWs {
+    size_t rowstats, gmax, total;
+};
+QuantWs quant_ws(int64_t M, int granularity) {
+    QuantWs w{};
+    size_t off = 0;
+    w.rowstats = off;
+    off += granularity == BL_GAMMA_PER_TENSOR ? align256((size_t)M * 16) : 0;
+    w.gmax = off;
+    off += 256;
+    w.total = off;
+    return w;
+}
+struct ForwardWs {
+    size_t codes, gamma, rowsum, quant, total;
+};
+ForwardWs forward_ws(int64_t M, int64_t K, int granularity) {
+    ForwardWs w{};
+    size_t off = 0;
+    w.codes = off;
+    off += align256((size_t)M * (size_t)K);
+    w.gamma = off;
+    off += align256((size_t)M * 4);
+    w.rowsum = off;
+    off += align256((size_t)M * 4);
+    w.quant = off;
+    off += quant_ws(M, granularity).total;
+    w.total = off;
+    return w;
+}
+
+int check_hip(hipError_t e) { return e == hipSuccess ? BL_OK : BL_ERR_HIP; }
+
+}  // namespace
+
+extern "C" {
+
+size_t bitlinear_packed_bytes(int64_t N, int64_t K, unsigned flags) {
+    if (!shape_ok(N, K) || (flags & ~kKnownFlags)) return 0;
+    size_t b = tiles_bytes(N, K);
+    if (flags & BL_FLAG_PACK_TRANSPOSE) b += tiles_bytes(K, N);
+    return b;
+}
+
+size_t bitlinear_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int granularity,
+                                 unsigned flags) {
+    (void)flags;
+    if (!gran_ok(granularity)) return 0;
+    switch (op) {
+        case BL_OP_PACK:
+            if (!shape_ok(N, K)) return 0;
+            return align256((size_t)reduce_grid(N * K / 4) * 16);
+        case BL_OP_QUANT:
+            if (M < 0 || M > kMaxDim || K <= 0 || K % 32) return 0;
+            return quant_ws(M, granularity).total;
+        case BL_OP_FORWARD:
+            if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return 0;
+            return forward_ws(M, K, granularity).total;
+        case BL_OP_BACKWARD:
+            if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return 0;
+            return 256;
+        default:
+            return 0;
+    }
+}
+
+int bitlinear_pack_weights(const float* W, int64_t N, int64_t K, unsigned flags, void* packed,
+                           float* alpha, float* beta, void* workspace, size_t workspace_bytes,
+                           void* stream) {
+    if (!W || !packed || !alpha || !beta) return BL_ERR_NULL;
+    if (!shape_ok(N, K)) return BL_ERR_SHAPE;
+    if (flags & ~(BL_FLAG_BETA_CENTERED | BL_FLAG_PACK_TRANSPOSE)) return BL_ERR_UNSUPPORTED;
+    if (flags & BL_FLAG_PACK_TRANSPOSE) return BL_ERR_UNSUPPORTED;
+    const size_t need = bitlinear_workspace_bytes(BL_OP_PACK, 0, N, K, 0, flags);
+    if (!workspace || workspace_bytes < need) return BL_ERR_WORKSPACE;
+    return check_hip(launch_pack(W, N, K, (flags & BL_FLAG_BETA_CENTERED) != 0, (uint32_t*)packed,
+                                 alpha, beta, (double*)workspace, (hipStream_t)stream));
+}
+
+int bitlinear_packed_to_canonical(const void* packed, int64_t N, int64_t K, uint32_t* canonical,
+                                  void* stream) {
+    if (!packed || !canonical) return BL_ERR_NULL;
+    if (!shape_ok(N, K)) return BL_ERR_SHAPE;
+    return check_hip(launch_to_canonical((const uint32_t*)packed, N, K, canonical,
+                                         (hipStream_t)stream));
+}
+
+int bitlinear_quant_act(const float* X, int64_t M, int64_t K, const float* ln_gain,
+                        const float* ln_bias, float ln_eps, int granularity, unsigned flags,
+                        int8_t* codes, float* gamma, int32_t* rowsum, float* xhat_dump,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+    if (!X || !codes || !gamma) return BL_ERR_NULL;
+    if (M < 0 || M > kMaxDim || K <= 0 || K > kMaxDim || K % 32) return BL_ERR_SHAPE;
+    if (!gran_ok(granularity) || (flags & ~BL_FLAG_SKIP_LN)) return BL_ERR_UNSUPPORTED;
+    if (!quant_supported(K)) return BL_ERR_UNSUPPORTED;
+    const QuantWs ws = quant_ws(M, granularity);
+    if (!workspace || workspace_bytes < ws.total) return BL_ERR_WORKSPACE;
+    if (M == 0) return BL_OK;
+    QuantArgs a{};
+    a.X = X; a.M = M; a.K = K; a.gain = ln_gain; a.bias = ln_bias; a.eps = ln_eps;
+    a.skip_ln = (flags & BL_FLAG_SKIP_LN) != 0;
+    a.per_tensor = granularity == BL_GAMMA_PER_TENSOR;
+    a.codes = codes; a.gamma = gamma; a.rowsum = rowsum; a.xhat_dump = xhat_dump;
+    a.rowstats = (double*)((char*)workspace + ws.rowstats);
+    a.gmax_bits = (uint32_t*)((char*)workspace + ws.gmax);
+    return check_hip(launch_quant(a, (hipStream_t)stream));
+}
+
+int bitlinear_matmul(const int8_t* codes, const float* gamma, const int32_t* rowsum, int64_t M,
+                     int64_t K, const void* packed, int64_t N, const float* beta, int granularity,
+                     unsigned flags, float* Y, void* stream) {
+    if (!codes || !gamma || !rowsum || !packed || !beta || !Y) return BL_ERR_NULL;
+    if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return BL_ERR_SHAPE;
+    if (!gran_ok(granularity) || (flags & ~BL_FLAG_OUT_ACC_I32)) return BL_ERR_UNSUPPORTED;
+    if (M == 0) return BL_OK;
+    GemmArgs a{};
+    a.codes = codes; a.gamma = gamma; a.rowsum = rowsum; a.M = M; a.K = K; a.N = N;
+    a.packed = (const uint32_t*)packed; a.beta = beta;
+    a.per_tensor = granularity == BL_GAMMA_PER_TENSOR;
+    a.out_acc = (flags & BL_FLAG_OUT_ACC_I32) != 0;
+    a.Y = Y;
+    if (M <= 16) return check_hip(launch_gemm_decode(a, (hipStream_t)stream));
+    return check_hip(launch_gemm_prefill(a, (hipStream_t)stream));
+}
+
+int bitlinear_forward(const float* X, int64_t M, int64_t K, const void* packed, int64_t N,
+                      const float* beta, const float* ln_gain, const float* ln_bias, float ln_eps,
+                      int granularity, unsigned flags, float* Y, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+    if (!X || !packed || !beta || !Y) return BL_ERR_NULL;
+    if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return BL_ERR_SHAPE;
+    if (!gran_ok(granularity) || (flags & ~(BL_FLAG_SKIP_LN | BL_FLAG_OUT_ACC_I32)))
+        return BL_ERR_UNSUPPORTED;
+    const ForwardWs ws = forward_ws(M, K, granularity);
+    if (!workspace || workspace_bytes < ws.total) return BL_ERR_WORKSPACE;
+    if (M == 0) return BL_OK;
+    char* base = (char*)workspace;
+    int8_t* codes = (int8_t*)(base + ws.codes);
+    float* gamma = (float*)(base + ws.gamma);
+    int32_t* rowsum = (int32_t*)(base + ws.rowsum);
+    int rc = bitlinear_quant_act(X, M, K, ln_gain, ln_bias, ln_eps, granularity,
+                                 flags & BL_FLAG_SKIP_LN, codes, gamma, rowsum, nullptr,
+                                 base + ws.quant, workspace_bytes - ws.quant, stream);
+    if (rc != BL_OK) return rc;
+    return bitlinear_matmul(codes, gamma, rowsum, M, K, packed, N, beta, granularity,
+                            flags & BL_FLAG_OUT_ACC_I32, Y, stream);
+}
+
+int bitlinear_backward_ste(const float* dY, int64_t M, int64_t N, int64_t K, const int8_t* codes,
+                           const float* gamma, int granularity, const void* packed,
+                           const float* beta, float* dX, float* dW, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+    (void)workspace; (void)workspace_bytes; (void)stream;
+    if (!dY || !codes || !gamma || !beta) return BL_ERR_NULL;
+    if (dX && !packed) return BL_ERR_NULL;
+    if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return BL_ERR_SHAPE;
+    if (!gran_ok(granularity)) return BL_ERR_UNSUPPORTED;
+    return BL_ERR_UNSUPPORTED;
+}
+
+const char* bitlinear_status_string(int status) {
+    switch (status) {
+        case BL_OK: return "ok";
+        case BL_ERR_NULL: return "a required pointer is NULL";
+        case BL_ERR_SHAPE: return "bad shape (M, N, K out of range or K not a multiple of 32)";
+        case BL_ERR_UNSUPPORTED: return "unsupported granularity, flag or size";
+        case BL_ERR_WORKSPACE: return "workspace missing or too small";
+        case BL_ERR_HIP: return "HIP launch failed";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

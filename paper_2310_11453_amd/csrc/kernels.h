@@ -1,0 +1,49 @@
+// Host-side launchers implemented by the kernel files; called from api.hip only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace bl {
+
+// pack.hip
+int reduce_grid(int64_t count4);
+hipError_t launch_pack(const float* W, int64_t N, int64_t K, bool beta_centered, uint32_t* packed,
+                       float* alpha, float* beta, double* partials, hipStream_t s);
+hipError_t launch_to_canonical(const uint32_t* packed, int64_t N, int64_t K, uint32_t* canonical,
+                               hipStream_t s);
+
+// quant.hip
+struct QuantArgs {
+    const float* X;
+    int64_t M, K;
+    const float* gain;
+    const float* bias;
+    float eps;
+    bool skip_ln;
+    bool per_tensor;
+    int8_t* codes;
+    float* gamma;
+    int32_t* rowsum;
+    float* xhat_dump;
+    double* rowstats;   // per-tensor only: [M][2] = (mean, rstd)
+    uint32_t* gmax_bits; // per-tensor only: [1], bit pattern of the running max
+};
+bool quant_supported(int64_t K);
+hipError_t launch_quant(const QuantArgs& a, hipStream_t s);
+
+// gemm_decode.hip / gemm_prefill.hip
+struct GemmArgs {
+    const int8_t* codes;
+    const float* gamma;
+    const int32_t* rowsum;
+    int64_t M, K, N;
+    const uint32_t* packed;
+    const float* beta;
+    bool per_tensor;
+    bool out_acc;
+    float* Y;
+};
+hipError_t launch_gemm_decode(const GemmArgs& a, hipStream_t s);
+hipError_t launch_gemm_prefill(const GemmArgs& a, hipStream_t s);
+
+}  // namespace bl

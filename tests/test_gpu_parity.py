@@ -1,0 +1,235 @@
+"""GPU parity: the HIP path, called through the C ABI binding, against the CPU oracle.
+
+Integer results (packed bits, int8 codes, int32 accumulators) must be bit-exact; codes are
+compared "given the same normalised input" (the oracle quantises the x^ the GPU dumped) and,
+separately, x^ itself is compared with the oracle's fp64 LayerNorm.  fp32 outputs: exact
+given shared codes/gamma/beta (the epilogue is one fp32 multiply on both sides), and
+within 1e-3 relative (Frobenius, and max error against rms) end to end.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+f32 = np.float32
+
+
+@pytest.fixture(scope="module")
+def bl():
+    import paper_2310_11453_amd as lib
+    lib.load_library()
+    assert torch.cuda.is_available()
+    return lib
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def host(t):
+    return t.cpu().numpy()
+
+
+# ------------------------------------------------------------------ weights (Eq. 1-3, 12)
+PACK_SHAPES = [(512, 256), (3, 32), (16, 512), (17, 544), (200, 96), (100, 1056), (2048, 2048)]
+
+
+@pytest.mark.parametrize("N,K", PACK_SHAPES)
+@pytest.mark.parametrize("mean", [0.0, 0.04])
+def test_pack_bits_alpha_beta(bl, N, K, mean):
+    print(f"pack N={N} K={K} mean={mean}", flush=True)
+    W = wl.make_weight(N, K, 0.02, seed=wl.seed_for(0, N + K), mean=mean)
+    a, b = oracle.weight_stats(W)
+    words = oracle.pack_canonical(oracle.binarize(W, a))
+    packed, alpha, beta = bl.bitlinear_pack_weights(dev(W))
+    canon = host(bl.bitlinear_packed_to_canonical(packed, N, K)).view(np.uint32)
+    assert host(alpha)[0] == a and host(beta)[0] == b
+    assert np.array_equal(canon, words)
+    _, _, beta_c = bl.bitlinear_pack_weights(dev(W), flags=bl.FLAG_BETA_CENTERED)
+    assert host(beta_c)[0] == oracle.weight_stats(W, beta_centered=True)[1]
+
+
+def test_pack_constant_weight_sign_zero(bl):
+    W = np.full((40, 64), 0.03125, f32)
+    packed, alpha, beta = bl.bitlinear_pack_weights(dev(W))
+    assert host(alpha)[0] == f32(0.03125) and host(beta)[0] == f32(0.03125)
+    assert not host(bl.bitlinear_packed_to_canonical(packed, 40, 64)).any()
+
+
+def test_pack_deterministic(bl):
+    W = dev(wl.make_weight(1000, 2080, 0.02, seed=5))
+    p1, a1, b1 = bl.bitlinear_pack_weights(W)
+    p2, a2, b2 = bl.bitlinear_pack_weights(W)
+    assert torch.equal(p1, p2) and torch.equal(a1, a2) and torch.equal(b1, b2)
+
+
+# ------------------------------------------------------------------ activations (Eq. 12, 4, 5)
+QUANT_SHAPES = [(8, 256), (1, 2048), (5, 96), (3, 544), (16, 8192), (33, 4096), (7, 7168),
+                (2, 28672), (4, 16384), (64, 1024)]
+
+
+@pytest.mark.parametrize("M,K", QUANT_SHAPES)
+@pytest.mark.parametrize("per_tensor", [False, True])
+def test_quant_codes_bit_exact_given_xhat(bl, M, K, per_tensor):
+    print(f"quant M={M} K={K} per_tensor={per_tensor}", flush=True)
+    X = wl.make_activation(M, K, wl.seed_for(1, M + K), outlier_p=0.001, outlier_mul=20.0)
+    X = X * f32(1.7) + f32(0.3)
+    codes, gamma, rowsum, xhat = bl.bitlinear_quant_act(dev(X), 1e-5, per_tensor, want_xhat=True)
+    xh_gpu = host(xhat)
+    g_ref = oracle.absmax(xh_gpu, per_tensor)
+    assert np.array_equal(host(gamma), g_ref)
+    q_ref = oracle.quantize(xh_gpu, g_ref, per_tensor)
+    assert np.array_equal(host(codes), q_ref)
+    assert np.array_equal(host(rowsum)[:M], q_ref.astype(np.int64).sum(1))
+    xh_ref = oracle.layernorm(X, 1e-5)
+    assert np.abs(xh_gpu - xh_ref).max() <= 2e-6 * max(1.0, np.abs(xh_ref).max())
+    # end to end from raw X: the fp64 LayerNorm on both sides rounds to the same fp32
+    q_e2e = oracle.quantize(xh_ref, oracle.absmax(xh_ref, per_tensor), per_tensor)
+    mism = int((host(codes) != q_e2e).sum())
+    assert mism <= max(1, M * K // 100000), f"{mism} codes differ end to end"
+
+
+def test_quant_skip_ln_ties_clip_zero_row_affine(bl):
+    row = np.zeros((3, 32), f32)
+    row[0, :8] = [1, 1 / 256, 3 / 256, 5 / 256, -1 / 256, -3 / 256, -1, 127.5 / 128]
+    row[2] = wl.make_activation(1, 32, 3)[0]
+    codes, gamma, rowsum, _ = bl.bitlinear_quant_act(dev(row), flags=bl.FLAG_SKIP_LN)
+    c = host(codes)
+    assert c[0, :8].tolist() == [127, 0, 2, 2, 0, -2, -128, 127]
+    assert not c[1].any() and host(gamma)[1] == f32(1e-5)
+    g = oracle.absmax(row)
+    assert np.array_equal(c, oracle.quantize(row, g)) and np.array_equal(host(gamma), g)
+    # constant row through LN: normalises to zero
+    X = np.full((2, 64), 3.25, f32)
+    codes, gamma, _, _ = bl.bitlinear_quant_act(dev(X))
+    assert not host(codes).any() and (host(gamma) == f32(1e-5)).all()
+    # affine LN
+    X = wl.make_activation(6, 320, 9)
+    gain = np.linspace(0.5, 1.5, 320).astype(f32)
+    bias = np.linspace(-1, 1, 320).astype(f32)
+    codes, gamma, _, xhat = bl.bitlinear_quant_act(dev(X), ln_gain=dev(gain), ln_bias=dev(bias),
+                                                   want_xhat=True)
+    ref = oracle.layernorm(X, 1e-5, gain, bias)
+    assert np.abs(host(xhat) - ref).max() <= 4e-6
+    assert np.array_equal(host(codes), oracle.quantize(host(xhat), host(gamma)))
+
+
+# ------------------------------------------------------------------ matmul (Eq. 7, 11)
+# (M, K, N): decode path (M <= 16) and MFMA-tiled path (M > 16); several tiles + ragged tails
+GEMM_SHAPES = [(8, 256, 512), (1, 2048, 2048), (4, 96, 40), (16, 544, 200), (13, 1056, 72),
+               (3, 8192, 64), (16, 7168, 96), (2, 16384, 48), (5, 28672, 32), (1, 2048, 6144),
+               (17, 256, 512), (70, 544, 200), (64, 1056, 136), (300, 96, 260), (256, 2048, 384),
+               (513, 1024, 130)]
+
+
+@pytest.mark.parametrize("M,K,N", GEMM_SHAPES)
+def test_matmul_acc_bit_exact_and_y(bl, M, K, N):
+    print(f"matmul M={M} K={K} N={N}", flush=True)
+    sd = wl.seed_for(2, M + K + N)
+    W = wl.make_weight(N, K, 0.02, sd)
+    X = wl.make_activation(M, K, sd)
+    packed, alpha, beta = bl.bitlinear_pack_weights(dev(W))
+    codes, gamma, rowsum, _ = bl.bitlinear_quant_act(dev(X))
+    sign = oracle.unpack_canonical(host(bl.bitlinear_packed_to_canonical(packed, N, K)).view(np.uint32), K)
+    acc_ref = oracle.matmul_i32(host(codes), sign)
+    acc = bl.bitlinear_matmul(codes, gamma, rowsum, packed, N, beta, flags=bl.FLAG_OUT_ACC_I32)
+    assert np.array_equal(host(acc), acc_ref)
+    y = bl.bitlinear_matmul(codes, gamma, rowsum, packed, N, beta)
+    y_ref = oracle.dequant(acc_ref, host(gamma), host(beta))
+    assert np.array_equal(host(y), y_ref)  # one fp32 multiply per output on both sides
+    # extreme codes: every product has the same sign, |acc| = 128 K
+    q = torch.full((M, K), -128, dtype=torch.int8, device="cuda")
+    rs = torch.full((M,), -128 * K, dtype=torch.int32, device="cuda")
+    acc = bl.bitlinear_matmul(q, gamma, rs, packed, N, beta, flags=bl.FLAG_OUT_ACC_I32)
+    assert np.array_equal(host(acc), np.repeat((-128 * sign.astype(np.int64).sum(1))[None], M, 0))
+
+
+@pytest.mark.parametrize("M,K,N,per_tensor", [(8, 256, 512, False), (8, 256, 512, True),
+                                              (16, 2048, 2048, False), (130, 512, 272, True),
+                                              (40, 1024, 1000, False)])
+def test_forward_end_to_end(bl, M, K, N, per_tensor):
+    print(f"forward M={M} K={K} N={N} per_tensor={per_tensor}", flush=True)
+    sd = wl.seed_for(0, M + K + N)
+    W = wl.make_weight(N, K, 0.02, sd)
+    X = wl.make_activation(M, K, sd)
+    r = oracle.forward(X, W, per_tensor=per_tensor)
+    packed, alpha, beta = bl.bitlinear_pack_weights(dev(W))
+    y = host(bl.bitlinear_forward(dev(X), packed, N, beta, per_tensor=per_tensor))
+    rms = np.sqrt(np.mean(r["y"].astype(np.float64) ** 2))
+    assert np.abs(y - r["y"]).max() <= 1e-3 * rms
+    assert np.linalg.norm(y - r["y"]) <= 1e-3 * np.linalg.norm(r["y"])
+    acc = host(bl.bitlinear_forward(dev(X), packed, N, beta, per_tensor=per_tensor,
+                                    flags=bl.FLAG_OUT_ACC_I32))
+    assert (acc != r["acc"]).mean() <= 1e-3  # differs only where an x^ sits on a rounding tie
+
+
+def test_empty_batch_and_errors(bl):
+    W = dev(wl.make_weight(32, 64, 0.02, 1))
+    packed, alpha, beta = bl.bitlinear_pack_weights(W)
+    y = bl.bitlinear_forward(torch.empty((0, 64), device="cuda"), packed, 32, beta)
+    assert y.shape == (0, 32)
+    with pytest.raises(bl.BitLinearError):
+        bl.bitlinear_forward(torch.empty((2, 48), device="cuda"), packed, 32, beta)  # K % 32
+    with pytest.raises(bl.BitLinearError):
+        bl.bitlinear_forward(torch.empty((2, 64), device="cuda"), packed, 32, beta,
+                             workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
+
+
+# ------------------------------------------------------------------ full benchmark sizes
+def _sampled_check(bl, M, K, N, w_std, outlier_p, outlier_mul, seed, n_samples=4096):
+    """Full-size run in the launch configuration the bench uses; all bits and codes are
+    checked, accumulators and outputs on a seeded sample the oracle computes one by one."""
+    W = wl.make_weight(N, K, w_std, seed)
+    X = wl.make_activation(M, K, seed, outlier_p, outlier_mul)
+    packed, alpha, beta = bl.bitlinear_pack_weights(dev(W))
+    a, b = oracle.weight_stats(W)
+    assert host(alpha)[0] == a and host(beta)[0] == b
+    canon = host(bl.bitlinear_packed_to_canonical(packed, N, K)).view(np.uint32)
+    sign = oracle.binarize(W, a)
+    assert np.array_equal(canon, oracle.pack_canonical(sign))
+    del W
+    Xd = dev(X)
+    codes, gamma, rowsum, xhat = bl.bitlinear_quant_act(Xd, want_xhat=True)
+    xh = host(xhat)
+    del xhat
+    g_ref = oracle.absmax(xh)
+    assert np.array_equal(host(gamma), g_ref)
+    assert np.array_equal(host(codes), oracle.quantize(xh, g_ref))
+    del xh
+    y = host(bl.bitlinear_forward(Xd, packed, N, beta))
+    rng = np.random.default_rng(seed)
+    rows = rng.integers(0, M, n_samples)
+    cols = rng.integers(0, N, n_samples)
+    rows[:4] = [0, M - 1, 0, M - 1]
+    cols[:4] = [0, N - 1, N - 1, 0]
+    acc = oracle.matmul_i32_sampled(host(codes), sign, rows, cols)
+    sc = (b * g_ref[rows]) / f32(128.0)
+    y_ref = acc.astype(f32) * sc
+    assert np.array_equal(y[rows, cols], y_ref)
+    # property that holds at any size: Var(y) ~ K beta^2 E[x~^2] (Eq. 8-10)
+    return y
+
+
+@pytest.mark.parametrize("li,M", [(0, 1), (1, 4), (2, 16), (3, 16)])
+def test_full_size_decode_1p3b(bl, li, M):
+    L = wl.CONFIGS[1].layers[li]
+    print(f"full decode {L} M={M}", flush=True)
+    _sampled_check(bl, M, L.K, L.N, 0.02, 0, 1, wl.seed_for(1, li))
+
+
+@pytest.mark.parametrize("li", [0, 1])
+def test_full_size_prefill_6p7b(bl, li):
+    L = wl.CONFIGS[2].layers[li]
+    print(f"full prefill {L}", flush=True)
+    y = _sampled_check(bl, 2048, L.K, L.N, 0.02, 0.001, 20.0, wl.seed_for(2, li))
+    assert np.isfinite(y).all()
+
+
+@pytest.mark.parametrize("li,M", [(0, 64), (2, 64), (1, 16)])
+def test_full_size_30b_batched_decode(bl, li, M):
+    L = wl.CONFIGS[3].layers[li]
+    print(f"full 30b {L} M={M}", flush=True)
+    _sampled_check(bl, M, L.K, L.N, 0.01, 0, 1, wl.seed_for(3, li), n_samples=2048)
