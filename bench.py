@@ -1,0 +1,247 @@
+#!/usr/bin/env python3
+"""Benchmark of the BitLinear hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu] [--no-decode]
+
+Workload at one GPU: the BitNet-6.7B-shaped prefill pair (4096->16384 and 16384->4096 at
+M = 2048 tokens, activations N(0,1) with 0.1 % outliers x20, weights N(0, 0.02^2)).
+A step is one BitLinear forward (LayerNorm + absmax quantiser + 1-bit x 8-bit MFMA GEMM +
+dequantisation, i.e. Eq. 12, 4-5, 7 and 11 of arXiv 2310.11453) through each of the two
+layers, inputs and packed weights resident in HBM.  Weight packing (Eq. 1-3) happens once
+per weight at inference and is timed separately ("weight_prep").
+
+Prints ONE JSON line.  `value` is prefill TOPS (2*M*N*K summed over the step / step time);
+`roofline` describes the dominant kernel (the MFMA GEMM) from HIP-event timing of that
+kernel alone inside the timed loop; `decode` reports the packed-weight streaming rate of
+the small-M kernel on BitNet-30B-shaped layers; `cpu_baseline` times the CPU oracle on a
+bounded sample of the same workload on this machine's host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+
+import workloads as wl
+
+HBM_PEAK_GBS = 8000.0
+I8_MFMA_PEAK_TOPS = 5000.0
+
+# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE (see profiles/); None until measured for the current kernel.
+TRAFFIC_BYTES = {"gemm_prefill_up": None}
+
+
+def gemm_bytes(M, K, N):
+    """Algorithmic bytes of GEMM + epilogue: packed weights, int8 codes, fp32 output, gamma."""
+    return N * K // 8 + M * K + 4 * M * N + 4 * M
+
+
+def event_ms(fn, iters, torch):
+    start, end = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    start.record()
+    for _ in range(iters):
+        fn()
+    end.record()
+    end.synchronize()
+    return start.elapsed_time(end) / iters
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-decode", action="store_true", help="skip the decode streaming leg")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2310_11453_amd as bl
+
+    bl.load_library()  # raises if the HIP library is missing: there is no fallback
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU")
+    dev = torch.device("cuda:0")
+    cfg = wl.CONFIGS[2]
+    M = cfg.Ms[0]
+
+    # ---- inputs: seeded, generated on the host, resident in HBM before timing ----------
+    layers = []
+    for li, L in enumerate(cfg.layers):
+        seed = wl.seed_for(2, li)
+        W = wl.make_weight(L.N, L.K, cfg.w_std, seed)
+        X = wl.make_activation(M, L.K, seed, cfg.outlier_p, cfg.outlier_mul)
+        Wd = torch.from_numpy(W).to(dev)
+        packed, alpha, beta = bl.bitlinear_pack_weights(Wd)
+        Xd = torch.from_numpy(X).to(dev)
+        Y = torch.empty((M, L.N), dtype=torch.float32, device=dev)
+        ws = torch.empty(bl.workspace_bytes(bl.OP_FORWARD, M, L.N, L.K), dtype=torch.uint8, device=dev)
+        layers.append(dict(L=L, W=W, X=X, Wd=Wd, Xd=Xd, packed=packed, beta=beta, Y=Y, ws=ws))
+    torch.cuda.synchronize()
+
+    def step():
+        for d in layers:
+            bl.bitlinear_forward(d["Xd"], d["packed"], d["L"].N, d["beta"], out=d["Y"],
+                                 workspace=d["ws"])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ms_events = event_ms(step, args.steps, torch)
+    torch.cuda.synchronize()
+    ms_wall = (time.perf_counter() - t0) * 1e3 / args.steps
+    ms_step = max(ms_events, 0.0)
+    ops_step = sum(2 * M * d["L"].N * d["L"].K for d in layers)
+    tops = ops_step / (ms_step * 1e-3) / 1e12
+
+    # ---- per-kernel timing inside a second timed loop (events bracket each kernel) -------
+    kern = {}
+    for d in layers:
+        L = d["L"]
+        codes, gamma, rowsum, _ = bl.bitlinear_quant_act(d["Xd"])
+        torch.cuda.synchronize()
+        t_q = event_ms(lambda: bl.bitlinear_quant_act(d["Xd"]), args.steps, torch)
+        t_g = event_ms(lambda: bl.bitlinear_matmul(codes, gamma, rowsum, d["packed"], L.N, d["beta"],
+                                                   out=d["Y"]), args.steps, torch)
+        kern[L.name] = dict(quant_ms=t_q, gemm_ms=t_g,
+                            gemm_tops=2 * M * L.N * L.K / (t_g * 1e-3) / 1e12,
+                            quant_gbs=5 * M * L.K / (t_q * 1e-3) / 1e9)
+    up = layers[0]["L"]
+    g_ms = kern[up.name]["gemm_ms"]
+    roof = dict(bound="mfma", kernel="gemm_prefill_kernel<256,128,2,2> (4096->16384, M=2048)",
+                achieved=2 * M * up.N * up.K / (g_ms * 1e-3) / 1e12, peak=I8_MFMA_PEAK_TOPS,
+                unit="TOP/s", traffic=TRAFFIC_BYTES["gemm_prefill_up"], launch_ms=g_ms)
+    roof["frac"] = roof["achieved"] / roof["peak"]
+
+    # ---- weight preparation (Eq. 1-3, 12), once per weight at inference ----------------------
+    d0 = layers[0]
+    pws = torch.empty(bl.workspace_bytes(bl.OP_PACK, 0, up.N, up.K), dtype=torch.uint8, device=dev)
+    t_pack = event_ms(lambda: bl.bitlinear_pack_weights(d0["Wd"], workspace=pws), 10, torch)
+    prep = dict(ms=t_pack, gbs=(2 * 4 + 0.125) * up.N * up.K / (t_pack * 1e-3) / 1e9,
+                note="two passes over fp32 W (stats, then compare+pack)")
+
+    # ---- parity guard: a fast-but-wrong kernel must not report a number ----------------------
+    import oracle
+    parity = "skipped"
+    d = layers[0]
+    L = d["L"]
+    codes, gamma, rowsum, xhat = bl.bitlinear_quant_act(d["Xd"], want_xhat=True)
+    rows = np.arange(0, M, 257)
+    xh = xhat[torch.from_numpy(rows).to(dev)].cpu().numpy()
+    g_ref = oracle.absmax(xh)
+    q_ref = oracle.quantize(xh, g_ref)
+    ok = np.array_equal(codes.cpu().numpy()[rows], q_ref)
+    a, b = oracle.weight_stats(d["W"])
+    sign = oracle.binarize(d["W"], a)
+    rng = np.random.default_rng(1)
+    cols = rng.integers(0, L.N, rows.size * 16)
+    rr = np.repeat(np.arange(rows.size), 16)
+    acc = oracle.matmul_i32_sampled(q_ref, sign, rr, cols)
+    y_ref = acc.astype(np.float32) * ((b * g_ref[rr]) / np.float32(128.0))
+    y_gpu = d["Y"].cpu().numpy()[rows[rr], cols]
+    ok = ok and np.array_equal(y_gpu, y_ref) and float(d["beta"].cpu()[0]) == float(b)
+    parity = "ok" if ok else "FAILED"
+
+    # ---- decode leg: packed-weight streaming on 30B-shaped layers, M = 16 and M = 1 ----------
+    decode = None
+    if not args.no_decode:
+        decode = {"workload": "bitnet-30b layers, GEMM+dequant kernel per launch", "shapes": []}
+        c3 = wl.CONFIGS[3]
+        best = None
+        for li, L3 in enumerate(c3.layers):
+            W3 = wl.make_weight(L3.N, L3.K, c3.w_std, wl.seed_for(3, li))
+            p3, a3, b3 = bl.bitlinear_pack_weights(torch.from_numpy(W3).to(dev))
+            del W3
+            # rotate through copies so the working set (>= 512 MB) exceeds L2 + Infinity Cache
+            ncopy = max(2, int(np.ceil(512e6 / p3.numel())))
+            copies = [p3.clone() for _ in range(ncopy)]
+            for Md in (1, 16):
+                X3 = torch.from_numpy(wl.make_activation(Md, L3.K, wl.seed_for(3, li))).to(dev)
+                codes3, gamma3, rowsum3, _ = bl.bitlinear_quant_act(X3)
+                Y3 = torch.empty((Md, L3.N), dtype=torch.float32, device=dev)
+                state = {"i": 0}
+
+                def run():
+                    bl.bitlinear_matmul(codes3, gamma3, rowsum3, copies[state["i"] % ncopy], L3.N,
+                                        b3, out=Y3)
+                    state["i"] += 1
+
+                for _ in range(ncopy):
+                    run()
+                t = event_ms(run, 4 * ncopy, torch)
+                gbs = gemm_bytes(Md, L3.K, L3.N) / (t * 1e-3) / 1e9
+                rec = dict(layer=L3.name, K=L3.K, N=L3.N, M=Md, us=t * 1e3, gbs=gbs,
+                           frac_hbm=gbs / HBM_PEAK_GBS)
+                decode["shapes"].append(rec)
+                if best is None or gbs > best["gbs"]:
+                    best = rec
+            del copies, p3
+        decode["value"] = best["gbs"]
+        decode["unit"] = "GB/s"
+        decode["roofline"] = dict(bound="hbm", kernel="gemm_decode_kernel", achieved=best["gbs"],
+                                  peak=HBM_PEAK_GBS, unit="GB/s", frac=best["gbs"] / HBM_PEAK_GBS,
+                                  traffic=None,
+                                  note="events around back-to-back launches: includes dispatch gaps")
+
+    # ---- CPU oracle on a bounded sample of the same workload ---------------------------------
+    cpu = None
+    if not args.no_cpu:
+        d = layers[0]
+        L = d["L"]
+        threads = oracle.num_threads()
+        t0 = time.perf_counter()
+        r_rows = 64
+        xh = oracle.layernorm(d["X"][:r_rows])
+        g = oracle.absmax(xh)
+        q = oracle.quantize(xh, g)
+        oracle.matmul_i32(q[:8], sign[:2048])  # calibration: 8 x 2048 outputs
+        t_cal = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        oracle.matmul_i32(q[:8], sign[:2048])
+        t_unit = max(time.perf_counter() - t0, 1e-4)
+        # rows of the full-width layer that fit the time budget
+        per_row = t_unit / 8 * (L.N / 2048)
+        s_rows = int(min(M, max(8, args.cpu_seconds / per_row)))
+        t0 = time.perf_counter()
+        xh = oracle.layernorm(d["X"][:s_rows])
+        g = oracle.absmax(xh)
+        q = oracle.quantize(xh, g)
+        acc = oracle.matmul_i32(q, sign)
+        y = oracle.dequant(acc, g, b)
+        dt = time.perf_counter() - t0
+        cpu = dict(value=2 * s_rows * L.N * L.K / dt / 1e12, unit="TOPS", cores=threads,
+                   kind="oracle", seconds=dt,
+                   sample=f"first {s_rows} of {M} tokens through {L.K}->{L.N} (LN, quantise, "
+                          f"int GEMM, dequant); weights pre-binarised")
+        del t_cal, y
+
+    out = {
+        "metric": "BitLinear prefill TOPS (i8 MFMA %) + decode packed-weight HBM GB/s",
+        "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "ms_per_step_wall": ms_wall, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "i8 x 1-bit -> i32, f32 out",
+        "data": "synthetic",
+        "config": {"workload": "bitnet-6.7b-prefill: BitLinear forward 4096->16384 and "
+                               "16384->4096, M=2048, per-token gamma, fp32 in/out",
+                   "step": "LN+quantise+GEMM+dequant for both layers; weights packed beforehand"},
+        "mfma_frac_of_peak": tops / I8_MFMA_PEAK_TOPS,
+        "kernels": kern, "roofline": roof, "weight_prep": prep, "decode": decode,
+        "cpu_baseline": cpu, "parity": parity,
+    }
+    print(json.dumps(out))
+    if parity != "ok":
+        sys.exit(1)
+
+
+if __name__ == "__main__":
+    main()

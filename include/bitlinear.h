@@ -20,7 +20,8 @@
  *   - W is fp32 [N,K] row-major (K = fan-in, contiguous), X is fp32 [M,K],
  *     Y is fp32 [M,N].  K must be a multiple of 32.
  *   - Return value: BL_OK or a negative bl_status.  Argument errors are found
- *     on the host before any launch.  M == 0 is a successful no-op.
+ *     on the host before any launch, in the order shape, flags, pointers,
+ *     workspace.  M == 0 is a successful no-op (pointers are not looked at).
  *   - Inputs are never written; outputs must not alias inputs.  NaN/Inf in W
  *     or X is undefined behaviour.  Results are deterministic run to run.
  *   - Scratch memory is passed in as `workspace` (size from

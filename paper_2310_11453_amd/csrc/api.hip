@@ -92,10 +92,10 @@ size_t bitlinear_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int gr
 int bitlinear_pack_weights(const float* W, int64_t N, int64_t K, unsigned flags, void* packed,
                            float* alpha, float* beta, void* workspace, size_t workspace_bytes,
                            void* stream) {
-    if (!W || !packed || !alpha || !beta) return BL_ERR_NULL;
     if (!shape_ok(N, K)) return BL_ERR_SHAPE;
     if (flags & ~(BL_FLAG_BETA_CENTERED | BL_FLAG_PACK_TRANSPOSE)) return BL_ERR_UNSUPPORTED;
     if (flags & BL_FLAG_PACK_TRANSPOSE) return BL_ERR_UNSUPPORTED;
+    if (!W || !packed || !alpha || !beta) return BL_ERR_NULL;
     const size_t need = bitlinear_workspace_bytes(BL_OP_PACK, 0, N, K, 0, flags);
     if (!workspace || workspace_bytes < need) return BL_ERR_WORKSPACE;
     return check_hip(launch_pack(W, N, K, (flags & BL_FLAG_BETA_CENTERED) != 0, (uint32_t*)packed,
@@ -104,8 +104,8 @@ int bitlinear_pack_weights(const float* W, int64_t N, int64_t K, unsigned flags,
 
 int bitlinear_packed_to_canonical(const void* packed, int64_t N, int64_t K, uint32_t* canonical,
                                   void* stream) {
-    if (!packed || !canonical) return BL_ERR_NULL;
     if (!shape_ok(N, K)) return BL_ERR_SHAPE;
+    if (!packed || !canonical) return BL_ERR_NULL;
     return check_hip(launch_to_canonical((const uint32_t*)packed, N, K, canonical,
                                          (hipStream_t)stream));
 }
@@ -114,13 +114,13 @@ int bitlinear_quant_act(const float* X, int64_t M, int64_t K, const float* ln_ga
                         const float* ln_bias, float ln_eps, int granularity, unsigned flags,
                         int8_t* codes, float* gamma, int32_t* rowsum, float* xhat_dump,
                         void* workspace, size_t workspace_bytes, void* stream) {
-    if (!X || !codes || !gamma) return BL_ERR_NULL;
     if (M < 0 || M > kMaxDim || K <= 0 || K > kMaxDim || K % 32) return BL_ERR_SHAPE;
     if (!gran_ok(granularity) || (flags & ~BL_FLAG_SKIP_LN)) return BL_ERR_UNSUPPORTED;
     if (!quant_supported(K)) return BL_ERR_UNSUPPORTED;
+    if (M == 0) return BL_OK;  // nothing to read or write: pointers may be NULL
+    if (!X || !codes || !gamma) return BL_ERR_NULL;
     const QuantWs ws = quant_ws(M, granularity);
     if (!workspace || workspace_bytes < ws.total) return BL_ERR_WORKSPACE;
-    if (M == 0) return BL_OK;
     QuantArgs a{};
     a.X = X; a.M = M; a.K = K; a.gain = ln_gain; a.bias = ln_bias; a.eps = ln_eps;
     a.skip_ln = (flags & BL_FLAG_SKIP_LN) != 0;
@@ -134,10 +134,10 @@ int bitlinear_quant_act(const float* X, int64_t M, int64_t K, const float* ln_ga
 int bitlinear_matmul(const int8_t* codes, const float* gamma, const int32_t* rowsum, int64_t M,
                      int64_t K, const void* packed, int64_t N, const float* beta, int granularity,
                      unsigned flags, float* Y, void* stream) {
-    if (!codes || !gamma || !rowsum || !packed || !beta || !Y) return BL_ERR_NULL;
     if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return BL_ERR_SHAPE;
     if (!gran_ok(granularity) || (flags & ~BL_FLAG_OUT_ACC_I32)) return BL_ERR_UNSUPPORTED;
     if (M == 0) return BL_OK;
+    if (!codes || !gamma || !rowsum || !packed || !beta || !Y) return BL_ERR_NULL;
     GemmArgs a{};
     a.codes = codes; a.gamma = gamma; a.rowsum = rowsum; a.M = M; a.K = K; a.N = N;
     a.packed = (const uint32_t*)packed; a.beta = beta;
@@ -152,13 +152,13 @@ int bitlinear_forward(const float* X, int64_t M, int64_t K, const void* packed, 
                       const float* beta, const float* ln_gain, const float* ln_bias, float ln_eps,
                       int granularity, unsigned flags, float* Y, void* workspace,
                       size_t workspace_bytes, void* stream) {
-    if (!X || !packed || !beta || !Y) return BL_ERR_NULL;
     if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return BL_ERR_SHAPE;
     if (!gran_ok(granularity) || (flags & ~(BL_FLAG_SKIP_LN | BL_FLAG_OUT_ACC_I32)))
         return BL_ERR_UNSUPPORTED;
+    if (M == 0) return BL_OK;
+    if (!X || !packed || !beta || !Y) return BL_ERR_NULL;
     const ForwardWs ws = forward_ws(M, K, granularity);
     if (!workspace || workspace_bytes < ws.total) return BL_ERR_WORKSPACE;
-    if (M == 0) return BL_OK;
     char* base = (char*)workspace;
     int8_t* codes = (int8_t*)(base + ws.codes);
     float* gamma = (float*)(base + ws.gamma);
@@ -176,10 +176,10 @@ int bitlinear_backward_ste(const float* dY, int64_t M, int64_t N, int64_t K, con
                            const float* beta, float* dX, float* dW, void* workspace,
                            size_t workspace_bytes, void* stream) {
     (void)workspace; (void)workspace_bytes; (void)stream;
-    if (!dY || !codes || !gamma || !beta) return BL_ERR_NULL;
-    if (dX && !packed) return BL_ERR_NULL;
     if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return BL_ERR_SHAPE;
     if (!gran_ok(granularity)) return BL_ERR_UNSUPPORTED;
+    if (!dY || !codes || !gamma || !beta) return BL_ERR_NULL;
+    if (dX && !packed) return BL_ERR_NULL;
     return BL_ERR_UNSUPPORTED;
 }
 
