@@ -3,30 +3,38 @@
 // of arXiv 2310.11453.  Compute-bound: the contraction runs on the i8 MFMA
 // (v_mfma_i32_32x32x32_i8, int32 accumulators).
 //
-// Tiling.  A workgroup computes a BM x BN block of Y.
+// Tiling.  A workgroup computes a BM x BN block of Y; a wave a WTM x WTN part of it.
 //  * Activation codes (int8) are streamed global -> LDS with the direct
 //    global_load_lds_dwordx4 path, no registers in between, through a ring of NS
-//    stages of BM rows x 64 k.  A stage is issued NS-1 stages ahead of its use,
-//    which hides the L2/HBM latency behind (NS-1) x 16 MFMAs per wave.  The 16-byte
-//    segments of a row are XOR-swizzled with (row/4)%4 so that the 16-byte operand
-//    reads of 16 consecutive rows hit every LDS bank exactly once.
+//    stages of BM rows x 64 k.  The 16-byte segments of a row are XOR-swizzled with
+//    (row/4)%4 so that the 16-byte operand reads of 16 consecutive rows hit every LDS
+//    bank exactly once.
 //  * The 1-bit weights of the block's BN columns for one 512-chunk (BN/16 packed tiles of
-//    1 KiB) take the same DMA path into a small LDS buffer, one chunk ahead.  At the start
-//    of a chunk each lane copies the 16-byte groups of its own columns to registers (16
-//    bytes cover 16 k in each of the eight 64-wide sub-blocks of the chunk) and expands
-//    them right before use, never as bytes in LDS:
+//    1 KiB) take the same DMA path into a small LDS buffer, one chunk ahead.  Once per
+//    chunk each lane copies the 16-byte groups of its own columns to registers (16 bytes
+//    cover 16 k in each of the eight 64-wide sub-blocks of the chunk) and expands them
+//    right before use, never as bytes in LDS:
 //        b = (w >> i) & 0x01010101           four {0,1} bytes, two VALU operations
 //    amortised over the WTM/32 MFMAs that reuse the operand.  The MFMA accumulates
 //    sum_k q b; the epilogue restores sum_k q s = 2 sum_k q b - sum_k q with the row sums
 //    of the codes that the quantiser already produced.
-//  * A 128 x 64 wave tile keeps LDS traffic (one 1 KiB operand read per two MFMAs)
-//    and expansion cost (24 VALU per 8 MFMAs) well below the MFMA time; two
-//    workgroups share a CU so one's epilogue overlaps the other's main loop.
+//  * A 128 x 64 wave tile keeps LDS traffic (one 1 KiB operand read per two MFMAs) and
+//    expansion cost (16 VALU per 8 MFMAs) well below the MFMA time.
+//  * Eight waves share a 256 x 256 (or 128 x 256) block, one block per CU.  The L2 -> LDS
+//    stream of codes is BM*K bytes per block, i.e. 2*BN operations per byte: with BN = 256
+//    the whole chip needs ~5 TB/s of it at half the MFMA peak, and with a latency of about
+//    2 us that is ~40 KiB in flight per CU, hence the deep ring (NS = 8 stages of 16 KiB).
 //
-// Synchronisation is explicit: s_waitcnt vmcnt(n) on the wave's own DMA, then a bare
-// s_barrier (no fence: a fence would drain every DMA in flight).  LDS reads of stage
-// st happen strictly between barrier(st) and barrier(st+1); the DMA that overwrites
-// the same buffer is issued after barrier(st+1).
+// Schedule.  The unit of work is a half-step: 32 k of a stage, MI*NI MFMAs.  One asm block
+// issues the LDS reads of the NEXT half-step's activation operand, then the MFMAs of the
+// current one, then waits for the reads: the LDS latency hides under the MFMAs and every
+// register the block defines is valid when it ends.  (An LDS read the compiler can see
+// makes it drain the whole DMA queue first, because it cannot tell the read from the DMA's
+// target; reads whose completion the compiler cannot see must not escape an asm block.)
+// Between the two half-steps of stage st every wave waits for its own DMA of stage st+1
+// (s_waitcnt vmcnt(n), n counted by hand) and meets the others at a bare s_barrier (no
+// fence: a fence would drain every DMA in flight).  After that barrier stage st+1 is
+// readable and the buffer of stage st-1 is free, so the DMA of stage st+NS-1 goes there.
 #include <type_traits>
 
 #include "common.h"
@@ -45,9 +53,6 @@ __device__ inline void static_for(F&& f) {
     }
 }
 
-// four {0,1} bytes: bit plane i of a packed dword
-__device__ inline int expand_01(uint32_t w, int i) { return (int)((w >> i) & 0x01010101u); }
-
 template <int N>
 __device__ inline void wait_vmcnt() {
     static_assert(N >= 0 && N < 64, "vmcnt range");
@@ -57,29 +62,31 @@ __device__ inline void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
-// LDS reads are written as asm.  The data is put there by DMA, and an LDS read the compiler
-// can see makes it drain the DMA queue (vmcnt(0)) first, which would undo the prefetch.  Each
-// asm block issues its reads AND waits for them (lgkmcnt(0)), so every output register is
-// valid when the block ends and the compiler is free to copy or move it.
-template <int O>
-__device__ inline void lds_read_x4(v4i (&a0)[4], uint32_t ad0) {
-    asm volatile(
-        "ds_read_b128 %0, %4 offset:%5\n\t"
-        "ds_read_b128 %1, %4 offset:%6\n\t"
-        "ds_read_b128 %2, %4 offset:%7\n\t"
-        "ds_read_b128 %3, %4 offset:%8\n\t"
-        "s_waitcnt lgkmcnt(0)"
-        : "=&v"(a0[0]), "=&v"(a0[1]), "=&v"(a0[2]), "=&v"(a0[3])
-        : "v"(ad0), "n"(O), "n"(O + 2048), "n"(O + 4096), "n"(O + 6144));
+__device__ inline void block_barrier() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
 }
-template <int O>
-__device__ inline void lds_read_x2(v4i (&a0)[2], uint32_t ad0) {
+
+// ---- asm blocks ----------------------------------------------------------------------
+// Operand reads of one half-step (sub-tile mi at +2048*mi), complete on exit.
+__device__ inline void lds_read_a(v4i (&a)[4], uint32_t ad) {
     asm volatile(
-        "ds_read_b128 %0, %2 offset:%3\n\t"
-        "ds_read_b128 %1, %2 offset:%4\n\t"
+        "ds_read_b128 %0, %4\n\t"
+        "ds_read_b128 %1, %4 offset:2048\n\t"
+        "ds_read_b128 %2, %4 offset:4096\n\t"
+        "ds_read_b128 %3, %4 offset:6144\n\t"
         "s_waitcnt lgkmcnt(0)"
-        : "=&v"(a0[0]), "=&v"(a0[1])
-        : "v"(ad0), "n"(O), "n"(O + 2048));
+        : "=&v"(a[0]), "=&v"(a[1]), "=&v"(a[2]), "=&v"(a[3])
+        : "v"(ad));
+}
+__device__ inline void lds_read_a(v4i (&a)[2], uint32_t ad) {
+    asm volatile(
+        "ds_read_b128 %0, %2\n\t"
+        "ds_read_b128 %1, %2 offset:2048\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(a[0]), "=&v"(a[1])
+        : "v"(ad));
 }
 // packed weight bits of a lane: [NI][h]; sub-tile s at +2048, half h at +512
 __device__ inline void lds_read_bits(v4i (&bw)[2][2], uint32_t ad) {
@@ -101,13 +108,80 @@ __device__ inline void lds_read_bits(v4i (&bw)[1][2], uint32_t ad) {
         : "v"(ad));
 }
 
-__device__ inline void block_barrier() {
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
+// Half-step, 4 x 2 sub-tiles: prefetch an[] from LDS address `ad`, acc[mi][s] += ac[mi] x b[s].
+// The four reads ahead of the first MFMA also separate it from whatever VALU instruction
+// the compiler placed last.
+__device__ inline void half_step(v16i (&acc)[4][2], const v4i (&ac)[4], const v4i (&b)[2],
+                                 v4i (&an)[4], uint32_t ad) {
+    asm volatile(
+        "ds_read_b128 %8, %18\n\t"
+        "ds_read_b128 %9, %18 offset:2048\n\t"
+        "ds_read_b128 %10, %18 offset:4096\n\t"
+        "ds_read_b128 %11, %18 offset:6144\n\t"
+        "v_mfma_i32_32x32x32_i8 %0, %12, %16, %0\n\t"
+        "v_mfma_i32_32x32x32_i8 %1, %12, %17, %1\n\t"
+        "v_mfma_i32_32x32x32_i8 %2, %13, %16, %2\n\t"
+        "v_mfma_i32_32x32x32_i8 %3, %13, %17, %3\n\t"
+        "v_mfma_i32_32x32x32_i8 %4, %14, %16, %4\n\t"
+        "v_mfma_i32_32x32x32_i8 %5, %14, %17, %5\n\t"
+        "v_mfma_i32_32x32x32_i8 %6, %15, %16, %6\n\t"
+        "v_mfma_i32_32x32x32_i8 %7, %15, %17, %7\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "+v"(acc[0][0]), "+v"(acc[0][1]), "+v"(acc[1][0]), "+v"(acc[1][1]), "+v"(acc[2][0]),
+          "+v"(acc[2][1]), "+v"(acc[3][0]), "+v"(acc[3][1]), "=&v"(an[0]), "=&v"(an[1]),
+          "=&v"(an[2]), "=&v"(an[3])
+        : "v"(ac[0]), "v"(ac[1]), "v"(ac[2]), "v"(ac[3]), "v"(b[0]), "v"(b[1]), "v"(ad));
+}
+// Timing experiments only: the MFMAs of a 4 x 2 half-step without the operand prefetch.
+__device__ inline void half_step_noread(v16i (&acc)[4][2], const v4i (&ac)[4], const v4i (&b)[2]) {
+    asm volatile(
+        "v_mfma_i32_32x32x32_i8 %0, %8, %12, %0\n\t"
+        "v_mfma_i32_32x32x32_i8 %1, %8, %13, %1\n\t"
+        "v_mfma_i32_32x32x32_i8 %2, %9, %12, %2\n\t"
+        "v_mfma_i32_32x32x32_i8 %3, %9, %13, %3\n\t"
+        "v_mfma_i32_32x32x32_i8 %4, %10, %12, %4\n\t"
+        "v_mfma_i32_32x32x32_i8 %5, %10, %13, %5\n\t"
+        "v_mfma_i32_32x32x32_i8 %6, %11, %12, %6\n\t"
+        "v_mfma_i32_32x32x32_i8 %7, %11, %13, %7"
+        : "+v"(acc[0][0]), "+v"(acc[0][1]), "+v"(acc[1][0]), "+v"(acc[1][1]), "+v"(acc[2][0]),
+          "+v"(acc[2][1]), "+v"(acc[3][0]), "+v"(acc[3][1])
+        : "v"(ac[0]), "v"(ac[1]), "v"(ac[2]), "v"(ac[3]), "v"(b[0]), "v"(b[1]));
+}
+template <class A, class B, class C>
+__device__ inline void half_step_noread(A&, const B&, const C&) {}
+
+// Half-step, 2 x 2 sub-tiles.
+__device__ inline void half_step(v16i (&acc)[2][2], const v4i (&ac)[2], const v4i (&b)[2],
+                                 v4i (&an)[2], uint32_t ad) {
+    asm volatile(
+        "ds_read_b128 %4, %10\n\t"
+        "ds_read_b128 %5, %10 offset:2048\n\t"
+        "s_nop 1\n\t"
+        "v_mfma_i32_32x32x32_i8 %0, %6, %8, %0\n\t"
+        "v_mfma_i32_32x32x32_i8 %1, %6, %9, %1\n\t"
+        "v_mfma_i32_32x32x32_i8 %2, %7, %8, %2\n\t"
+        "v_mfma_i32_32x32x32_i8 %3, %7, %9, %3\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "+v"(acc[0][0]), "+v"(acc[0][1]), "+v"(acc[1][0]), "+v"(acc[1][1]), "=&v"(an[0]),
+          "=&v"(an[1])
+        : "v"(ac[0]), "v"(ac[1]), "v"(b[0]), "v"(b[1]), "v"(ad));
+}
+// Half-step, 2 x 1 sub-tiles.
+__device__ inline void half_step(v16i (&acc)[2][1], const v4i (&ac)[2], const v4i (&b)[1],
+                                 v4i (&an)[2], uint32_t ad) {
+    asm volatile(
+        "ds_read_b128 %2, %7\n\t"
+        "ds_read_b128 %3, %7 offset:2048\n\t"
+        "s_nop 1\n\t"
+        "v_mfma_i32_32x32x32_i8 %0, %4, %6, %0\n\t"
+        "v_mfma_i32_32x32x32_i8 %1, %5, %6, %1\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "+v"(acc[0][0]), "+v"(acc[1][0]), "=&v"(an[0]), "=&v"(an[1])
+        : "v"(ac[0]), "v"(ac[1]), "v"(b[0]), "v"(ad));
 }
 
-template <int BM, int BN, int WM, int WN, int NS>
+// NS = stages in the LDS ring (4 or 8: it must divide the 8 stages of a chunk)
+template <int BM, int BN, int WM, int WN, int NS, int ABL = 0>
 __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs a, int grid_m,
                                                                         int grid_n) {
     constexpr int THREADS = WM * WN * kWave;
@@ -117,8 +191,10 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
     constexpr int NWAVES = WM * WN;
     constexpr int NBW = (BN / 16) / NWAVES;  // packed-weight tiles (DMA pieces) per wave per chunk
     constexpr int STAGE_BYTES = BM * kStageK;
-    static_assert(BM * 4 % THREADS == 0 && MI >= 1 && NI >= 1, "tile shape");
-    static_assert(NS == 4 || NS == 8, "ring size must divide the 8 stages of a chunk");
+    static_assert(BM * 4 % THREADS == 0, "tile shape");
+    static_assert((MI == 4 && NI == 2) || (MI == 2 && NI == 2) || (MI == 2 && NI == 1),
+                  "wave tiles with an asm block");
+    static_assert(NS == 4 || NS == 8, "ring size");
     static_assert((BN / 16) % NWAVES == 0 && (NS - 2) * P + NBW < 64, "tile shape");
 
     __shared__ __attribute__((aligned(1024))) uint8_t smA[NS * STAGE_BYTES];
@@ -140,10 +216,9 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
     const int nst = (int)((K + kStageK - 1) / kStageK);
 
     // ---- DMA of one stage: thread -> P pieces; piece = (row, swizzled 16-byte segment) ----
-    // Global address = uniform base (block row 0, stage k) + a 32-bit per-lane offset, so
-    // advancing a stage costs scalar arithmetic only.  Rows past M re-read row M-1 (never
-    // stored).  CLAMP: stages that may reach past K re-read the last 16 valid bytes of the row
-    // (the upper half of a half-filled last stage is never read).
+    // Global address = uniform base (block row 0, stage k) + a 32-bit per-lane offset.  Rows
+    // past M re-read row M-1 (never stored).  clamp: stages that may reach past K re-read the
+    // last 16 valid bytes of the row (nobody reads those buffer bytes).
     uint32_t goff[P];
     int gseg[P];
 #pragma unroll
@@ -156,7 +231,7 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
     }
     const int8_t* gbase = a.codes + m0 * K;
     const uint32_t lds_wave = (uint32_t)(w * kWave * 16);
-    auto issue = [&](int st, int buf, bool clamp) {
+    auto issue = [&](int st, bool clamp) {
 #pragma unroll
         for (int q = 0; q < P; ++q) {
             const int8_t* src = gbase + (int64_t)st * kStageK + goff[q];
@@ -166,7 +241,7 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
             }
             __builtin_amdgcn_global_load_lds(
                 (const void*)src,
-                (__attribute__((address_space(3))) void*)(smA + buf * STAGE_BYTES +
+                (__attribute__((address_space(3))) void*)(smA + (st % NS) * STAGE_BYTES +
                                                           q * THREADS * 16 + lds_wave),
                 16, 0, 0);
         }
@@ -183,6 +258,7 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
         bsrc[q] = a.packed + tile_dword_offset(tn, 0, TK) + l * 4;
     }
     auto issue_bits = [&](int64_t tk) {
+        if (tk > TK - 1) tk = TK - 1;
 #pragma unroll
         for (int q = 0; q < NBW; ++q)
             __builtin_amdgcn_global_load_lds(
@@ -192,8 +268,12 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
     // lane (j, g2) of sub-tile s, half h reads lane slot (2h+g2)*16 + j%16 of tile (..+j/16)
     const uint32_t b_lane = (uint32_t)(uintptr_t)smB + ((wn * WTN + j) >> 4) * 1024 +
                             (g2 * 16 + (j & 15)) * 16;
-    v4i bw[NI][2];
-    auto read_bits = [&]() { lds_read_bits(bw, b_lane); };
+    // lane's operand address inside a stage: row (wm*WTM + j), segment (2h+g2) ^ swizzle
+    const int sw = (j >> 2) & 3;
+    const uint32_t a_lane[2] = {
+        (uint32_t)(uintptr_t)smA + (wm * WTM + j) * kStageK + ((g2) ^ sw) * 16,
+        (uint32_t)(uintptr_t)smA + (wm * WTM + j) * kStageK + ((2 + g2) ^ sw) * 16};
+    auto a_addr = [&](int st, int h) { return a_lane[h] + (uint32_t)((st % NS) * STAGE_BYTES); };
 
     v16i acc[MI][NI];
 #pragma unroll
@@ -203,81 +283,73 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mi][s][r] = 0;
 
-    issue_bits(0);
-#pragma unroll
-    for (int s = 0; s < NS - 1; ++s) issue(s, s, true);
-
-    // lane's operand address inside a stage: row (wm*WTM + j), segment (2h+g2) ^ swizzle
-    const int sw = (j >> 2) & 3;
-    const uint32_t a_lane[2] = {
-        (uint32_t)(uintptr_t)smA + (wm * WTM + j) * kStageK + ((g2) ^ sw) * 16,
-        (uint32_t)(uintptr_t)smA + (wm * WTM + j) * kStageK + ((2 + g2) ^ sw) * 16};
-
-    // One stage of MFMAs: 2 k-steps of 32 (h = 0, 1); `i` selects the bit plane of the chunk.
-    // The weight operand holds {0,1}; the epilogue turns sum_k q b into sum_k q (2b - 1).
-    // BUFOFF is the stage's byte offset in the ring when known at compile time (main loop),
-    // else 0 with the offset folded into `dyn`.
-    auto mfma_half = [&](v4i (&av)[MI], int h, int i) {
-        v4i b[NI];
+    v4i bw[NI][2];  // packed bits of the current chunk
+    // bit plane i of half h as {0,1} bytes; the epilogue turns sum_k q b into sum_k q (2b - 1)
+    auto expand = [&](v4i (&b)[NI], int h, int i) {
 #pragma unroll
         for (int s = 0; s < NI; ++s)
 #pragma unroll
-            for (int d = 0; d < 4; ++d) b[s][d] = expand_01((uint32_t)bw[s][h][d], i);
-#pragma unroll
-        for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-            for (int s = 0; s < NI; ++s)
-                acc[mi][s] = __builtin_amdgcn_mfma_i32_32x32x32_i8(av[mi], b[s], acc[mi][s], 0, 0, 0);
+            for (int d = 0; d < 4; ++d) b[s][d] = (int)(((uint32_t)bw[s][h][d] >> i) & 0x01010101u);
     };
-    auto compute = [&](auto bufoff, uint32_t dyn, int i, bool half) {
-        constexpr int O = decltype(bufoff)::value;
-        static_assert(MI == 2 || MI == 4, "activation sub-tiles per wave");
-        // one half (4 or 2 operand reads) at a time keeps 16 registers live instead of 32
-        v4i av[MI];
-        if constexpr (MI == 4) lds_read_x4<O>(av, a_lane[0] + dyn);
-        else lds_read_x2<O>(av, a_lane[0] + dyn);
-        mfma_half(av, 0, i);
+
+    // ---- prologue: weight bits of chunk 0, stages 0..2 in flight, operands of half-step 0 --
+    issue_bits(0);
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s) issue(s, true);
+    wait_vmcnt<(NS - 2) * P>();  // younger than stage 0: stages 1 .. NS-2
+    block_barrier();
+    lds_read_bits(bw, b_lane);
+    v4i ax[MI], ay[MI], bx[NI], by[NI];
+    lds_read_a(ax, a_addr(0, 0));
+    expand(bx, 0, 0);
+
+    // Stage st, bit plane i = st % 8.  In: ax/bx = operands of (st, h=0).  Out: ax/bx =
+    // operands of (st+1, h=0).  DMA bookkeeping at the mid-stage point: the groups younger
+    // than stage st+1 are stages st+2 .. st+NS-2 ((NS-3)*P operations), plus the NBW weight
+    // tiles while they are among them: the tiles are issued at i == 2 ahead of stage
+    // st+NS-1's group, so they are younger than stage st+1 at i = 3 .. NS-1.  At i == 7 they
+    // are never allowed to be outstanding: smB is read right after that barrier.
+    auto stage = [&](int st, int i, bool clamp, bool half) {
+        if (!(ABL & 4)) expand(by, 1, i);
+        if (ABL & 1) half_step_noread(acc, ax, bx);
+        else half_step(acc, ax, bx, ay, a_addr(st, 1));
+        if (!(ABL & 8)) {
+            if (i >= 3 && i <= NS - 1 && i <= 6) wait_vmcnt<(NS - 3) * P + NBW>();
+            else wait_vmcnt<(NS - 3) * P>();
+            block_barrier();
+        }
+        if (i == 7) lds_read_bits(bw, b_lane);  // bits of the next chunk (landed long ago)
+        if (!(ABL & 2)) {
+            if (i == 2) issue_bits((st >> 3) + 1);
+            issue(st + NS - 1, clamp);
+        }
         if (!half) {
-            if constexpr (MI == 4) lds_read_x4<O>(av, a_lane[1] + dyn);
-            else lds_read_x2<O>(av, a_lane[1] + dyn);
-            mfma_half(av, 1, i);
+            if (!(ABL & 4)) expand(bx, 0, (i + 1) & 7);
+            if (ABL & 1) half_step_noread(acc, ay, by);
+            else half_step(acc, ay, by, ax, a_addr(st + 1, 0));
+        } else {
+            lds_read_a(ax, a_addr(st + 1, 0));
         }
     };
 
-    // Every stage issues the same DMA operations (P pieces of a stage NS-1 ahead, plus, at
-    // i == 2, the NBW weight tiles of the next chunk; past the end they re-read valid bytes
-    // into buffers nobody reads), so the number of operations younger than a given group is a
-    // compile-time constant: (NS-2)*P, plus NBW while the weight tiles are among them.  The
-    // tiles are older than group 8*tk+5, so they have landed for every wave after the barrier
-    // of stage 8*tk+5; smB is free again once every wave has passed the barrier of 8*tk+1.
-    //
-    // Main loop: chunks whose look-ahead stays inside K; no clamps, constant LDS offsets.
+    // Main loop: chunks whose look-ahead stays inside K (no clamps, constant folding of i).
     const int64_t kfull = K / kStageK;
     const int64_t main_chunks = kfull >= NS + 7 ? (kfull - NS - 7) / 8 + 1 : 0;
     for (int64_t tk = 0; tk < main_chunks; ++tk) {
         static_for<0, 8>([&](auto ic) {
             constexpr int i = decltype(ic)::value;
-            if constexpr (i == 3 || i == 4) wait_vmcnt<(NS - 2) * P + NBW>();
-            else wait_vmcnt<(NS - 2) * P>();
-            block_barrier();
-            if constexpr (i == 0) read_bits();
-            if constexpr (i == 2) issue_bits(tk + 1);
-            issue((int)tk * 8 + i + NS - 1, (i + NS - 1) % NS, false);
-            compute(std::integral_constant<int, (i % NS) * STAGE_BYTES>{}, 0u, i, false);
+            stage((int)tk * 8 + i, i, false, false);
         });
     }
     // Remaining stages (last chunk, ragged K): same schedule with clamped addresses.
-    for (int st = (int)main_chunks * 8; st < nst; ++st) {
-        const int i = st & 7;
-        if (i == 3 || i == 4) wait_vmcnt<(NS - 2) * P + NBW>();
-        else wait_vmcnt<(NS - 2) * P>();
-        block_barrier();
-        if (i == 0) read_bits();
-        if (i == 2) issue_bits((st >> 3) + 1 < TK ? (st >> 3) + 1 : (st >> 3));
-        issue(st + NS - 1, (st + NS - 1) % NS, true);
-        compute(std::integral_constant<int, 0>{}, (uint32_t)((st % NS) * STAGE_BYTES), i,
-                (int64_t)st * kStageK + 32 >= K);
-    }
+    for (int st = (int)main_chunks * 8; st < nst; ++st)
+        stage(st, st & 7, true, (int64_t)st * kStageK + 32 >= K);
+
+    // The accumulators were last written by MFMAs inside an asm block: give the matrix
+    // pipeline time to retire them before ordinary instructions read them.  Also drain the
+    // look-ahead DMA that ran past the end of K: it must not land after the LDS is released.
+    asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
+    wait_vmcnt<0>();
 
     // ---- epilogue (Eq. 11): lane (j, g2) holds column n and rows 8*(r/4) + 4*g2 + r%4 -----
     //   sum_k q s = 2 sum_k q b - sum_k q ;  y = that * (beta * gamma_m / 128)
@@ -296,24 +368,55 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
                 const int64_t n = n0 + wn * WTN + 32 * s + j;
                 if (n >= a.N) continue;
                 const int pm = 2 * acc[mi][s][r] - rs;
+                if ((ABL & 16) && pm != 0x12345678) continue;  // timing experiment: no stores
                 if (a.out_acc) reinterpret_cast<int*>(a.Y)[m * a.N + n] = pm;
                 else a.Y[m * a.N + n] = (float)pm * sc;
             }
         }
 }
 
-template <int BM, int BN, int WM, int WN, int NS>
+template <int BM, int BN, int WM, int WN, int NS, int ABL = 0>
 static void launch_tile(const GemmArgs& a, hipStream_t s) {
     const int grid_m = (int)((a.M + BM - 1) / BM), grid_n = (int)((a.N + BN - 1) / BN);
-    gemm_prefill_kernel<BM, BN, WM, WN, NS>
+    gemm_prefill_kernel<BM, BN, WM, WN, NS, ABL>
         <<<(unsigned)(grid_m * grid_n), WM * WN * kWave, 0, s>>>(a, grid_m, grid_n);
 }
 
 // K < 2^22 is required (the per-lane offset into a block of 256 rows is kept in 32 bits).
 hipError_t launch_gemm_prefill(const GemmArgs& a, hipStream_t s) {
     if (a.K >= ((int64_t)1 << 22)) return hipErrorInvalidValue;
-    if (a.M <= 64) launch_tile<64, 128, 1, 4, 4>(a, s);
-    else launch_tile<256, 128, 2, 2, 4>(a, s);
+    const char* e = getenv("BITLINEAR_PREFILL_TILE");  // bench-only override: 0, 1, 2
+    int pick;
+    if (e) pick = atoi(e);
+    else if (a.M <= 64) pick = 0;
+    else {
+        // 256x256 unless the 128-row tile needs fewer block-rounds of work on the 256 CUs
+        auto cost = [&](int64_t bm, int64_t bn) {
+            const int64_t blocks = ((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn);
+            return ((blocks + 255) / 256) * bm * bn;
+        };
+        pick = cost(128, 256) < cost(256, 256) ? 1 : 2;
+    }
+    if (const char* ab = getenv("BITLINEAR_PREFILL_ABLATE")) {  // timing experiments (wrong results)
+        switch (atoi(ab)) {
+            case 1: launch_tile<256, 256, 2, 4, 8, 1>(a, s); break;
+            case 2: launch_tile<256, 256, 2, 4, 8, 2>(a, s); break;
+            case 3: launch_tile<256, 256, 2, 4, 8, 3>(a, s); break;
+            case 4: launch_tile<256, 256, 2, 4, 8, 4>(a, s); break;
+            case 7: launch_tile<256, 256, 2, 4, 8, 7>(a, s); break;
+            case 8: launch_tile<256, 256, 2, 4, 8, 8>(a, s); break;
+            case 15: launch_tile<256, 256, 2, 4, 8, 15>(a, s); break;
+            case 16: launch_tile<256, 256, 2, 4, 8, 16>(a, s); break;
+            case 31: launch_tile<256, 256, 2, 4, 8, 31>(a, s); break;
+            case 116: launch_tile<128, 256, 2, 4, 8, 16>(a, s); break;
+            case 131: launch_tile<128, 256, 2, 4, 8, 30>(a, s); break;
+            default: launch_tile<256, 256, 2, 4, 8, 11>(a, s); break;
+        }
+        return hipGetLastError();
+    }
+    if (pick == 0) launch_tile<64, 128, 1, 4, 4>(a, s);
+    else if (pick == 1) launch_tile<128, 256, 2, 4, 8>(a, s);
+    else launch_tile<256, 256, 2, 4, 8>(a, s);
     return hipGetLastError();
 }
 
