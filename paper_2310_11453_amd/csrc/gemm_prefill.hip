@@ -180,7 +180,21 @@ __device__ inline void half_step(v16i (&acc)[2][1], const v4i (&ac)[2], const v4
         : "v"(ac[0]), "v"(ac[1]), "v"(b[0]), "v"(ad));
 }
 
-// NS = stages in the LDS ring (4 or 8: it must divide the 8 stages of a chunk)
+// Row scale and row sum of four consecutive rows (epilogue), complete on exit.
+__device__ inline void lds_read_rows(v4f& sc, v4i& rs, uint32_t ad_sc, uint32_t ad_rs) {
+    asm volatile(
+        "ds_read_b128 %0, %2\n\t"
+        "ds_read_b128 %1, %3\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(sc), "=&v"(rs)
+        : "v"(ad_sc), "v"(ad_rs));
+}
+__device__ inline void lds_write_b32(uint32_t ad, uint32_t v) {
+    asm volatile("ds_write_b32 %0, %1" : : "v"(ad), "v"(v) : "memory");
+}
+
+// NS = stages in the LDS ring (4 or 8: it must divide the 8 stages of a chunk).
+// Persistent: gridDim.x workgroups (one per CU) walk the tiles t = blockIdx.x, + gridDim.x, ...
 template <int BM, int BN, int WM, int WN, int NS, int ABL = 0>
 __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs a, int grid_m,
                                                                         int grid_n) {
@@ -199,14 +213,8 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
 
     __shared__ __attribute__((aligned(1024))) uint8_t smA[NS * STAGE_BYTES];
     __shared__ __attribute__((aligned(1024))) uint8_t smB[(BN / 16) * 1024];
-
-    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD one contiguous
-    // range of tiles (M fastest) so the tiles sharing an L2 share weight columns.
-    const int nb = grid_m * grid_n;
-    int pid = blockIdx.x;
-    if ((nb & 7) == 0) pid = (pid & 7) * (nb >> 3) + (pid >> 3);
-    const int bm = pid % grid_m, bn = pid / grid_m;
-    const int64_t m0 = (int64_t)bm * BM, n0 = (int64_t)bn * BN;
+    __shared__ __attribute__((aligned(16))) float smScale[2][BM];  // beta*gamma_m/128, per tile parity
+    __shared__ __attribute__((aligned(16))) int smRowsum[2][BM];   // sum_k q[m,k]
 
     const int w = threadIdx.x / kWave, l = threadIdx.x % kWave;
     const int wm = w / WN, wn = w % WN;
@@ -214,22 +222,52 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
     const int64_t TN = tiles_n(a.N), TK = tiles_k(a.K);
     const int64_t M = a.M, K = a.K;
     const int nst = (int)((K + kStageK - 1) / kStageK);
+    const int ntiles = grid_m * grid_n;
+
+    // Tile order.  Workgroups are dealt round-robin to the 8 XCDs, each with its own L2; give
+    // each XCD one contiguous range of tiles, N fastest, so that the tiles running together
+    // on an XCD read the same rows of codes (the large operand: 16 KiB per stage against 2 KiB
+    // of packed weights) and those rows come out of HBM once per XCD.
+    auto tile_origin = [&](int t, int64_t& m0, int64_t& n0) {
+        int logical = t;
+        const int G = (int)gridDim.x;
+        if ((ntiles & 7) == 0 && (G & 7) == 0) {
+            const int q = ((t % G) >> 3) + (t / G) * (G >> 3);  // index inside the XCD's range
+            logical = (t & 7) * (ntiles >> 3) + q;
+            // the XCD's range may end before the last round does
+            if (q >= (ntiles >> 3)) logical = -1;
+        }
+        m0 = logical < 0 ? -1 : (int64_t)(logical / grid_n) * BM;
+        n0 = logical < 0 ? -1 : (int64_t)(logical % grid_n) * BN;
+    };
 
     // ---- DMA of one stage: thread -> P pieces; piece = (row, swizzled 16-byte segment) ----
-    // Global address = uniform base (block row 0, stage k) + a 32-bit per-lane offset.  Rows
+    // Global address = uniform base (tile row 0, stage k) + a 32-bit per-lane offset.  Rows
     // past M re-read row M-1 (never stored).  clamp: stages that may reach past K re-read the
     // last 16 valid bytes of the row (nobody reads those buffer bytes).
     uint32_t goff[P];
     int gseg[P];
+    const int8_t* gbase = a.codes;
+    const uint32_t* bsrc[NBW];
+    auto setup_dma = [&](int64_t m0, int64_t n0) {
 #pragma unroll
-    for (int q = 0; q < P; ++q) {
-        const int slot = q * THREADS + threadIdx.x;
-        int row = slot >> 2;
-        gseg[q] = ((slot & 3) ^ ((row >> 2) & 3)) * 16;
-        if (m0 + row > M - 1) row = (int)(M - 1 - m0);
-        goff[q] = (uint32_t)row * (uint32_t)K + gseg[q];
-    }
-    const int8_t* gbase = a.codes + m0 * K;
+        for (int q = 0; q < P; ++q) {
+            const int slot = q * THREADS + threadIdx.x;
+            int row = slot >> 2;
+            gseg[q] = ((slot & 3) ^ ((row >> 2) & 3)) * 16;
+            if (m0 + row > M - 1) row = (int)(M - 1 - m0);
+            goff[q] = (uint32_t)row * (uint32_t)K + gseg[q];
+        }
+        gbase = a.codes + m0 * K;
+        // packed weights: tile t of the block goes to smB + t KiB, lane for lane as it lies in
+        // memory; wave w moves tiles w, w + NWAVES, ...  Columns past N read a valid tile.
+#pragma unroll
+        for (int q = 0; q < NBW; ++q) {
+            int64_t tn = (n0 >> 4) + w + q * NWAVES;
+            if (tn > TN - 1) tn = TN - 1;
+            bsrc[q] = a.packed + tile_dword_offset(tn, 0, TK) + l * 4;
+        }
+    };
     const uint32_t lds_wave = (uint32_t)(w * kWave * 16);
     auto issue = [&](int st, bool clamp) {
 #pragma unroll
@@ -246,25 +284,20 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
                 16, 0, 0);
         }
     };
-
-    // ---- packed weights: DMA of the block's BN/16 tiles for one 512-chunk -----------------
-    // Tile t of the block goes to smB + t KiB, lane for lane as it lies in memory; wave w
-    // moves tiles w, w + NWAVES, ...  Columns past N read a valid tile (never stored).
-    const uint32_t* bsrc[NBW];
-#pragma unroll
-    for (int q = 0; q < NBW; ++q) {
-        int64_t tn = (n0 >> 4) + w + q * NWAVES;
-        if (tn > TN - 1) tn = TN - 1;
-        bsrc[q] = a.packed + tile_dword_offset(tn, 0, TK) + l * 4;
-    }
     auto issue_bits = [&](int64_t tk) {
-        if (tk > TK - 1) tk = TK - 1;
 #pragma unroll
         for (int q = 0; q < NBW; ++q)
             __builtin_amdgcn_global_load_lds(
                 (const void*)(bsrc[q] + tk * 256),
                 (__attribute__((address_space(3))) void*)(smB + (w + q * NWAVES) * 1024), 16, 0, 0);
     };
+    // what a tile starts with: weight bits of chunk 0 and stages 0 .. NS-2 (clamped: K may be short)
+    auto issue_tile_start = [&]() {
+        issue_bits(0);
+#pragma unroll
+        for (int s = 0; s < NS - 1; ++s) issue(s, true);
+    };
+
     // lane (j, g2) of sub-tile s, half h reads lane slot (2h+g2)*16 + j%16 of tile (..+j/16)
     const uint32_t b_lane = (uint32_t)(uintptr_t)smB + ((wn * WTN + j) >> 4) * 1024 +
                             (g2 * 16 + (j & 15)) * 16;
@@ -276,13 +309,6 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
     auto a_addr = [&](int st, int h) { return a_lane[h] + (uint32_t)((st % NS) * STAGE_BYTES); };
 
     v16i acc[MI][NI];
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-        for (int s = 0; s < NI; ++s)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[mi][s][r] = 0;
-
     v4i bw[NI][2];  // packed bits of the current chunk
     // bit plane i of half h as {0,1} bytes; the epilogue turns sum_k q b into sum_k q (2b - 1)
     auto expand = [&](v4i (&b)[NI], int h, int i) {
@@ -291,95 +317,159 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
 #pragma unroll
             for (int d = 0; d < 4; ++d) b[s][d] = (int)(((uint32_t)bw[s][h][d] >> i) & 0x01010101u);
     };
-
-    // ---- prologue: weight bits of chunk 0, stages 0..2 in flight, operands of half-step 0 --
-    issue_bits(0);
-#pragma unroll
-    for (int s = 0; s < NS - 1; ++s) issue(s, true);
-    wait_vmcnt<(NS - 2) * P>();  // younger than stage 0: stages 1 .. NS-2
-    block_barrier();
-    lds_read_bits(bw, b_lane);
     v4i ax[MI], ay[MI], bx[NI], by[NI];
-    lds_read_a(ax, a_addr(0, 0));
-    expand(bx, 0, 0);
 
     // Stage st, bit plane i = st % 8.  In: ax/bx = operands of (st, h=0).  Out: ax/bx =
-    // operands of (st+1, h=0).  DMA bookkeeping at the mid-stage point: the groups younger
-    // than stage st+1 are stages st+2 .. st+NS-2 ((NS-3)*P operations), plus the NBW weight
-    // tiles while they are among them: the tiles are issued at i == 2 ahead of stage
-    // st+NS-1's group, so they are younger than stage st+1 at i = 3 .. NS-1.  At i == 7 they
-    // are never allowed to be outstanding: smB is read right after that barrier.
-    auto stage = [&](int st, int i, bool clamp, bool half) {
+    // operands of (st+1, h=0).  DMA bookkeeping at the mid-stage point, while the look-ahead
+    // stage st+NS-1 exists (`ahead`): the groups younger than stage st+1 are stages st+2 ..
+    // st+NS-2 ((NS-3)*P operations), plus the NBW weight tiles while they are among them: the
+    // tiles are issued at i == 2 ahead of stage st+NS-1's group, so they are younger than stage
+    // st+1 at i = 3 .. NS-1.  At i == 7 they are never allowed to be outstanding: smB is read
+    // right after that barrier.  Near the end of K nothing more is issued and the wait is for
+    // everything outstanding (all of it is needed within the next NS-2 stages).
+    auto stage = [&](int st, int i, bool clamp, bool half, bool ahead, bool bits_in_flight) {
         if (!(ABL & 4)) expand(by, 1, i);
         if (ABL & 1) half_step_noread(acc, ax, bx);
         else half_step(acc, ax, bx, ay, a_addr(st, 1));
         if (!(ABL & 8)) {
-            if (i >= 3 && i <= NS - 1 && i <= 6) wait_vmcnt<(NS - 3) * P + NBW>();
+            if (!ahead) wait_vmcnt<0>();
+            else if (bits_in_flight && i >= 3 && i <= NS - 1 && i <= 6) wait_vmcnt<(NS - 3) * P + NBW>();
             else wait_vmcnt<(NS - 3) * P>();
             block_barrier();
         }
         if (i == 7) lds_read_bits(bw, b_lane);  // bits of the next chunk (landed long ago)
         if (!(ABL & 2)) {
-            if (i == 2) issue_bits((st >> 3) + 1);
-            issue(st + NS - 1, clamp);
+            if (i == 2 && (st >> 3) + 1 < TK) issue_bits((st >> 3) + 1);
+            if (ahead) issue(st + NS - 1, clamp);
         }
         if (!half) {
             if (!(ABL & 4)) expand(bx, 0, (i + 1) & 7);
             if (ABL & 1) half_step_noread(acc, ay, by);
             else half_step(acc, ay, by, ax, a_addr(st + 1, 0));
-        } else {
-            lds_read_a(ax, a_addr(st + 1, 0));
         }
     };
 
-    // Main loop: chunks whose look-ahead stays inside K (no clamps, constant folding of i).
-    const int64_t kfull = K / kStageK;
-    const int64_t main_chunks = kfull >= NS + 7 ? (kfull - NS - 7) / 8 + 1 : 0;
-    for (int64_t tk = 0; tk < main_chunks; ++tk) {
-        static_for<0, 8>([&](auto ic) {
-            constexpr int i = decltype(ic)::value;
-            stage((int)tk * 8 + i, i, false, false);
-        });
-    }
-    // Remaining stages (last chunk, ragged K): same schedule with clamped addresses.
-    for (int st = (int)main_chunks * 8; st < nst; ++st)
-        stage(st, st & 7, true, (int64_t)st * kStageK + 32 >= K);
-
-    // The accumulators were last written by MFMAs inside an asm block: give the matrix
-    // pipeline time to retire them before ordinary instructions read them.  Also drain the
-    // look-ahead DMA that ran past the end of K: it must not land after the LDS is released.
-    asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
-    wait_vmcnt<0>();
-
-    // ---- epilogue (Eq. 11): lane (j, g2) holds column n and rows 8*(r/4) + 4*g2 + r%4 -----
-    //   sum_k q s = 2 sum_k q b - sum_k q ;  y = that * (beta * gamma_m / 128)
     const float beta = *a.beta;
-    const float g_all = a.per_tensor ? a.gamma[0] : 0.f;
-#pragma unroll
-    for (int mi = 0; mi < MI; ++mi)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int64_t m = m0 + wm * WTM + 32 * mi + 8 * (r >> 2) + 4 * g2 + (r & 3);
-            if (m >= M) continue;
-            const int rs = a.rowsum[m];
-            const float sc = (beta * (a.per_tensor ? g_all : a.gamma[m])) / 128.0f;
-#pragma unroll
-            for (int s = 0; s < NI; ++s) {
-                const int64_t n = n0 + wn * WTN + 32 * s + j;
-                if (n >= a.N) continue;
-                const int pm = 2 * acc[mi][s][r] - rs;
-                if ((ABL & 16) && pm != 0x12345678) continue;  // timing experiment: no stores
-                if (a.out_acc) reinterpret_cast<int*>(a.Y)[m * a.N + n] = pm;
-                else a.Y[m * a.N + n] = (float)pm * sc;
+    const int64_t kfull = K / kStageK;
+    // chunks whose look-ahead stays inside K and that have a successor chunk
+    const int64_t main_chunks = kfull >= NS + 7 ? (kfull - NS - 7) / 8 + 1 : 0;
+
+    int t = (int)blockIdx.x, parity = 0;
+    int64_t m0, n0;
+    tile_origin(t, m0, n0);
+    if (m0 < 0) return;  // uniform for the whole workgroup
+    setup_dma(m0, n0);
+    issue_tile_start();
+
+    while (true) {
+        // per-row dequantisation scale (Eq. 11) and row sum of the codes, for the epilogue
+        for (int r = threadIdx.x; r < BM; r += THREADS) {
+            const int64_t m = m0 + r;
+            float sc = 0.f;
+            int rs = 0;
+            if (m < M) {
+                sc = (beta * (a.per_tensor ? a.gamma[0] : a.gamma[m])) / 128.0f;
+                rs = a.rowsum[m];
             }
+            lds_write_b32((uint32_t)(uintptr_t)&smScale[parity][r], __float_as_uint(sc));
+            lds_write_b32((uint32_t)(uintptr_t)&smRowsum[parity][r], (uint32_t)rs);
         }
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int s = 0; s < NI; ++s)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[mi][s][r] = 0;
+
+        // stage 0 and the bits of chunk 0 have landed; operands of half-step 0
+        wait_vmcnt<(NS - 2) * P>();  // younger than stage 0: stages 1 .. NS-2
+        block_barrier();
+        lds_read_bits(bw, b_lane);
+        lds_read_a(ax, a_addr(0, 0));
+        expand(bx, 0, 0);
+
+        // Main loop: no clamps, i folds to a constant.  Then the remaining stages.
+        for (int64_t tk = 0; tk < main_chunks; ++tk) {
+            static_for<0, 8>([&](auto ic) {
+                constexpr int i = decltype(ic)::value;
+                stage((int)tk * 8 + i, i, false, false, true, true);
+            });
+        }
+        for (int st = (int)main_chunks * 8; st < nst; ++st)
+            stage(st, st & 7, true, (int64_t)st * kStageK + 32 >= K, st + NS - 1 < nst,
+                  (st >> 3) + 1 < TK);
+
+        // The accumulators were last written by MFMAs inside an asm block: give the matrix
+        // pipeline time to retire them before ordinary instructions read them.
+        asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
+
+        // Every wave is done with the LDS ring: start the next tile's stream, then store.
+        block_barrier();
+        const int t_next = t + (int)gridDim.x;
+        int64_t m0n = -1, n0n = -1;
+        if (t_next < ntiles) tile_origin(t_next, m0n, n0n);
+        if (m0n >= 0) {
+            setup_dma(m0n, n0n);
+            issue_tile_start();
+        }
+
+        // ---- epilogue (Eq. 11): lane (j, g2) holds column n, rows 8*(r/4) + 4*g2 + r%4 ----
+        //   sum_k q s = 2 sum_k q b - sum_k q ;  y = that * (beta * gamma_m / 128)
+        const uint32_t sc_base = (uint32_t)(uintptr_t)&smScale[parity][wm * WTM + 4 * g2];
+        const uint32_t rs_base = (uint32_t)(uintptr_t)&smRowsum[parity][wm * WTM + 4 * g2];
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                v4f sc4;
+                v4i rs4;
+                lds_read_rows(sc4, rs4, sc_base + (32 * mi + 8 * rq) * 4, rs_base + (32 * mi + 8 * rq) * 4);
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    const int r = rq * 4 + rr;
+                    const int64_t m = m0 + wm * WTM + 32 * mi + 8 * rq + 4 * g2 + rr;
+                    if (m >= M) continue;
+#pragma unroll
+                    for (int s = 0; s < NI; ++s) {
+                        const int64_t n = n0 + wn * WTN + 32 * s + j;
+                        if (n >= a.N) continue;
+                        const int pm = 2 * acc[mi][s][r] - rs4[rr];
+                        if ((ABL & 16) && pm != 0x12345678) continue;  // timing experiment: no stores
+                        if (a.out_acc) reinterpret_cast<int*>(a.Y)[m * a.N + n] = pm;
+                        else a.Y[m * a.N + n] = (float)pm * sc4[rr];
+                    }
+                }
+            }
+        if (m0n < 0) break;
+        t = t_next;
+        m0 = m0n;
+        n0 = n0n;
+        parity ^= 1;
+    }
+}
+
+static int num_cus() {
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+            n = prop.multiProcessorCount;
+        if (n <= 0) n = 256;
+    }
+    return n;
 }
 
 template <int BM, int BN, int WM, int WN, int NS, int ABL = 0>
 static void launch_tile(const GemmArgs& a, hipStream_t s) {
     const int grid_m = (int)((a.M + BM - 1) / BM), grid_n = (int)((a.N + BN - 1) / BN);
+    const int ntiles = grid_m * grid_n;
+    // one workgroup per CU for the 8-wave tiles; the small 4-wave tile fits four per CU
+    int grid = num_cus() * (WM * WN <= 4 ? 4 : 1);
+    if (const char* e = getenv("BITLINEAR_PREFILL_GRID")) grid = atoi(e);  // bench-only override
+    if (grid > ntiles) grid = ntiles;
     gemm_prefill_kernel<BM, BN, WM, WN, NS, ABL>
-        <<<(unsigned)(grid_m * grid_n), WM * WN * kWave, 0, s>>>(a, grid_m, grid_n);
+        <<<(unsigned)grid, WM * WN * kWave, 0, s>>>(a, grid_m, grid_n);
 }
 
 // K < 2^22 is required (the per-lane offset into a block of 256 rows is kept in 32 bits).
