@@ -30,9 +30,10 @@ import workloads as wl
 HBM_PEAK_GBS = 8000.0
 I8_MFMA_PEAK_TOPS = 5000.0
 
-# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE (see profiles/); None until measured for the current kernel.
-TRAFFIC_BYTES = {"gemm_prefill_up": None}
+# HBM bytes per launch of the dominant kernel (the 4096->16384 GEMM at M=2048) measured with
+# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the same counter reads for a
+# plain 256 MiB device copy (x2.000 and x1.000): profiles/gemm_prefill_6p7b_counters.txt.
+TRAFFIC_BYTES = {"gemm_prefill_up": int((41328 * 2.000 + 131072 * 1.000) * 1024)}
 
 
 def gemm_bytes(M, K, N):
@@ -58,6 +59,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode streaming leg")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run plain device copies of 256 MiB (reference for the rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)",
@@ -71,6 +75,14 @@ def main():
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs a GPU")
     dev = torch.device("cuda:0")
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_per_launch": src.numel(), "launches": 10}))
+        return
     cfg = wl.CONFIGS[2]
     M = cfg.Ms[0]
 
@@ -118,7 +130,7 @@ def main():
                             quant_gbs=5 * M * L.K / (t_q * 1e-3) / 1e9)
     up = layers[0]["L"]
     g_ms = kern[up.name]["gemm_ms"]
-    roof = dict(bound="mfma", kernel="gemm_prefill_kernel<256,128,2,2> (4096->16384, M=2048)",
+    roof = dict(bound="mfma", kernel="gemm_prefill_kernel<256,256,2,4,8> (4096->16384, M=2048)",
                 achieved=2 * M * up.N * up.K / (g_ms * 1e-3) / 1e12, peak=I8_MFMA_PEAK_TOPS,
                 unit="TOP/s", traffic=TRAFFIC_BYTES["gemm_prefill_up"], launch_ms=g_ms)
     roof["frac"] = roof["achieved"] / roof["peak"]

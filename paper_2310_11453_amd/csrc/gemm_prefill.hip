@@ -132,24 +132,6 @@ __device__ inline void half_step(v16i (&acc)[4][2], const v4i (&ac)[4], const v4
           "=&v"(an[2]), "=&v"(an[3])
         : "v"(ac[0]), "v"(ac[1]), "v"(ac[2]), "v"(ac[3]), "v"(b[0]), "v"(b[1]), "v"(ad));
 }
-// Timing experiments only: the MFMAs of a 4 x 2 half-step without the operand prefetch.
-__device__ inline void half_step_noread(v16i (&acc)[4][2], const v4i (&ac)[4], const v4i (&b)[2]) {
-    asm volatile(
-        "v_mfma_i32_32x32x32_i8 %0, %8, %12, %0\n\t"
-        "v_mfma_i32_32x32x32_i8 %1, %8, %13, %1\n\t"
-        "v_mfma_i32_32x32x32_i8 %2, %9, %12, %2\n\t"
-        "v_mfma_i32_32x32x32_i8 %3, %9, %13, %3\n\t"
-        "v_mfma_i32_32x32x32_i8 %4, %10, %12, %4\n\t"
-        "v_mfma_i32_32x32x32_i8 %5, %10, %13, %5\n\t"
-        "v_mfma_i32_32x32x32_i8 %6, %11, %12, %6\n\t"
-        "v_mfma_i32_32x32x32_i8 %7, %11, %13, %7"
-        : "+v"(acc[0][0]), "+v"(acc[0][1]), "+v"(acc[1][0]), "+v"(acc[1][1]), "+v"(acc[2][0]),
-          "+v"(acc[2][1]), "+v"(acc[3][0]), "+v"(acc[3][1])
-        : "v"(ac[0]), "v"(ac[1]), "v"(ac[2]), "v"(ac[3]), "v"(b[0]), "v"(b[1]));
-}
-template <class A, class B, class C>
-__device__ inline void half_step_noread(A&, const B&, const C&) {}
-
 // Half-step, 2 x 2 sub-tiles.
 __device__ inline void half_step(v16i (&acc)[2][2], const v4i (&ac)[2], const v4i (&b)[2],
                                  v4i (&an)[2], uint32_t ad) {
@@ -195,7 +177,7 @@ __device__ inline void lds_write_b32(uint32_t ad, uint32_t v) {
 
 // NS = stages in the LDS ring (4 or 8: it must divide the 8 stages of a chunk).
 // Persistent: gridDim.x workgroups (one per CU) walk the tiles t = blockIdx.x, + gridDim.x, ...
-template <int BM, int BN, int WM, int WN, int NS, int ABL = 0>
+template <int BM, int BN, int WM, int WN, int NS>
 __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs a, int grid_m,
                                                                         int grid_n) {
     constexpr int THREADS = WM * WN * kWave;
@@ -328,24 +310,18 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
     // right after that barrier.  Near the end of K nothing more is issued and the wait is for
     // everything outstanding (all of it is needed within the next NS-2 stages).
     auto stage = [&](int st, int i, bool clamp, bool half, bool ahead, bool bits_in_flight) {
-        if (!(ABL & 4)) expand(by, 1, i);
-        if (ABL & 1) half_step_noread(acc, ax, bx);
-        else half_step(acc, ax, bx, ay, a_addr(st, 1));
-        if (!(ABL & 8)) {
-            if (!ahead) wait_vmcnt<0>();
-            else if (bits_in_flight && i >= 3 && i <= NS - 1 && i <= 6) wait_vmcnt<(NS - 3) * P + NBW>();
-            else wait_vmcnt<(NS - 3) * P>();
-            block_barrier();
-        }
+        expand(by, 1, i);
+        half_step(acc, ax, bx, ay, a_addr(st, 1));
+        if (!ahead) wait_vmcnt<0>();
+        else if (bits_in_flight && i >= 3 && i <= NS - 1 && i <= 6) wait_vmcnt<(NS - 3) * P + NBW>();
+        else wait_vmcnt<(NS - 3) * P>();
+        block_barrier();
         if (i == 7) lds_read_bits(bw, b_lane);  // bits of the next chunk (landed long ago)
-        if (!(ABL & 2)) {
-            if (i == 2 && (st >> 3) + 1 < TK) issue_bits((st >> 3) + 1);
-            if (ahead) issue(st + NS - 1, clamp);
-        }
+        if (i == 2 && (st >> 3) + 1 < TK) issue_bits((st >> 3) + 1);
+        if (ahead) issue(st + NS - 1, clamp);
         if (!half) {
-            if (!(ABL & 4)) expand(bx, 0, (i + 1) & 7);
-            if (ABL & 1) half_step_noread(acc, ay, by);
-            else half_step(acc, ay, by, ax, a_addr(st + 1, 0));
+            expand(bx, 0, (i + 1) & 7);
+            half_step(acc, ay, by, ax, a_addr(st + 1, 0));
         }
     };
 
@@ -434,7 +410,6 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
                         const int64_t n = n0 + wn * WTN + 32 * s + j;
                         if (n >= a.N) continue;
                         const int pm = 2 * acc[mi][s][r] - rs4[rr];
-                        if ((ABL & 16) && pm != 0x12345678) continue;  // timing experiment: no stores
                         if (a.out_acc) reinterpret_cast<int*>(a.Y)[m * a.N + n] = pm;
                         else a.Y[m * a.N + n] = (float)pm * sc4[rr];
                     }
@@ -460,7 +435,7 @@ static int num_cus() {
     return n;
 }
 
-template <int BM, int BN, int WM, int WN, int NS, int ABL = 0>
+template <int BM, int BN, int WM, int WN, int NS>
 static void launch_tile(const GemmArgs& a, hipStream_t s) {
     const int grid_m = (int)((a.M + BM - 1) / BM), grid_n = (int)((a.N + BN - 1) / BN);
     const int ntiles = grid_m * grid_n;
@@ -468,7 +443,7 @@ static void launch_tile(const GemmArgs& a, hipStream_t s) {
     int grid = num_cus() * (WM * WN <= 4 ? 4 : 1);
     if (const char* e = getenv("BITLINEAR_PREFILL_GRID")) grid = atoi(e);  // bench-only override
     if (grid > ntiles) grid = ntiles;
-    gemm_prefill_kernel<BM, BN, WM, WN, NS, ABL>
+    gemm_prefill_kernel<BM, BN, WM, WN, NS>
         <<<(unsigned)grid, WM * WN * kWave, 0, s>>>(a, grid_m, grid_n);
 }
 
@@ -486,23 +461,6 @@ hipError_t launch_gemm_prefill(const GemmArgs& a, hipStream_t s) {
             return ((blocks + 255) / 256) * bm * bn;
         };
         pick = cost(128, 256) < cost(256, 256) ? 1 : 2;
-    }
-    if (const char* ab = getenv("BITLINEAR_PREFILL_ABLATE")) {  // timing experiments (wrong results)
-        switch (atoi(ab)) {
-            case 1: launch_tile<256, 256, 2, 4, 8, 1>(a, s); break;
-            case 2: launch_tile<256, 256, 2, 4, 8, 2>(a, s); break;
-            case 3: launch_tile<256, 256, 2, 4, 8, 3>(a, s); break;
-            case 4: launch_tile<256, 256, 2, 4, 8, 4>(a, s); break;
-            case 7: launch_tile<256, 256, 2, 4, 8, 7>(a, s); break;
-            case 8: launch_tile<256, 256, 2, 4, 8, 8>(a, s); break;
-            case 15: launch_tile<256, 256, 2, 4, 8, 15>(a, s); break;
-            case 16: launch_tile<256, 256, 2, 4, 8, 16>(a, s); break;
-            case 31: launch_tile<256, 256, 2, 4, 8, 31>(a, s); break;
-            case 116: launch_tile<128, 256, 2, 4, 8, 16>(a, s); break;
-            case 131: launch_tile<128, 256, 2, 4, 8, 30>(a, s); break;
-            default: launch_tile<256, 256, 2, 4, 8, 11>(a, s); break;
-        }
-        return hipGetLastError();
     }
     if (pick == 0) launch_tile<64, 128, 1, 4, 4>(a, s);
     else if (pick == 1) launch_tile<128, 256, 2, 4, 8>(a, s);
