@@ -55,10 +55,8 @@ enum {
     BL_FLAG_SKIP_LN = 1u,       /* input is already normalised: skip LN of Eq. 12 */
     BL_FLAG_OUT_ACC_I32 = 2u,   /* forward/matmul: write the int32 accumulator of Eq. 7
                                    into Y (reinterpreted as int32 [M,N]) instead of Eq. 11 */
-    BL_FLAG_BETA_CENTERED = 4u, /* pack: beta = mean|W - alpha| (prose above Eq. 1)
+    BL_FLAG_BETA_CENTERED = 4u  /* pack: beta = mean|W - alpha| (prose above Eq. 1)
                                    instead of the literal mean|W| of Eq. 12 */
-    BL_FLAG_PACK_TRANSPOSE = 8u /* pack: also store the bits with N as the fast axis,
-                                   which the dX contraction of the backward reads */
 };
 
 /* Operation selector for bitlinear_workspace_bytes. */
@@ -66,8 +64,7 @@ typedef enum { BL_OP_PACK = 0, BL_OP_QUANT = 1, BL_OP_FORWARD = 2, BL_OP_BACKWAR
 
 /* host: size in bytes of the packed-weight blob for an [N,K] matrix (0 on bad
  * shape).  The blob is the library's own tiled 1-bit layout (1 bit per weight,
- * N padded to 16 and K to 512); with BL_FLAG_PACK_TRANSPOSE it holds a second
- * copy tiled the other way. */
+ * N padded to 16 and K to 512). */
 size_t bitlinear_packed_bytes(int64_t N, int64_t K, unsigned flags);
 
 /* host: scratch bytes the given operation needs (never 0 for valid shapes). */
@@ -120,11 +117,14 @@ int bitlinear_forward(const float* X, int64_t M, int64_t K, const void* packed, 
 
 /* Section 2.2, straight-through estimator: Sign, Clip and rounding are treated
  * as identity, alpha/beta/gamma as constants.
- *   dY     in   fp32 [M,N], rounded to bf16 as the MFMA operand
- *   codes, gamma  in  as saved by the forward
- *   packed in   blob packed with BL_FLAG_PACK_TRANSPOSE (needed when dX != NULL)
+ *   dY     in   fp32 [M,N], rounded to bf16 (nearest even) as the MFMA operand
+ *   codes, gamma  in  as produced by bitlinear_quant_act in the forward
+ *   packed, beta  in  as produced by bitlinear_pack_weights (needed when dX != NULL)
  *   dX     out  fp32 [M,K] = beta * dY W~           (gradient w.r.t. LN(x)), or NULL
- *   dW     out  fp32 [N,K] = dY^T (codes * gamma/128), or NULL */
+ *   dW     out  fp32 [N,K] = dY^T (codes * gamma/128), or NULL; with a per-token gamma
+ *               the factor gamma_m/128 is folded into row m of dY before the bf16 rounding
+ * The workspace (bitlinear_workspace_bytes(BL_OP_BACKWARD, ...)) holds the bf16 operand
+ * copies: about 2*(2*M*N + K*N + K*M) bytes. */
 int bitlinear_backward_ste(const float* dY, int64_t M, int64_t N, int64_t K, const int8_t* codes,
                            const float* gamma, int granularity, const void* packed,
                            const float* beta, float* dX, float* dW, void* workspace,

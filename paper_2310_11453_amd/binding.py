@@ -16,7 +16,7 @@ LIB_PATH = _PKG / "libbitlinear.so"
 
 BL_OK = 0
 GAMMA_PER_TOKEN, GAMMA_PER_TENSOR = 0, 1
-FLAG_SKIP_LN, FLAG_OUT_ACC_I32, FLAG_BETA_CENTERED, FLAG_PACK_TRANSPOSE = 1, 2, 4, 8
+FLAG_SKIP_LN, FLAG_OUT_ACC_I32, FLAG_BETA_CENTERED = 1, 2, 4
 OP_PACK, OP_QUANT, OP_FORWARD, OP_BACKWARD = 0, 1, 2, 3
 
 EXPORTS = (

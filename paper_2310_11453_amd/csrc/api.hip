@@ -9,8 +9,7 @@ using namespace bl;
 namespace {
 
 constexpr int64_t kMaxDim = (int64_t)1 << 30;
-constexpr unsigned kKnownFlags = BL_FLAG_SKIP_LN | BL_FLAG_OUT_ACC_I32 | BL_FLAG_BETA_CENTERED |
-                                 BL_FLAG_PACK_TRANSPOSE;
+constexpr unsigned kKnownFlags = BL_FLAG_SKIP_LN | BL_FLAG_OUT_ACC_I32 | BL_FLAG_BETA_CENTERED;
 
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
@@ -62,9 +61,7 @@ extern "C" {
 
 size_t bitlinear_packed_bytes(int64_t N, int64_t K, unsigned flags) {
     if (!shape_ok(N, K) || (flags & ~kKnownFlags)) return 0;
-    size_t b = tiles_bytes(N, K);
-    if (flags & BL_FLAG_PACK_TRANSPOSE) b += tiles_bytes(K, N);
-    return b;
+    return tiles_bytes(N, K);
 }
 
 size_t bitlinear_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int granularity,
@@ -83,7 +80,7 @@ size_t bitlinear_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int gr
             return forward_ws(M, K, granularity).total;
         case BL_OP_BACKWARD:
             if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return 0;
-            return 256;
+            return backward_workspace_bytes(M, N, K) + 256;
         default:
             return 0;
     }
@@ -93,8 +90,7 @@ int bitlinear_pack_weights(const float* W, int64_t N, int64_t K, unsigned flags,
                            float* alpha, float* beta, void* workspace, size_t workspace_bytes,
                            void* stream) {
     if (!shape_ok(N, K)) return BL_ERR_SHAPE;
-    if (flags & ~(BL_FLAG_BETA_CENTERED | BL_FLAG_PACK_TRANSPOSE)) return BL_ERR_UNSUPPORTED;
-    if (flags & BL_FLAG_PACK_TRANSPOSE) return BL_ERR_UNSUPPORTED;
+    if (flags & ~BL_FLAG_BETA_CENTERED) return BL_ERR_UNSUPPORTED;
     if (!W || !packed || !alpha || !beta) return BL_ERR_NULL;
     const size_t need = bitlinear_workspace_bytes(BL_OP_PACK, 0, N, K, 0, flags);
     if (!workspace || workspace_bytes < need) return BL_ERR_WORKSPACE;
@@ -175,12 +171,20 @@ int bitlinear_backward_ste(const float* dY, int64_t M, int64_t N, int64_t K, con
                            const float* gamma, int granularity, const void* packed,
                            const float* beta, float* dX, float* dW, void* workspace,
                            size_t workspace_bytes, void* stream) {
-    (void)workspace; (void)workspace_bytes; (void)stream;
     if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return BL_ERR_SHAPE;
     if (!gran_ok(granularity)) return BL_ERR_UNSUPPORTED;
-    if (!dY || !codes || !gamma || !beta) return BL_ERR_NULL;
-    if (dX && !packed) return BL_ERR_NULL;
-    return BL_ERR_UNSUPPORTED;
+    if (M == 0 || (!dX && !dW)) return BL_OK;
+    if (!dY || !gamma) return BL_ERR_NULL;
+    if (dX && (!packed || !beta)) return BL_ERR_NULL;
+    if (dW && !codes) return BL_ERR_NULL;
+    const size_t need = bitlinear_workspace_bytes(BL_OP_BACKWARD, M, N, K, granularity, 0);
+    if (!workspace || workspace_bytes < need) return BL_ERR_WORKSPACE;
+    BackwardArgs a{};
+    a.dY = dY; a.M = M; a.N = N; a.K = K; a.codes = codes; a.gamma = gamma;
+    a.per_tensor = granularity == BL_GAMMA_PER_TENSOR;
+    a.packed = (const uint32_t*)packed; a.beta = beta; a.dX = dX; a.dW = dW;
+    a.workspace = (void*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255);
+    return check_hip(launch_backward(a, (hipStream_t)stream));
 }
 
 const char* bitlinear_status_string(int status) {

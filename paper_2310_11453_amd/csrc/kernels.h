@@ -46,4 +46,20 @@ struct GemmArgs {
 hipError_t launch_gemm_decode(const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm_prefill(const GemmArgs& a, hipStream_t s);
 
+// backward.hip
+struct BackwardArgs {
+    const float* dY;
+    int64_t M, N, K;
+    const int8_t* codes;
+    const float* gamma;
+    bool per_tensor;
+    const uint32_t* packed;
+    const float* beta;
+    float* dX;
+    float* dW;
+    void* workspace;
+};
+size_t backward_workspace_bytes(int64_t M, int64_t N, int64_t K);
+hipError_t launch_backward(const BackwardArgs& a, hipStream_t s);
+
 }  // namespace bl

@@ -39,10 +39,11 @@ def test_host_size_queries(lib):
     assert bl.packed_bytes(2048, 2048) == 2048 * 2048 // 8
     assert bl.packed_bytes(17, 544) == 32 * 1024 // 8
     assert bl.packed_bytes(16, 48) == 0 and bl.packed_bytes(0, 32) == 0
-    assert bl.packed_bytes(512, 512, bl.FLAG_PACK_TRANSPOSE) == 2 * 512 * 512 // 8
+    assert bl.packed_bytes(512, 512, 8) == 0  # unknown flag
     for op in (bl.OP_PACK, bl.OP_QUANT, bl.OP_FORWARD, bl.OP_BACKWARD):
         assert bl.workspace_bytes(op, 8, 512, 256) > 0
     assert bl.workspace_bytes(bl.OP_FORWARD, 8, 512, 256) >= 8 * 256
+    assert bl.workspace_bytes(bl.OP_BACKWARD, 64, 512, 256) >= 2 * (2 * 64 * 512 + 256 * 512 + 256 * 64)
     assert bl.workspace_bytes(99, 8, 512, 256) == 0
 
 
