@@ -12,7 +12,7 @@
 //   sum_k q s = 2 * sum_k q b - sum_k q,        s = 2 b - 1
 // with sum_k q taken from the quantiser's row sums.
 //
-// Work split: a workgroup owns T consecutive 16-row weight tiles and all of K;
+// Work split: a workgroup owns up to T consecutive 16-row weight tiles and all of K;
 // wave w of the group owns the K-chunks {w*C .. w*C+C-1} (+ W*C per round) and
 // keeps the matching slice of the activation codes in registers as MFMA
 // operands, reusing them for every tile.  Partial sums meet in LDS.
@@ -21,52 +21,95 @@
 
 namespace bl {
 
-template <int C, int T, int MAXT>
-__global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a) {
-    extern __shared__ int red[];  // [W][T][64][4]
+// C = K-chunks per wave and round, T = weight tiles per workgroup (compile-time bound; `tpb`
+// <= T of them are used), MAXT = launch bound.  ONE_ROUND: the waves of the group cover K in a
+// single round, so a tile's partial sum goes straight to LDS and no per-tile registers are
+// kept - this is what lets a wave keep eight 1 KiB weight loads in flight.
+template <int C, int T, int MAXT, bool ONE_ROUND>
+__global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) {
+    __shared__ __attribute__((aligned(16))) int red[(MAXT / kWave) * T * 256];  // [W][T][64][4]
     const int W = blockDim.x / kWave;
     const int w = threadIdx.x / kWave, l = threadIdx.x % kWave;
     const int m = l & 15, g = l >> 4;
     const int64_t TN = tiles_n(a.N), TK = tiles_k(a.K);
     const int M = (int)a.M;
+    const int64_t tn0 = (int64_t)blockIdx.x * tpb;
 
-    int part[T][4];
-#pragma unroll
-    for (int t = 0; t < T; ++t)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) part[t][r] = 0;
+    // epilogue operands, requested up front so their latency hides under the weight stream
+    const float beta = *a.beta;
+    const int mc = m < M ? m : M - 1;
+    const int rs = a.rowsum[mc];
+    const float gm = a.per_tensor ? a.gamma[0] : a.gamma[mc];
 
-    const int64_t rounds = (TK + (int64_t)W * C - 1) / ((int64_t)W * C);
+    int part[ONE_ROUND ? 1 : T][4];
+    if (!ONE_ROUND) {
+#pragma unroll
+        for (int t = 0; t < T; ++t)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) part[t][r] = 0;
+    }
+
+    const int64_t rounds = ONE_ROUND ? 1 : (TK + (int64_t)W * C - 1) / ((int64_t)W * C);
     for (int64_t rd = 0; rd < rounds; ++rd) {
         const int64_t tk0 = (rd * W + w) * C;
 
-        // activation operand: lane (m, g) holds codes[m][512*tk + 64*i + 16*g .. +15]
+        // Every load below is unconditional (addresses are clamped instead of guarded): with
+        // no branches around them the loads complete in issue order and the MFMAs of tile t
+        // wait for tile t only, not for the whole weight stream behind it.
+        //
+        // activation operand: lane (m, g) holds codes[m][512*tk + 64*i + 16*g .. +15].  Rows
+        // m >= M read row M-1 (their outputs are never stored); columns k >= K read the last 16
+        // valid bytes (the packed bits there are zero, so they contribute nothing).
+        const int8_t* arow = a.codes + (int64_t)(m < M ? m : M - 1) * a.K;
         v4i act[C][8];
 #pragma unroll
         for (int c = 0; c < C; ++c)
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-                const int64_t k = (tk0 + c) * kChunkK + 64 * i + 16 * g;
-                v4i z = {0, 0, 0, 0};
-                if (m < M && k < a.K) z = *reinterpret_cast<const v4i*>(a.codes + (int64_t)m * a.K + k);
-                act[c][i] = z;
+                int64_t k = (tk0 + c) * kChunkK + 64 * i + 16 * g;
+                if (k > a.K - 16) k = a.K - 16;
+                act[c][i] = *reinterpret_cast<const v4i*>(arow + k);
             }
 
-        // all weight tiles of this round are requested before the first MFMA
+        // Weight tiles: a software pipeline of depth kDepth per wave.  Asking for everything at
+        // once looks attractive for a 4-microsecond stream, but the memory system then returns
+        // the requests in no particular order, every wave gets its first tile late and all the
+        // MFMA work piles up behind the stream.  With three tiles in flight per wave (~42 KiB per
+        // CU, enough to cover the latency) tiles arrive in order and compute overlaps the stream.
+        // Tiles past the end re-read the last tile (never stored); chunks past the end are
+        // masked to zero arithmetically (no branch around a load).
+        constexpr int kDepth = T < 3 ? T : 3;
         v4i wt[T][C];
+        // chunk c of this wave: valid index and all-ones / all-zeros mask
+        int64_t tkc[C];
+        int livem[C];
 #pragma unroll
-        for (int t = 0; t < T; ++t)
+        for (int c = 0; c < C; ++c) {
+            livem[c] = -(int)(tk0 + c < TK);
+            tkc[c] = tk0 + c < TK ? tk0 + c : TK - 1;
+        }
+        // tile t of the group lies t*TK KiB after tile 0; tiles past the last valid one
+        // (ragged N, or tpb < T) re-read the last valid tile
+        const int t_last = (int)((tn0 + tpb - 1 < TN - 1 ? tn0 + tpb - 1 : TN - 1) - tn0);
+        const uint32_t* wbase[C];
+#pragma unroll
+        for (int c = 0; c < C; ++c) wbase[c] = a.packed + (tn0 * TK + tkc[c]) * 256 + l * 4;
+        const uint32_t tile_stride = (uint32_t)TK * 256;  // dwords; K < 2^22 keeps it in 32 bits
+        auto load_tile = [&](int t) {
+            const uint32_t off = (uint32_t)(t < t_last ? t : t_last) * tile_stride;
 #pragma unroll
             for (int c = 0; c < C; ++c) {
-                const int64_t tn = (int64_t)blockIdx.x * T + t, tk = tk0 + c;
-                v4i z = {0, 0, 0, 0};
-                if (tn < TN && tk < TK)
-                    z = *reinterpret_cast<const v4i*>(a.packed + tile_dword_offset(tn, tk, TK) + l * 4);
-                wt[t][c] = z;
+                const v4i z = *reinterpret_cast<const v4i*>(wbase[c] + off);
+                wt[t][c] = (C == 1 && ONE_ROUND) ? z : (z & livem[c]);
             }
+        };
+#pragma unroll
+        for (int t = 0; t < kDepth; ++t) load_tile(t);
 
 #pragma unroll
         for (int t = 0; t < T; ++t) {
+            if (t + kDepth < T) load_tile(t + kDepth);
+            __builtin_amdgcn_sched_barrier(0);  // keep the request ahead of this tile's MFMAs
             v4i acc[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) acc[i] = (v4i){0, 0, 0, 0};
@@ -79,44 +122,42 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a) {
                     // rows of the MFMA = weights (n), columns = tokens (m)
                     acc[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(plane, act[c][i], acc[i], 0, 0, 0);
                 }
-            // fold the planes: every acc[i] is an exact multiple of 2^i
+            // fold the planes, scaled by 128 so that one shift-add per plane does it:
+            //   128 * sum_k q b = sum_{i<7} acc_i * 2^(7-i) - acc_7      (|.| < 2^24 per chunk)
+            v4i sum;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                int h = acc[6][r];
+                int h = acc[0][r];
 #pragma unroll
-                for (int i = 5; i >= 0; --i) h = acc[i][r] + (h >> 1);
-                part[t][r] += h - (acc[7][r] >> 7);
+                for (int i = 1; i < 7; ++i) h = (h << 1) + acc[i][r];
+                sum[r] = (h << 1) - acc[7][r];
             }
+            if (ONE_ROUND) {
+                *reinterpret_cast<v4i*>(&red[((w * T + t) * kWave + l) * 4]) = sum;
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) part[t][r] += sum[r];
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 
     // cross-wave reduction over K, then the dequantisation epilogue
-    if (W > 1) {
+    if (!ONE_ROUND) {
 #pragma unroll
         for (int t = 0; t < T; ++t)
             *reinterpret_cast<v4i*>(&red[((w * T + t) * kWave + l) * 4]) =
                 (v4i){part[t][0], part[t][1], part[t][2], part[t][3]};
-        __syncthreads();
     }
-    const float beta = *a.beta;
-    for (int t = w; t < T; t += W) {
-        v4i sum;
-        if (W > 1) {
-            sum = (v4i){0, 0, 0, 0};
-            for (int ww = 0; ww < W; ++ww)
-                sum += *reinterpret_cast<const v4i*>(&red[((ww * T + t) * kWave + l) * 4]);
-        } else {
-            // W == 1: t == the only wave's own tile index; select without dynamic indexing
-            sum = (v4i){0, 0, 0, 0};
-#pragma unroll
-            for (int tt = 0; tt < T; ++tt)
-                if (tt == t) sum = (v4i){part[tt][0], part[tt][1], part[tt][2], part[tt][3]};
-        }
-        const int64_t tn = (int64_t)blockIdx.x * T + t;
+    __syncthreads();
+    for (int t = w; t < tpb; t += W) {
+        v4i sum = (v4i){0, 0, 0, 0};
+        for (int ww = 0; ww < W; ++ww)
+            sum += *reinterpret_cast<const v4i*>(&red[((ww * T + t) * kWave + l) * 4]);
+        const int64_t tn = tn0 + t;
         const int64_t n = tn * kTileN + 4 * g;
         if (tn >= TN || m >= M || n >= a.N) continue;
-        const int rs = a.rowsum[m];
-        const v4i pm = sum * 2 - rs;  // sum_k q s
+        const v4i pm = (sum >> 6) - rs;  // sum_k q s = 2 * (sum / 128) - sum_k q, exact shift
         float* y = a.Y + (int64_t)m * a.N + n;
         if (a.out_acc) {
             int* yi = reinterpret_cast<int*>(y);
@@ -125,7 +166,6 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a) {
                 for (int r = 0; r < 4; ++r)
                     if (n + r < a.N) yi[r] = pm[r];
         } else {
-            const float gm = a.per_tensor ? a.gamma[0] : a.gamma[m];
             const float sc = (beta * gm) / 128.0f;
             const v4f o = {(float)pm[0] * sc, (float)pm[1] * sc, (float)pm[2] * sc, (float)pm[3] * sc};
             if ((a.N & 3) == 0) *reinterpret_cast<v4f*>(y) = o;
@@ -141,35 +181,73 @@ static int env_int(const char* name, int dflt) {
     return e ? atoi(e) : dflt;
 }
 
-template <int C, int T, int MAXT>
-static void launch_one(const GemmArgs& a, int W, hipStream_t s) {
+static int num_cus() {
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+            n = prop.multiProcessorCount;
+        if (n <= 0) n = 256;
+    }
+    return n;
+}
+
+template <int C, int T, int MAXT, bool ONE_ROUND>
+static void launch_one(const GemmArgs& a, int W, int tpb, hipStream_t s) {
     const int64_t TN = tiles_n(a.N);
-    const unsigned grid = (unsigned)((TN + T - 1) / T);
-    const size_t lds = W > 1 ? (size_t)W * T * 1024 : 0;
-    gemm_decode_kernel<C, T, MAXT><<<grid, W * kWave, lds, s>>>(a);
+    const unsigned grid = (unsigned)((TN + tpb - 1) / tpb);
+    gemm_decode_kernel<C, T, MAXT, ONE_ROUND><<<grid, W * kWave, 0, s>>>(a, tpb);
+}
+
+// one round, up to 8 waves, exactly tpb = 1..8 tiles per group
+template <int C>
+static void launch_tiles(const GemmArgs& a, int W, int tpb, hipStream_t s) {
+    switch (tpb) {
+        case 1: launch_one<C, 1, 512, true>(a, W, 1, s); break;
+        case 2: launch_one<C, 2, 512, true>(a, W, 2, s); break;
+        case 3: launch_one<C, 3, 512, true>(a, W, 3, s); break;
+        case 4: launch_one<C, 4, 512, true>(a, W, 4, s); break;
+        case 5: launch_one<C, 5, 512, true>(a, W, 5, s); break;
+        case 6: launch_one<C, 6, 512, true>(a, W, 6, s); break;
+        case 7: launch_one<C, 7, 512, true>(a, W, 7, s); break;
+        default: launch_one<C, 8, 512, true>(a, W, 8, s); break;
+    }
 }
 
 hipError_t launch_gemm_decode(const GemmArgs& a, hipStream_t s) {
     const int64_t TN = tiles_n(a.N), TK = tiles_k(a.K);
-    // waves per group cover K: one chunk each (up to 16 waves) while K <= 8192, two chunks
-    // each (up to 8 waves, which leaves 256 registers per lane) beyond; longer K loops
-    const int C = TK <= 16 ? 1 : 2;
-    const int maxW = C == 1 ? 16 : 8;
-    const int64_t slots = (TK + C - 1) / C;
-    const int64_t rounds = (slots + maxW - 1) / maxW;
-    const int W = (int)((slots + rounds - 1) / rounds);
-    // tiles per group: few when the matrix is small (parallelism first), more when
-    // 16 tokens make the activation operand as heavy as the weights
-    int T = TN >= 1024 ? (a.M > 4 ? 4 : 2) : 1;
-    T = env_int("BITLINEAR_DECODE_T", T);
-    if (C == 1) {
-        if (T == 1) launch_one<1, 1, 1024>(a, W, s);
-        else if (T == 2) launch_one<1, 2, 1024>(a, W, s);
-        else launch_one<1, 4, 1024>(a, W, s);
+    // The whole matrix is a few microseconds of HBM time, so the kernel is built to have every
+    // byte requested at once: one round of workgroups (about one per CU), each wave asking for
+    // all of its weight tiles before the first MFMA.
+    auto tiles_per_group = [&](int cap) {
+        int tpb = (int)((TN + num_cus() - 1) / num_cus());
+        tpb = tpb > cap ? cap : tpb < 1 ? 1 : tpb;
+        return env_int("BITLINEAR_DECODE_T", tpb);
+    };
+    if (TK < 8) {
+        // K < 4096: one K-chunk per wave, W = TK waves cover K in one round
+        const int W = (int)TK;
+        const int tpb = tiles_per_group(8);
+        launch_tiles<1>(a, W, tpb, s);
+    } else if (TK <= 16) {
+        // 4096 <= K <= 8192: two chunks per wave (the fold of the bit planes, once per tile and
+        // wave, is then shared by two chunks), W = ceil(TK/2) <= 8 waves, one round
+        const int W = (int)((TK + 1) / 2);
+        const int tpb = tiles_per_group(8);
+        launch_tiles<2>(a, W, tpb, s);
+    } else if (TK <= 32) {
+        // K <= 16384: up to 16 waves of two chunks, one round; 128 registers per lane
+        const int W = (int)((TK + 1) / 2);
+        const int tpb = tiles_per_group(2);
+        if (tpb <= 1) launch_one<2, 1, 1024, true>(a, W, 1, s);
+        else launch_one<2, 2, 1024, true>(a, W, 2, s);
     } else {
-        if (T == 1) launch_one<2, 1, 512>(a, W, s);
-        else if (T == 2) launch_one<2, 2, 512>(a, W, s);
-        else launch_one<2, 4, 512>(a, W, s);
+        // longer K: two chunks per wave and round, up to 16 waves, several rounds
+        const int64_t slots = (TK + 1) / 2;
+        const int64_t rounds = (slots + 15) / 16;
+        const int W = (int)((slots + rounds - 1) / rounds);
+        launch_one<2, 1, 1024, false>(a, W, 1, s);
     }
     return hipGetLastError();
 }
