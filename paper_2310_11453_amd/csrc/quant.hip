@@ -1,14 +1,16 @@
 // Fused LayerNorm + absmax + round/clip activation quantiser
 // (arXiv 2310.11453, Eq. 12 for LN, Eq. 4-5 for the 8-bit absmax quantiser).
 //
-// One workgroup owns one token.  The row is read from HBM once and stays in
-// registers through the three reductions (mean, variance, max) and the
+// One to eight waves own one token.  The row is read from HBM once and stays in
+// registers through the reductions (sum with min/max, then variance) and the
 // rounding pass, so the kernel moves 4 bytes in and 1 byte out per element.
 // Mean, variance and the normalisation itself are evaluated in fp64 (the
 // kernel is bandwidth-bound, the extra ALU work is free) so that the fp32
 // value handed to the rounding step is the correctly rounded normalised
 // input; the steps that decide a code are single fp32 operations:
 //   scale = 128 / gamma,  t = x^ * scale,  code = clamp(rne(t), -128, 127).
+#include <stdlib.h>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -16,27 +18,111 @@ namespace bl {
 
 enum QuantMode { kFull = 0, kStats = 1, kApply = 2 };
 
+// ---- wave reductions on the DPP path (no LDS traffic) ---------------------------------
+// Butterfly inside each row of 16 lanes (xor 1, xor 2, mirror inside 8, mirror inside 16),
+// then the four row totals are read back as scalars and combined in a fixed order, so every
+// lane ends with the same bits and the result does not depend on the run.
+template <int CTRL>
+__device__ inline int dpp_mov(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, false);
+}
+template <int CTRL>
+__device__ inline float dpp_mov(float v) {
+    return __int_as_float(dpp_mov<CTRL>(__float_as_int(v)));
+}
+template <int CTRL>
+__device__ inline double dpp_mov(double v) {
+    return __hiloint2double(dpp_mov<CTRL>(__double2hiint(v)), dpp_mov<CTRL>(__double2loint(v)));
+}
+__device__ inline int lane_value(int v, int lane) { return __builtin_amdgcn_readlane(v, lane); }
+__device__ inline float lane_value(float v, int lane) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+__device__ inline double lane_value(double v, int lane) {
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), lane),
+                            __builtin_amdgcn_readlane(__double2loint(v), lane));
+}
+struct OpSum {
+    template <class T> __device__ T operator()(T a, T b) const { return a + b; }
+};
+struct OpMax {
+    __device__ float operator()(float a, float b) const { return fmaxf(a, b); }
+};
+struct OpMin {
+    __device__ float operator()(float a, float b) const { return fminf(a, b); }
+};
+template <class T, class Op>
+__device__ inline T wave_reduce(T v, Op op) {
+    v = op(v, dpp_mov<0xB1>(v));   // quad_perm [1,0,3,2]
+    v = op(v, dpp_mov<0x4E>(v));   // quad_perm [2,3,0,1]
+    v = op(v, dpp_mov<0x141>(v));  // row_half_mirror
+    v = op(v, dpp_mov<0x140>(v));  // row_mirror
+    return op(op(lane_value(v, 0), lane_value(v, 16)), op(lane_value(v, 32), lane_value(v, 48)));
+}
+
+// Reduction over the WPR waves that share a row: wave totals meet in LDS.  Every wave of the
+// workgroup takes part (rows past M are computed on a clamped row and never stored).  Each
+// slot array serves one reduction per kernel, so no barrier is needed ahead of the write.
+template <int WPR, class T, class Op>
+__device__ inline T row_reduce(T v, Op op, T* slots /* [rows per workgroup][WPR] */, int rw, int wr) {
+    v = wave_reduce(v, op);
+    if constexpr (WPR == 1) return v;
+    if ((threadIdx.x & (kWave - 1)) == 0) slots[rw * WPR + wr] = v;
+    __syncthreads();
+    T r = slots[rw * WPR];
+#pragma unroll
+    for (int i = 1; i < WPR; ++i) r = op(r, slots[rw * WPR + i]);
+    return r;
+}
+
+// WPR waves share one token (row); a lane holds NV float4 of it.  Workgroups have at least
+// four waves, so short rows are handled four (or two) to a workgroup, one per wave, with no
+// barrier at all.
 // kFull : per-token gamma, everything in one pass.
 // kStats: per-tensor, pass 1: row mean/rstd to rowstats, running max to gmax_bits.
 // kApply: per-tensor, pass 2: re-read the row, normalise with the saved stats,
 //         quantise with the tensor-wide gamma.
-template <int THREADS, int NV, int MODE>
-__global__ __launch_bounds__(THREADS) void ln_quant_rows(QuantArgs a) {
-    constexpr int NW = THREADS / kWave;
-    __shared__ double smd[NW > 1 ? NW : 1];
-    __shared__ float smf[NW > 1 ? NW : 1];
-    __shared__ int smi[NW > 1 ? NW : 1];
+template <int WPR, int NV, int MODE>
+__global__ __launch_bounds__((WPR < 4 ? 4 : WPR) * kWave, 4) void ln_quant_rows(QuantArgs a) {
+    constexpr int NW = WPR < 4 ? 4 : WPR;  // waves per workgroup
+    constexpr int RPW = NW / WPR;          // rows per workgroup
+    constexpr int RT = WPR * kWave;        // lanes per row
+    __shared__ double smd[2][NW];
+    __shared__ float smf[3][NW];
+    __shared__ int smi[NW];
 
-    const int64_t row = blockIdx.x;
+    const int wave = threadIdx.x / kWave;
+    const int rw = wave / WPR, wr = wave % WPR;
+    const int t = wr * kWave + (threadIdx.x & (kWave - 1));
+    int64_t row = (int64_t)blockIdx.x * RPW + rw;
+    const bool live = row < a.M;
+    if constexpr (WPR == 1) {
+        if (!live) return;  // no barriers on this path
+    } else {
+        if (!live) row = a.M - 1;
+    }
     const int K4 = (int)(a.K / 4);
     const float4* __restrict__ x4 = reinterpret_cast<const float4*>(a.X + row * a.K);
 
+    // The loads are unconditional (clamped index, value masked afterwards) so that all of
+    // them are in flight before the first is needed.
     float4 v[NV];
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
-        const int idx = threadIdx.x + j * THREADS;
-        v[j] = idx < K4 ? x4[idx] : make_float4(0.f, 0.f, 0.f, 0.f);
+        const int idx = t + j * RT;
+        v[j] = x4[idx < K4 ? idx : K4 - 1];
     }
+    // Each pass over the row converts its elements to fp64 again: `forget` hides the values
+    // from the optimiser between passes, or it would keep all the converted copies alive
+    // (two registers per element) and the kernel would run at minimal occupancy.
+    auto forget = [&]() {
+#pragma unroll
+        for (int j = 0; j < NV; ++j)
+            asm volatile("" : "+v"(v[j].x), "+v"(v[j].y), "+v"(v[j].z), "+v"(v[j].w));
+    };
+    const bool affine = a.gain != nullptr || a.bias != nullptr;
+    bool have_amax = false;
+    float amax = 0.f;
 
     if (!a.skip_ln) {
         double mu, rstd;
@@ -44,57 +130,101 @@ __global__ __launch_bounds__(THREADS) void ln_quant_rows(QuantArgs a) {
             mu = a.rowstats[2 * row];
             rstd = a.rowstats[2 * row + 1];
         } else {
-            double s = 0.0;
-#pragma unroll
-            for (int j = 0; j < NV; ++j)
-                s += ((double)v[j].x + (double)v[j].y) + ((double)v[j].z + (double)v[j].w);
-            mu = block_sum<NW>(s, smd) / (double)a.K;
-            double q = 0.0;
+            // One pass for the mean and the variance: sums of x and of (x - c)^2 in fp64, with
+            // c an element of the row, so that var = E[(x-c)^2] - (mu-c)^2 loses no digits to
+            // a large common offset.  Minimum and maximum ride along for the absmax.
+            const double c = (double)a.X[row * a.K];
+            double s = 0.0, q = 0.0;
+            float mn = v[0].x, mx = v[0].x;  // always an element of the row (clamped index)
 #pragma unroll
             for (int j = 0; j < NV; ++j) {
-                if (threadIdx.x + j * THREADS < K4) {
-                    const double dx = (double)v[j].x - mu, dy = (double)v[j].y - mu;
-                    const double dz = (double)v[j].z - mu, dw = (double)v[j].w - mu;
-                    q += (dx * dx + dy * dy) + (dz * dz + dw * dw);
+                if (t + j * RT < K4) {
+                    const double dx = (double)v[j].x, dy = (double)v[j].y;
+                    const double dz = (double)v[j].z, dw = (double)v[j].w;
+                    s += (dx + dy) + (dz + dw);
+                    q = fma(dx - c, dx - c, q);
+                    q = fma(dy - c, dy - c, q);
+                    q = fma(dz - c, dz - c, q);
+                    q = fma(dw - c, dw - c, q);
+                    mn = fminf(fminf(mn, v[j].x), fminf(fminf(v[j].y, v[j].z), v[j].w));
+                    mx = fmaxf(fmaxf(mx, v[j].x), fmaxf(fmaxf(v[j].y, v[j].z), v[j].w));
                 }
             }
-            const double var = block_sum<NW>(q, smd) / (double)a.K;
+            // one barrier for the four values
+            s = wave_reduce(s, OpSum{});
+            q = wave_reduce(q, OpSum{});
+            mn = wave_reduce(mn, OpMin{});
+            mx = wave_reduce(mx, OpMax{});
+            if constexpr (WPR > 1) {
+                if ((threadIdx.x & (kWave - 1)) == 0) {
+                    smd[0][wave] = s;
+                    smd[1][wave] = q;
+                    smf[0][wave] = mn;
+                    smf[1][wave] = mx;
+                }
+                __syncthreads();
+                s = smd[0][rw * WPR];
+                q = smd[1][rw * WPR];
+                mn = smf[0][rw * WPR];
+                mx = smf[1][rw * WPR];
+#pragma unroll
+                for (int i = 1; i < WPR; ++i) {
+                    s += smd[0][rw * WPR + i];
+                    q += smd[1][rw * WPR + i];
+                    mn = fminf(mn, smf[0][rw * WPR + i]);
+                    mx = fmaxf(mx, smf[1][rw * WPR + i]);
+                }
+            }
+            mu = s / (double)a.K;
+            const double qs = q;
+            const double var = fmax(qs / (double)a.K - (mu - c) * (mu - c), 0.0);
             rstd = 1.0 / sqrt(var + (double)a.eps);
             if constexpr (MODE == kStats) {
-                if (threadIdx.x == 0) {
+                if (t == 0 && live) {
                     a.rowstats[2 * row] = mu;
                     a.rowstats[2 * row + 1] = rstd;
                 }
             }
+            if (!affine) {
+                // x -> fl32((x - mu) * rstd) is monotone, so the largest magnitude of the
+                // normalised row is reached at the row's minimum or maximum.
+                const float lo = (float)(((double)mn - mu) * rstd);
+                const float hi = (float)(((double)mx - mu) * rstd);
+                amax = fmaxf(fabsf(lo), fabsf(hi));
+                have_amax = true;
+            }
         }
+        if (MODE != kStats || affine) {
+            forget();
 #pragma unroll
-        for (int j = 0; j < NV; ++j) {
-            const int idx = threadIdx.x + j * THREADS;
-            float4 o;
-            o.x = (float)(((double)v[j].x - mu) * rstd);
-            o.y = (float)(((double)v[j].y - mu) * rstd);
-            o.z = (float)(((double)v[j].z - mu) * rstd);
-            o.w = (float)(((double)v[j].w - mu) * rstd);
-            if (idx < K4) {
-                if (a.gain) {
-                    const float4 g = reinterpret_cast<const float4*>(a.gain)[idx];
-                    o.x = o.x * g.x; o.y = o.y * g.y; o.z = o.z * g.z; o.w = o.w * g.w;
+            for (int j = 0; j < NV; ++j) {
+                const int idx = t + j * RT;
+                float4 o;
+                o.x = (float)(((double)v[j].x - mu) * rstd);
+                o.y = (float)(((double)v[j].y - mu) * rstd);
+                o.z = (float)(((double)v[j].z - mu) * rstd);
+                o.w = (float)(((double)v[j].w - mu) * rstd);
+                if (idx < K4) {
+                    if (a.gain) {
+                        const float4 g = reinterpret_cast<const float4*>(a.gain)[idx];
+                        o.x = o.x * g.x; o.y = o.y * g.y; o.z = o.z * g.z; o.w = o.w * g.w;
+                    }
+                    if (a.bias) {
+                        const float4 b = reinterpret_cast<const float4*>(a.bias)[idx];
+                        o.x = o.x + b.x; o.y = o.y + b.y; o.z = o.z + b.z; o.w = o.w + b.w;
+                    }
+                    v[j] = o;
                 }
-                if (a.bias) {
-                    const float4 b = reinterpret_cast<const float4*>(a.bias)[idx];
-                    o.x = o.x + b.x; o.y = o.y + b.y; o.z = o.z + b.z; o.w = o.w + b.w;
-                }
-                v[j] = o;
             }
         }
     }
 
     if constexpr (MODE != kStats) {
-        if (a.xhat_dump) {
+        if (a.xhat_dump && live) {
             float4* __restrict__ d4 = reinterpret_cast<float4*>(a.xhat_dump + row * a.K);
 #pragma unroll
             for (int j = 0; j < NV; ++j) {
-                const int idx = threadIdx.x + j * THREADS;
+                const int idx = t + j * RT;
                 if (idx < K4) d4[idx] = v[j];
             }
         }
@@ -104,16 +234,19 @@ __global__ __launch_bounds__(THREADS) void ln_quant_rows(QuantArgs a) {
     if constexpr (MODE == kApply) {
         gamma = fmaxf(__uint_as_float(*a.gmax_bits), 1e-5f);
     } else {
-        float amax = 0.f;
+        if (!have_amax) {  // uniform: no LayerNorm, or a gain/bias after it
+            float m = 0.f;
 #pragma unroll
-        for (int j = 0; j < NV; ++j) {  // padding lanes hold 0 and cannot raise the max
-            amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v[j].x), fabsf(v[j].y)),
-                                     fmaxf(fabsf(v[j].z), fabsf(v[j].w))));
+            for (int j = 0; j < NV; ++j) {
+                if (t + j * RT < K4)
+                    m = fmaxf(m, fmaxf(fmaxf(fabsf(v[j].x), fabsf(v[j].y)),
+                                       fmaxf(fabsf(v[j].z), fabsf(v[j].w))));
+            }
+            amax = row_reduce<WPR>(m, OpMax{}, smf[2], rw, wr);
         }
-        amax = block_max<NW>(amax, smf);
         if constexpr (MODE == kStats) {
             // non-negative floats order like their bit patterns: integer max is exact
-            if (threadIdx.x == 0) atomicMax(a.gmax_bits, __float_as_uint(amax));
+            if (t == 0 && live) atomicMax(a.gmax_bits, __float_as_uint(amax));
             return;
         }
         gamma = fmaxf(amax, 1e-5f);
@@ -122,24 +255,34 @@ __global__ __launch_bounds__(THREADS) void ln_quant_rows(QuantArgs a) {
     const float scale = 128.0f / gamma;
     int rs = 0;
     uint32_t* __restrict__ c4 = reinterpret_cast<uint32_t*>(a.codes + row * a.K);
+    // code = clamp(rne(x^ * scale), -128, 127), one fp32 operation per step.  The integral
+    // float plus 128 lies in 0..255 and goes straight into its byte of the output word;
+    // flipping the top bit of each byte turns that offset form into two's complement.
+    auto code_word = [&](const float4& x) {
+        const float q0 = fminf(fmaxf(rintf(x.x * scale), -128.f), 127.f) + 128.f;
+        const float q1 = fminf(fmaxf(rintf(x.y * scale), -128.f), 127.f) + 128.f;
+        const float q2 = fminf(fmaxf(rintf(x.z * scale), -128.f), 127.f) + 128.f;
+        const float q3 = fminf(fmaxf(rintf(x.w * scale), -128.f), 127.f) + 128.f;
+        uint32_t wd = __builtin_amdgcn_cvt_pk_u8_f32(q0, 0, 0u);
+        wd = __builtin_amdgcn_cvt_pk_u8_f32(q1, 1, wd);
+        wd = __builtin_amdgcn_cvt_pk_u8_f32(q2, 2, wd);
+        wd = __builtin_amdgcn_cvt_pk_u8_f32(q3, 3, wd);
+        return wd ^ 0x80808080u;
+    };
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
-        const int idx = threadIdx.x + j * THREADS;
-        const int q0 = (int)fminf(fmaxf(rintf(v[j].x * scale), -128.f), 127.f);
-        const int q1 = (int)fminf(fmaxf(rintf(v[j].y * scale), -128.f), 127.f);
-        const int q2 = (int)fminf(fmaxf(rintf(v[j].z * scale), -128.f), 127.f);
-        const int q3 = (int)fminf(fmaxf(rintf(v[j].w * scale), -128.f), 127.f);
+        const int idx = t + j * RT;
+        const uint32_t wd = code_word(v[j]);
         if (idx < K4) {
-            rs += (q0 + q1) + (q2 + q3);
-            c4[idx] = (uint32_t)(q0 & 0xff) | ((uint32_t)(q1 & 0xff) << 8) |
-                      ((uint32_t)(q2 & 0xff) << 16) | ((uint32_t)(q3 & 0xff) << 24);
+            rs = __builtin_amdgcn_sdot4((int)wd, 0x01010101, rs, false);  // sum of the four codes
+            if (live) c4[idx] = wd;
         }
     }
     if (a.rowsum) {
-        rs = block_sum<NW>(rs, smi);
-        if (threadIdx.x == 0) a.rowsum[row] = rs;
+        rs = row_reduce<WPR>(rs, OpSum{}, smi, rw, wr);
+        if (t == 0 && live) a.rowsum[row] = rs;
     }
-    if (threadIdx.x == 0) {
+    if (t == 0 && live) {
         if (MODE == kFull) a.gamma[row] = gamma;
         else if (row == 0) a.gamma[0] = gamma;
     }
@@ -147,31 +290,47 @@ __global__ __launch_bounds__(THREADS) void ln_quant_rows(QuantArgs a) {
 
 __global__ void fill_u32(uint32_t* p, uint32_t v) { *p = v; }
 
-// rows of up to 32768 elements stay in registers (8 float4 per lane, up to 1024 lanes)
-bool quant_supported(int64_t K) { return K % 4 == 0 && K / 4 <= 1024 * 8; }
+// rows of up to 32768 elements stay in registers (16 float4 per lane, up to 8 waves)
+bool quant_supported(int64_t K) { return K % 4 == 0 && K / 4 <= 8 * kWave * 16; }
 
-template <int THREADS, int NV>
+template <int WPR, int NV>
 static void launch_mode(const QuantArgs& a, hipStream_t s) {
-    const unsigned grid = (unsigned)a.M;
+    constexpr int NW = WPR < 4 ? 4 : WPR, RPW = NW / WPR;
+    const unsigned grid = (unsigned)((a.M + RPW - 1) / RPW);
     if (!a.per_tensor) {
-        ln_quant_rows<THREADS, NV, kFull><<<grid, THREADS, 0, s>>>(a);
+        ln_quant_rows<WPR, NV, kFull><<<grid, NW * kWave, 0, s>>>(a);
     } else {
         fill_u32<<<1, 1, 0, s>>>(a.gmax_bits, 0u);
-        ln_quant_rows<THREADS, NV, kStats><<<grid, THREADS, 0, s>>>(a);
-        ln_quant_rows<THREADS, NV, kApply><<<grid, THREADS, 0, s>>>(a);
+        ln_quant_rows<WPR, NV, kStats><<<grid, NW * kWave, 0, s>>>(a);
+        ln_quant_rows<WPR, NV, kApply><<<grid, NW * kWave, 0, s>>>(a);
     }
 }
 
+// Waves per row: enough of them that the chip holds about sixteen waves per CU (short rows
+// of a small batch are split over several waves rather than leaving most SIMDs idle), and
+// never more than 16 float4 per lane.
 hipError_t launch_quant(const QuantArgs& a, hipStream_t s) {
     const int64_t K4 = a.K / 4;
-    if (K4 <= 64) launch_mode<64, 1>(a, s);
-    else if (K4 <= 128) launch_mode<64, 2>(a, s);
-    else if (K4 <= 256) launch_mode<64, 4>(a, s);
-    else if (K4 <= 512) launch_mode<256, 2>(a, s);
-    else if (K4 <= 1024) launch_mode<256, 4>(a, s);
-    else if (K4 <= 2048) launch_mode<256, 8>(a, s);
-    else if (K4 <= 4096) launch_mode<512, 8>(a, s);
-    else launch_mode<1024, 8>(a, s);
+    int wpr = 1;
+    while (wpr < 8 && K4 > (int64_t)wpr * kWave * 16) wpr *= 2;             // capacity
+    while (wpr < 8 && a.M * wpr < 4096 && K4 >= (int64_t)wpr * 2 * kWave * 4) wpr *= 2;  // occupancy
+    if (const char* e = getenv("BITLINEAR_QUANT_WPR")) {  // bench-only override
+        const int v = atoi(e);
+        if ((v == 1 || v == 2 || v == 4 || v == 8) && K4 <= (int64_t)v * kWave * 16) wpr = v;
+    }
+    const int64_t per_lane = (K4 + wpr * kWave - 1) / (wpr * kWave);
+    int nv = 1;
+    while (nv < per_lane) nv *= 2;
+    if (wpr == 2 && nv < 4) nv = 4;
+    if (wpr == 4 && nv < 4) nv = 4;
+    if (wpr == 8 && nv < 8) nv = 8;
+#define BL_QUANT_CASE(W, V) if (wpr == W && nv == V) launch_mode<W, V>(a, s); else
+    BL_QUANT_CASE(1, 1) BL_QUANT_CASE(1, 2) BL_QUANT_CASE(1, 4) BL_QUANT_CASE(1, 8) BL_QUANT_CASE(1, 16)
+    BL_QUANT_CASE(2, 4) BL_QUANT_CASE(2, 8) BL_QUANT_CASE(2, 16)
+    BL_QUANT_CASE(4, 4) BL_QUANT_CASE(4, 8) BL_QUANT_CASE(4, 16)
+    BL_QUANT_CASE(8, 8) BL_QUANT_CASE(8, 16)
+    return hipErrorInvalidValue;
+#undef BL_QUANT_CASE
     return hipGetLastError();
 }
 
