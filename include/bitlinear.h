@@ -115,6 +115,49 @@ int bitlinear_forward(const float* X, int64_t M, int64_t K, const void* packed, 
                       int granularity, unsigned flags, float* Y, void* workspace,
                       size_t workspace_bytes, void* stream);
 
+/* ---- Group Quantization and Normalization (Eq. 13-15) -------------------------------
+ * The paper splits weights and activations into G groups "along the partition dimension"
+ * and estimates alpha, beta, gamma and the LayerNorm statistics per group, so that a
+ * tensor-parallel shard needs no exchange.  Its symbols leave the axis open; both are here:
+ *   groups_n  groups of N/groups_n output rows of W (column-parallel): alpha_g, beta_g per
+ *             group, activations untouched;
+ *   groups_k  groups of K/groups_k input columns (row-parallel): alpha_g, beta_g per slice
+ *             of W, LayerNorm over each slice of a token (Eq. 15), gamma_g per slice (Eq. 14),
+ *             and Y = sum_g acc_g * beta_g * gamma_g / 128 (each slice dequantised, then added
+ *             in fp32 in the order g = 0, 1, ...).
+ * Both at once give groups_n x groups_k blocks of W.  groups_n = groups_k = 1 is the plain
+ * layer, bit for bit.  Requirements: groups in 1..64, N % groups_n == 0,
+ * (N/groups_n) % 16 == 0 when groups_n > 1 (else BL_ERR_UNSUPPORTED), K % groups_k == 0,
+ * (K/groups_k) % 32 == 0 (else BL_ERR_SHAPE).
+ *   alpha, beta   fp32 [groups_n][groups_k]
+ *   packed        groups_k consecutive blobs, blob g = the [N, K/groups_k] slice in the tile
+ *                 layout; bitlinear_packed_bytes_grouped bytes
+ *   gamma         fp32 [M][groups_k] (per token) or [groups_k] (per tensor)
+ *   rowsum        int32 [M][groups_k]
+ *   ln_gain/bias  fp32 [K] or NULL, applied per element after the group statistics
+ * Everything else as in the functions above. */
+size_t bitlinear_packed_bytes_grouped(int64_t N, int64_t K, int groups_n, int groups_k);
+/* op = BL_OP_PACK, BL_OP_QUANT or BL_OP_FORWARD; 0 for anything invalid */
+size_t bitlinear_workspace_bytes_grouped(int op, int64_t M, int64_t N, int64_t K, int groups_n,
+                                         int groups_k, int granularity);
+int bitlinear_pack_weights_grouped(const float* W, int64_t N, int64_t K, int groups_n,
+                                   int groups_k, unsigned flags, void* packed, float* alpha,
+                                   float* beta, void* workspace, size_t workspace_bytes,
+                                   void* stream);
+/* canonical uint32 [N, K/32] as in bitlinear_packed_to_canonical */
+int bitlinear_packed_to_canonical_grouped(const void* packed, int64_t N, int64_t K, int groups_k,
+                                          uint32_t* canonical, void* stream);
+int bitlinear_quant_act_grouped(const float* X, int64_t M, int64_t K, int groups_k,
+                                const float* ln_gain, const float* ln_bias, float ln_eps,
+                                int granularity, unsigned flags, int8_t* codes, float* gamma,
+                                int32_t* rowsum, float* xhat_dump, void* workspace,
+                                size_t workspace_bytes, void* stream);
+/* flags: BL_FLAG_SKIP_LN only */
+int bitlinear_forward_grouped(const float* X, int64_t M, int64_t K, const void* packed, int64_t N,
+                              int groups_n, int groups_k, const float* beta, const float* ln_gain,
+                              const float* ln_bias, float ln_eps, int granularity, unsigned flags,
+                              float* Y, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Section 2.2, straight-through estimator: Sign, Clip and rounding are treated
  * as identity, alpha/beta/gamma as constants.
  *   dY     in   fp32 [M,N], rounded to bf16 (nearest even) as the MFMA operand

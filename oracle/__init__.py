@@ -221,3 +221,66 @@ def forward(X, W, eps=1e-5, per_tensor=False, skip_ln=False, beta_centered=False
     y = dequant(acc, gamma, beta, per_tensor)
     return dict(alpha=alpha, beta=beta, sign=sign, words=words, xhat=xhat, gamma=gamma,
                 codes=codes, acc=acc, y=y)
+
+
+# ---- Eq. 13-15: Group Quantization and Normalization -----------------------------------
+def weight_stats_grouped(W, groups_n: int = 1, groups_k: int = 1, beta_centered: bool = False):
+    """Eq. 13: alpha_g, beta_g of each of the groups_n x groups_k blocks of W (rows split in
+    groups_n equal parts, columns in groups_k).  Returns (alpha, beta), each [groups_n, groups_k]."""
+    W = _f32(W)
+    N, K = W.shape
+    assert N % groups_n == 0 and K % groups_k == 0
+    Ng, Kg = N // groups_n, K // groups_k
+    alpha = np.empty((groups_n, groups_k), np.float32)
+    beta = np.empty((groups_n, groups_k), np.float32)
+    for gn in range(groups_n):
+        for gk in range(groups_k):
+            blk = np.ascontiguousarray(W[gn * Ng:(gn + 1) * Ng, gk * Kg:(gk + 1) * Kg])
+            alpha[gn, gk], beta[gn, gk] = weight_stats(blk, beta_centered)
+    return alpha, beta
+
+
+def binarize_grouped(W, alpha):
+    """Eq. 1-2 with the alpha of the block that holds each weight; sign int8 [N,K]."""
+    W = _f32(W)
+    N, K = W.shape
+    groups_n, groups_k = alpha.shape
+    Ng, Kg = N // groups_n, K // groups_k
+    sign = np.empty((N, K), np.int8)
+    for gn in range(groups_n):
+        for gk in range(groups_k):
+            blk = np.ascontiguousarray(W[gn * Ng:(gn + 1) * Ng, gk * Kg:(gk + 1) * Kg])
+            sign[gn * Ng:(gn + 1) * Ng, gk * Kg:(gk + 1) * Kg] = binarize(blk, float(alpha[gn, gk]))
+    return sign
+
+
+def forward_grouped(X, W, groups_n: int = 1, groups_k: int = 1, eps=1e-5, per_tensor=False,
+                    skip_ln=False, beta_centered=False, gain=None, bias=None):
+    """BitLinear forward with the group parameters of Eq. 13-15.  The weights are split into
+    groups_n row groups and groups_k column groups (alpha, beta per block); the activations into
+    groups_k slices of each token (group LayerNorm, Eq. 15; gamma per slice, Eq. 14).  Each
+    K-slice is contracted on its own and dequantised with its own beta_g * gamma_g / 128
+    (fp32 product as in Eq. 11); the slices are added in fp64."""
+    X = _f32(X)
+    W = _f32(W)
+    M, K = X.shape
+    N = W.shape[0]
+    Ng, Kg = N // groups_n, K // groups_k
+    alpha, beta = weight_stats_grouped(W, groups_n, groups_k, beta_centered)
+    sign = binarize_grouped(W, alpha)
+    xhat = X if skip_ln else layernorm(X, eps, gain, bias, groups=groups_k)
+    gamma = absmax(xhat, per_tensor, groups=groups_k)       # [M*groups_k] or [groups_k]
+    codes = quantize(xhat, gamma, per_tensor, groups=groups_k)
+    gam = gamma.reshape(-1, groups_k)                       # [M, groups_k] or [1, groups_k]
+    ysum = np.zeros((M, N), np.float64)
+    accs = []
+    for gk in range(groups_k):
+        acc = matmul_i32(codes, sign, gk * Kg, (gk + 1) * Kg)
+        accs.append(acc)
+        g_col = np.ascontiguousarray(gam[:, gk])
+        part = dequant(acc, g_col, np.ascontiguousarray(beta[:, gk]), per_tensor,
+                       beta_rows_per_group=Ng)
+        ysum += part.astype(np.float64)
+    return dict(alpha=alpha, beta=beta, sign=sign, words=pack_canonical(sign), xhat=xhat,
+                gamma=gam if not per_tensor else gam.reshape(groups_k), codes=codes, acc=accs,
+                y=ysum.astype(np.float32), y64=ysum)

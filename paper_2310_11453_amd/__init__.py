@@ -7,4 +7,6 @@ from .binding import (  # noqa: F401
     bitlinear_backward_ste, bitlinear_forward, bitlinear_matmul, bitlinear_pack_weights,
     bitlinear_packed_to_canonical, bitlinear_quant_act, load_library, packed_bytes,
     status_string, workspace_bytes,
+    bitlinear_forward_grouped, bitlinear_pack_weights_grouped, bitlinear_packed_to_canonical_grouped,
+    bitlinear_quant_act_grouped, packed_bytes_grouped, workspace_bytes_grouped,
 )

@@ -23,6 +23,9 @@ EXPORTS = (
     "bitlinear_packed_bytes", "bitlinear_workspace_bytes", "bitlinear_pack_weights",
     "bitlinear_packed_to_canonical", "bitlinear_quant_act", "bitlinear_matmul",
     "bitlinear_forward", "bitlinear_backward_ste", "bitlinear_status_string",
+    "bitlinear_packed_bytes_grouped", "bitlinear_workspace_bytes_grouped",
+    "bitlinear_pack_weights_grouped", "bitlinear_packed_to_canonical_grouped",
+    "bitlinear_quant_act_grouped", "bitlinear_forward_grouped",
 )
 
 _lib = None
@@ -58,6 +61,20 @@ def load_library() -> ctypes.CDLL:
     lib.bitlinear_forward.argtypes = [vp, i64, i64, vp, i64, vp, vp, vp, cf, ci, u32, vp, vp, sz, vp]
     lib.bitlinear_backward_ste.restype = ci
     lib.bitlinear_backward_ste.argtypes = [vp, i64, i64, i64, vp, vp, ci, vp, vp, vp, vp, vp, sz, vp]
+    lib.bitlinear_packed_bytes_grouped.restype = sz
+    lib.bitlinear_packed_bytes_grouped.argtypes = [i64, i64, ci, ci]
+    lib.bitlinear_workspace_bytes_grouped.restype = sz
+    lib.bitlinear_workspace_bytes_grouped.argtypes = [ci, i64, i64, i64, ci, ci, ci]
+    lib.bitlinear_pack_weights_grouped.restype = ci
+    lib.bitlinear_pack_weights_grouped.argtypes = [vp, i64, i64, ci, ci, u32, vp, vp, vp, vp, sz, vp]
+    lib.bitlinear_packed_to_canonical_grouped.restype = ci
+    lib.bitlinear_packed_to_canonical_grouped.argtypes = [vp, i64, i64, ci, vp, vp]
+    lib.bitlinear_quant_act_grouped.restype = ci
+    lib.bitlinear_quant_act_grouped.argtypes = [vp, i64, i64, ci, vp, vp, cf, ci, u32, vp, vp, vp, vp,
+                                                vp, sz, vp]
+    lib.bitlinear_forward_grouped.restype = ci
+    lib.bitlinear_forward_grouped.argtypes = [vp, i64, i64, vp, i64, ci, ci, vp, vp, vp, cf, ci, u32,
+                                              vp, vp, sz, vp]
     lib.bitlinear_status_string.restype = ctypes.c_char_p
     lib.bitlinear_status_string.argtypes = [ci]
     _lib = lib
@@ -200,3 +217,75 @@ def bitlinear_backward_ste(dY: torch.Tensor, codes: torch.Tensor, gamma: torch.T
         _gran(per_tensor), _ptr(packed), _ptr(beta, torch.float32), _ptr(dX), _ptr(dW), _ptr(ws),
         ws.numel(), _stream()), "bitlinear_backward_ste")
     return dX, dW
+
+
+# ---- Group Quantization and Normalization (Eq. 13-15) ----------------------------------
+def packed_bytes_grouped(N: int, K: int, groups_n: int, groups_k: int) -> int:
+    return int(load_library().bitlinear_packed_bytes_grouped(N, K, groups_n, groups_k))
+
+
+def workspace_bytes_grouped(op: int, M: int, N: int, K: int, groups_n: int, groups_k: int,
+                            per_tensor: bool = False) -> int:
+    return int(load_library().bitlinear_workspace_bytes_grouped(op, M, N, K, groups_n, groups_k,
+                                                                _gran(per_tensor)))
+
+
+def bitlinear_pack_weights_grouped(W: torch.Tensor, groups_n: int = 1, groups_k: int = 1,
+                                   flags: int = 0):
+    """Eq. 13.  Returns (packed blob, alpha [groups_n, groups_k], beta [groups_n, groups_k])."""
+    N, K = W.shape
+    nbytes = packed_bytes_grouped(N, K, groups_n, groups_k)
+    packed = torch.empty(max(nbytes, 1), dtype=torch.uint8, device=W.device)
+    alpha = torch.empty((groups_n, groups_k), dtype=torch.float32, device=W.device)
+    beta = torch.empty((groups_n, groups_k), dtype=torch.float32, device=W.device)
+    ws = _workspace(workspace_bytes_grouped(OP_PACK, 0, N, K, groups_n, groups_k), W.device)
+    _check(load_library().bitlinear_pack_weights_grouped(
+        _ptr(W, torch.float32), N, K, groups_n, groups_k, flags, _ptr(packed), _ptr(alpha),
+        _ptr(beta), _ptr(ws), ws.numel(), _stream()), "bitlinear_pack_weights_grouped")
+    return packed, alpha, beta
+
+
+def bitlinear_packed_to_canonical_grouped(packed: torch.Tensor, N: int, K: int,
+                                          groups_k: int) -> torch.Tensor:
+    out = torch.empty((N, K // 32), dtype=torch.int32, device=packed.device)
+    _check(load_library().bitlinear_packed_to_canonical_grouped(
+        _ptr(packed), N, K, groups_k, _ptr(out), _stream()), "bitlinear_packed_to_canonical_grouped")
+    return out
+
+
+def bitlinear_quant_act_grouped(X: torch.Tensor, groups_k: int, ln_eps: float = 1e-5,
+                                per_tensor: bool = False, flags: int = 0, ln_gain=None,
+                                ln_bias=None, want_xhat: bool = False):
+    """Eq. 14-15.  Returns (codes [M,K], gamma [M,groups_k] or [groups_k], rowsum [M,groups_k],
+    xhat or None)."""
+    M, K = X.shape
+    dev = X.device
+    codes = torch.empty((M, K), dtype=torch.int8, device=dev)
+    gamma = torch.empty((groups_k,) if per_tensor else (max(M, 1), groups_k), dtype=torch.float32,
+                        device=dev)
+    rowsum = torch.empty((max(M, 1), groups_k), dtype=torch.int32, device=dev)
+    xhat = torch.empty((M, K), dtype=torch.float32, device=dev) if want_xhat else None
+    ws = _workspace(workspace_bytes_grouped(OP_QUANT, M, 16, K, 1, groups_k, per_tensor), dev)
+    _check(load_library().bitlinear_quant_act_grouped(
+        _ptr(X, torch.float32), M, K, groups_k, _ptr(ln_gain, torch.float32),
+        _ptr(ln_bias, torch.float32), ln_eps, _gran(per_tensor), flags, _ptr(codes), _ptr(gamma),
+        _ptr(rowsum), _ptr(xhat), _ptr(ws), ws.numel(), _stream()), "bitlinear_quant_act_grouped")
+    return codes, gamma, rowsum, xhat
+
+
+def bitlinear_forward_grouped(X: torch.Tensor, packed: torch.Tensor, N: int, beta: torch.Tensor,
+                              groups_n: int = 1, groups_k: int = 1, ln_eps: float = 1e-5,
+                              per_tensor: bool = False, flags: int = 0, ln_gain=None, ln_bias=None,
+                              out: torch.Tensor | None = None) -> torch.Tensor:
+    """Eq. 11 with the group parameters of Eq. 13-15."""
+    M, K = X.shape
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=X.device)
+    ws = _workspace(workspace_bytes_grouped(OP_FORWARD, M, N, K, groups_n, groups_k, per_tensor),
+                    X.device)
+    _check(load_library().bitlinear_forward_grouped(
+        _ptr(X, torch.float32), M, K, _ptr(packed), N, groups_n, groups_k,
+        _ptr(beta, torch.float32), _ptr(ln_gain, torch.float32), _ptr(ln_bias, torch.float32),
+        ln_eps, _gran(per_tensor), flags, _ptr(out), _ptr(ws), ws.numel(), _stream()),
+        "bitlinear_forward_grouped")
+    return out

@@ -55,6 +55,42 @@ ForwardWs forward_ws(int64_t M, int64_t K, int granularity) {
 
 int check_hip(hipError_t e) { return e == hipSuccess ? BL_OK : BL_ERR_HIP; }
 
+// ---- group quantisation (Eq. 13-15) ----------------------------------------------
+constexpr int kMaxGroups = 64;
+// 0 = fine, else the status to return
+int groups_status(int64_t N, int64_t K, int groups_n, int groups_k) {
+    if (groups_n < 1 || groups_k < 1 || groups_n > kMaxGroups || groups_k > kMaxGroups)
+        return BL_ERR_SHAPE;
+    if (N % groups_n || K % groups_k || (K / groups_k) % 32) return BL_ERR_SHAPE;
+    // a 16-row weight tile carries one alpha: row groups must be whole tiles
+    if (groups_n > 1 && (N / groups_n) % kTileN) return BL_ERR_UNSUPPORTED;
+    return BL_OK;
+}
+QuantWs quant_ws_grouped(int64_t M, int groups_k, int granularity) {
+    return quant_ws(M * groups_k, granularity);
+}
+ForwardWs forward_ws_grouped(int64_t M, int64_t K, int groups_k, int granularity) {
+    ForwardWs w{};
+    size_t off = 0;
+    w.codes = off;
+    off += align256((size_t)M * (size_t)K);
+    w.gamma = off;
+    off += align256((size_t)M * groups_k * 4);
+    w.rowsum = off;
+    off += align256((size_t)M * groups_k * 4);
+    w.quant = off;
+    off += quant_ws_grouped(M, groups_k, granularity).total;
+    w.total = off;
+    return w;
+}
+void plain_fields(GemmArgs& a) {
+    a.ldq = a.K;
+    a.gstride = 1;
+    a.beta_rows = a.N;
+    a.beta_stride = 0;
+    a.accumulate = false;
+}
+
 }  // namespace
 
 extern "C" {
@@ -94,15 +130,16 @@ int bitlinear_pack_weights(const float* W, int64_t N, int64_t K, unsigned flags,
     if (!W || !packed || !alpha || !beta) return BL_ERR_NULL;
     const size_t need = bitlinear_workspace_bytes(BL_OP_PACK, 0, N, K, 0, flags);
     if (!workspace || workspace_bytes < need) return BL_ERR_WORKSPACE;
-    return check_hip(launch_pack(W, N, K, (flags & BL_FLAG_BETA_CENTERED) != 0, (uint32_t*)packed,
-                                 alpha, beta, (double*)workspace, (hipStream_t)stream));
+    return check_hip(launch_pack(W, N, K, K, (flags & BL_FLAG_BETA_CENTERED) != 0,
+                                 (uint32_t*)packed, alpha, beta, (double*)workspace,
+                                 (hipStream_t)stream));
 }
 
 int bitlinear_packed_to_canonical(const void* packed, int64_t N, int64_t K, uint32_t* canonical,
                                   void* stream) {
     if (!shape_ok(N, K)) return BL_ERR_SHAPE;
     if (!packed || !canonical) return BL_ERR_NULL;
-    return check_hip(launch_to_canonical((const uint32_t*)packed, N, K, canonical,
+    return check_hip(launch_to_canonical((const uint32_t*)packed, N, K, canonical, K / 32,
                                          (hipStream_t)stream));
 }
 
@@ -124,6 +161,7 @@ int bitlinear_quant_act(const float* X, int64_t M, int64_t K, const float* ln_ga
     a.codes = codes; a.gamma = gamma; a.rowsum = rowsum; a.xhat_dump = xhat_dump;
     a.rowstats = (double*)((char*)workspace + ws.rowstats);
     a.gmax_bits = (uint32_t*)((char*)workspace + ws.gmax);
+    a.groups = 1;
     return check_hip(launch_quant(a, (hipStream_t)stream));
 }
 
@@ -140,6 +178,7 @@ int bitlinear_matmul(const int8_t* codes, const float* gamma, const int32_t* row
     a.per_tensor = granularity == BL_GAMMA_PER_TENSOR;
     a.out_acc = (flags & BL_FLAG_OUT_ACC_I32) != 0;
     a.Y = Y;
+    plain_fields(a);
     if (M <= 16) return check_hip(launch_gemm_decode(a, (hipStream_t)stream));
     return check_hip(launch_gemm_prefill(a, (hipStream_t)stream));
 }
@@ -167,6 +206,137 @@ int bitlinear_forward(const float* X, int64_t M, int64_t K, const void* packed, 
                             flags & BL_FLAG_OUT_ACC_I32, Y, stream);
 }
 
+// ---- Group Quantization and Normalization (Eq. 13-15) ----------------------------------
+
+size_t bitlinear_packed_bytes_grouped(int64_t N, int64_t K, int groups_n, int groups_k) {
+    if (!shape_ok(N, K) || groups_status(N, K, groups_n, groups_k) != BL_OK) return 0;
+    return (size_t)groups_k * tiles_bytes(N, K / groups_k);
+}
+
+size_t bitlinear_workspace_bytes_grouped(int op, int64_t M, int64_t N, int64_t K, int groups_n,
+                                         int groups_k, int granularity) {
+    if (!gran_ok(granularity) || !shape_ok(N, K) || M < 0 || M > kMaxDim) return 0;
+    if (groups_status(N, K, groups_n, groups_k) != BL_OK) return 0;
+    switch (op) {
+        case BL_OP_PACK:
+            return align256((size_t)reduce_grid(N * K / 4) * 16);
+        case BL_OP_QUANT:
+            return quant_ws_grouped(M, groups_k, granularity).total;
+        case BL_OP_FORWARD:
+            return forward_ws_grouped(M, K, groups_k, granularity).total;
+        default:
+            return 0;
+    }
+}
+
+int bitlinear_pack_weights_grouped(const float* W, int64_t N, int64_t K, int groups_n,
+                                   int groups_k, unsigned flags, void* packed, float* alpha,
+                                   float* beta, void* workspace, size_t workspace_bytes,
+                                   void* stream) {
+    if (!shape_ok(N, K)) return BL_ERR_SHAPE;
+    if (int st = groups_status(N, K, groups_n, groups_k)) return st;
+    if (flags & ~BL_FLAG_BETA_CENTERED) return BL_ERR_UNSUPPORTED;
+    if (!W || !packed || !alpha || !beta) return BL_ERR_NULL;
+    const size_t need = bitlinear_workspace_bytes_grouped(BL_OP_PACK, 0, N, K, groups_n, groups_k, 0);
+    if (!workspace || workspace_bytes < need) return BL_ERR_WORKSPACE;
+    const int64_t Ng = N / groups_n, Kg = K / groups_k;
+    const size_t blob_dwords = tiles_bytes(N, Kg) / 4;
+    for (int gk = 0; gk < groups_k; ++gk)
+        for (int gn = 0; gn < groups_n; ++gn) {
+            // block (gn, gk): rows gn*Ng .., columns gk*Kg ..; its tiles are rows gn*Ng/16 .. of
+            // K-group gk's blob
+            uint32_t* dst = (uint32_t*)packed + gk * blob_dwords +
+                            tile_dword_offset(gn * Ng / kTileN, 0, tiles_k(Kg));
+            const int idx = gn * groups_k + gk;
+            hipError_t e = launch_pack(W + gn * Ng * K + gk * Kg, Ng, Kg, K,
+                                       (flags & BL_FLAG_BETA_CENTERED) != 0, dst, alpha + idx,
+                                       beta + idx, (double*)workspace, (hipStream_t)stream);
+            if (e != hipSuccess) return BL_ERR_HIP;
+        }
+    return BL_OK;
+}
+
+int bitlinear_packed_to_canonical_grouped(const void* packed, int64_t N, int64_t K, int groups_k,
+                                          uint32_t* canonical, void* stream) {
+    if (!shape_ok(N, K)) return BL_ERR_SHAPE;
+    if (int st = groups_status(N, K, 1, groups_k)) return st;
+    if (!packed || !canonical) return BL_ERR_NULL;
+    const int64_t Kg = K / groups_k;
+    const size_t blob_dwords = tiles_bytes(N, Kg) / 4;
+    for (int gk = 0; gk < groups_k; ++gk) {
+        hipError_t e = launch_to_canonical((const uint32_t*)packed + gk * blob_dwords, N, Kg,
+                                           canonical + gk * (Kg / 32), K / 32, (hipStream_t)stream);
+        if (e != hipSuccess) return BL_ERR_HIP;
+    }
+    return BL_OK;
+}
+
+int bitlinear_quant_act_grouped(const float* X, int64_t M, int64_t K, int groups_k,
+                                const float* ln_gain, const float* ln_bias, float ln_eps,
+                                int granularity, unsigned flags, int8_t* codes, float* gamma,
+                                int32_t* rowsum, float* xhat_dump, void* workspace,
+                                size_t workspace_bytes, void* stream) {
+    if (M < 0 || M > kMaxDim || K <= 0 || K > kMaxDim || K % 32) return BL_ERR_SHAPE;
+    if (groups_k < 1 || groups_k > kMaxGroups || K % groups_k || (K / groups_k) % 32)
+        return BL_ERR_SHAPE;
+    if (!gran_ok(granularity) || (flags & ~BL_FLAG_SKIP_LN)) return BL_ERR_UNSUPPORTED;
+    const int64_t Kg = K / groups_k;
+    if (!quant_supported(Kg) || M * groups_k > kMaxDim) return BL_ERR_UNSUPPORTED;
+    if (M == 0) return BL_OK;
+    if (!X || !codes || !gamma) return BL_ERR_NULL;
+    const QuantWs ws = quant_ws_grouped(M, groups_k, granularity);
+    if (!workspace || workspace_bytes < ws.total) return BL_ERR_WORKSPACE;
+    // a token's K-groups are consecutive rows of a [M * groups_k, Kg] matrix
+    QuantArgs a{};
+    a.X = X; a.M = M * groups_k; a.K = Kg; a.gain = ln_gain; a.bias = ln_bias; a.eps = ln_eps;
+    a.skip_ln = (flags & BL_FLAG_SKIP_LN) != 0;
+    a.per_tensor = granularity == BL_GAMMA_PER_TENSOR;
+    a.codes = codes; a.gamma = gamma; a.rowsum = rowsum; a.xhat_dump = xhat_dump;
+    a.rowstats = (double*)((char*)workspace + ws.rowstats);
+    a.gmax_bits = (uint32_t*)((char*)workspace + ws.gmax);
+    a.groups = groups_k;
+    return check_hip(launch_quant(a, (hipStream_t)stream));
+}
+
+int bitlinear_forward_grouped(const float* X, int64_t M, int64_t K, const void* packed, int64_t N,
+                              int groups_n, int groups_k, const float* beta, const float* ln_gain,
+                              const float* ln_bias, float ln_eps, int granularity, unsigned flags,
+                              float* Y, void* workspace, size_t workspace_bytes, void* stream) {
+    if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return BL_ERR_SHAPE;
+    if (int st = groups_status(N, K, groups_n, groups_k)) return st;
+    if (!gran_ok(granularity) || (flags & ~BL_FLAG_SKIP_LN)) return BL_ERR_UNSUPPORTED;
+    if (M == 0) return BL_OK;
+    if (!X || !packed || !beta || !Y) return BL_ERR_NULL;
+    const ForwardWs ws = forward_ws_grouped(M, K, groups_k, granularity);
+    if (!workspace || workspace_bytes < ws.total) return BL_ERR_WORKSPACE;
+    char* base = (char*)workspace;
+    int8_t* codes = (int8_t*)(base + ws.codes);
+    float* gamma = (float*)(base + ws.gamma);
+    int32_t* rowsum = (int32_t*)(base + ws.rowsum);
+    int rc = bitlinear_quant_act_grouped(X, M, K, groups_k, ln_gain, ln_bias, ln_eps, granularity,
+                                         flags & BL_FLAG_SKIP_LN, codes, gamma, rowsum, nullptr,
+                                         base + ws.quant, workspace_bytes - ws.quant, stream);
+    if (rc != BL_OK) return rc;
+    // one GEMM per K-group, each dequantised with its own beta_g * gamma_g and added (Eq. 13-14)
+    const int64_t Kg = K / groups_k;
+    const size_t blob_dwords = tiles_bytes(N, Kg) / 4;
+    for (int gk = 0; gk < groups_k; ++gk) {
+        GemmArgs a{};
+        a.codes = codes + gk * Kg; a.gamma = gamma + gk; a.rowsum = rowsum + gk;
+        a.M = M; a.K = Kg; a.N = N;
+        a.packed = (const uint32_t*)packed + gk * blob_dwords; a.beta = beta + gk;
+        a.per_tensor = granularity == BL_GAMMA_PER_TENSOR;
+        a.out_acc = false;
+        a.Y = Y;
+        a.ldq = K; a.gstride = groups_k; a.beta_rows = N / groups_n; a.beta_stride = groups_k;
+        a.accumulate = gk > 0;
+        const hipError_t e = M <= 16 ? launch_gemm_decode(a, (hipStream_t)stream)
+                                     : launch_gemm_prefill(a, (hipStream_t)stream);
+        if (e != hipSuccess) return BL_ERR_HIP;
+    }
+    return BL_OK;
+}
+
 int bitlinear_backward_ste(const float* dY, int64_t M, int64_t N, int64_t K, const int8_t* codes,
                            const float* gamma, int granularity, const void* packed,
                            const float* beta, float* dX, float* dW, void* workspace,
@@ -191,7 +361,8 @@ const char* bitlinear_status_string(int status) {
     switch (status) {
         case BL_OK: return "ok";
         case BL_ERR_NULL: return "a required pointer is NULL";
-        case BL_ERR_SHAPE: return "bad shape (M, N, K out of range or K not a multiple of 32)";
+        case BL_ERR_SHAPE:
+            return "bad shape (M, N, K out of range, K not a multiple of 32, or groups that do not divide)";
         case BL_ERR_UNSUPPORTED: return "unsupported granularity, flag or size";
         case BL_ERR_WORKSPACE: return "workspace missing or too small";
         case BL_ERR_HIP: return "HIP launch failed";

@@ -35,11 +35,17 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
     const int M = (int)a.M;
     const int64_t tn0 = (int64_t)blockIdx.x * tpb;
 
-    // epilogue operands, requested up front so their latency hides under the weight stream
-    const float beta = *a.beta;
+    // epilogue operands, requested up front so their latency hides under the weight stream.
+    // beta belongs to the group of output rows that holds a tile (Eq. 13; one group: beta[0]).
+    auto beta_of = [&](int64_t tn) {
+        if (a.beta_rows >= a.N) return a.beta[0];  // one group: no division on the plain path
+        if (tn > TN - 1) tn = TN - 1;
+        return a.beta[((uint32_t)(tn * kTileN) / (uint32_t)a.beta_rows) * a.beta_stride];  // N <= 2^30
+    };
+    const float beta_first = beta_of(tn0 + w);
     const int mc = m < M ? m : M - 1;
-    const int rs = a.rowsum[mc];
-    const float gm = a.per_tensor ? a.gamma[0] : a.gamma[mc];
+    const int rs = a.rowsum[mc * a.gstride];
+    const float gm = a.per_tensor ? a.gamma[0] : a.gamma[mc * a.gstride];
 
     int part[ONE_ROUND ? 1 : T][4];
     if (!ONE_ROUND) {
@@ -60,7 +66,7 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
         // activation operand: lane (m, g) holds codes[m][512*tk + 64*i + 16*g .. +15].  Rows
         // m >= M read row M-1 (their outputs are never stored); columns k >= K read the last 16
         // valid bytes (the packed bits there are zero, so they contribute nothing).
-        const int8_t* arow = a.codes + (int64_t)(m < M ? m : M - 1) * a.K;
+        const int8_t* arow = a.codes + (int64_t)(m < M ? m : M - 1) * a.ldq;
         v4i act[C][8];
 #pragma unroll
         for (int c = 0; c < C; ++c)
@@ -166,12 +172,16 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
                 for (int r = 0; r < 4; ++r)
                     if (n + r < a.N) yi[r] = pm[r];
         } else {
+            const float beta = t == w ? beta_first : beta_of(tn);
             const float sc = (beta * gm) / 128.0f;
-            const v4f o = {(float)pm[0] * sc, (float)pm[1] * sc, (float)pm[2] * sc, (float)pm[3] * sc};
-            if ((a.N & 3) == 0) *reinterpret_cast<v4f*>(y) = o;
-            else
+            v4f o = {(float)pm[0] * sc, (float)pm[1] * sc, (float)pm[2] * sc, (float)pm[3] * sc};
+            if ((a.N & 3) == 0) {
+                if (a.accumulate) o += *reinterpret_cast<const v4f*>(y);  // a later K-group
+                *reinterpret_cast<v4f*>(y) = o;
+            } else {
                 for (int r = 0; r < 4; ++r)
-                    if (n + r < a.N) y[r] = o[r];
+                    if (n + r < a.N) y[r] = a.accumulate ? y[r] + o[r] : o[r];
+            }
         }
     }
 }

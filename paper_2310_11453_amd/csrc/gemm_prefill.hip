@@ -171,6 +171,11 @@ __device__ inline void lds_read_rows(v4f& sc, v4i& rs, uint32_t ad_sc, uint32_t 
         : "=&v"(sc), "=&v"(rs)
         : "v"(ad_sc), "v"(ad_rs));
 }
+__device__ inline float lds_read_f32(uint32_t ad) {
+    float v;
+    asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(v) : "v"(ad));
+    return v;
+}
 __device__ inline void lds_write_b32(uint32_t ad, uint32_t v) {
     asm volatile("ds_write_b32 %0, %1" : : "v"(ad), "v"(v) : "memory");
 }
@@ -195,7 +200,8 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
 
     __shared__ __attribute__((aligned(1024))) uint8_t smA[NS * STAGE_BYTES];
     __shared__ __attribute__((aligned(1024))) uint8_t smB[(BN / 16) * 1024];
-    __shared__ __attribute__((aligned(16))) float smScale[2][BM];  // beta*gamma_m/128, per tile parity
+    __shared__ __attribute__((aligned(16))) float smScale[2][BM];  // gamma_m, per tile parity
+    __shared__ __attribute__((aligned(16))) float smBeta[2][BN];   // beta of each column's group
     __shared__ __attribute__((aligned(16))) int smRowsum[2][BM];   // sum_k q[m,k]
 
     const int w = threadIdx.x / kWave, l = threadIdx.x % kWave;
@@ -238,9 +244,9 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
             int row = slot >> 2;
             gseg[q] = ((slot & 3) ^ ((row >> 2) & 3)) * 16;
             if (m0 + row > M - 1) row = (int)(M - 1 - m0);
-            goff[q] = (uint32_t)row * (uint32_t)K + gseg[q];
+            goff[q] = (uint32_t)row * (uint32_t)a.ldq + gseg[q];
         }
-        gbase = a.codes + m0 * K;
+        gbase = a.codes + m0 * a.ldq;
         // packed weights: tile t of the block goes to smB + t KiB, lane for lane as it lies in
         // memory; wave w moves tiles w, w + NWAVES, ...  Columns past N read a valid tile.
 #pragma unroll
@@ -325,7 +331,6 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
         }
     };
 
-    const float beta = *a.beta;
     const int64_t kfull = K / kStageK;
     // chunks whose look-ahead stays inside K and that have a successor chunk
     const int64_t main_chunks = kfull >= NS + 7 ? (kfull - NS - 7) / 8 + 1 : 0;
@@ -338,17 +343,24 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
     issue_tile_start();
 
     while (true) {
-        // per-row dequantisation scale (Eq. 11) and row sum of the codes, for the epilogue
+        // per-row gamma and row sum of the codes, per-column beta (Eq. 11, Eq. 13), for the
+        // epilogue
         for (int r = threadIdx.x; r < BM; r += THREADS) {
             const int64_t m = m0 + r;
             float sc = 0.f;
             int rs = 0;
             if (m < M) {
-                sc = (beta * (a.per_tensor ? a.gamma[0] : a.gamma[m])) / 128.0f;
-                rs = a.rowsum[m];
+                sc = a.per_tensor ? a.gamma[0] : a.gamma[m * a.gstride];
+                rs = a.rowsum[m * a.gstride];
             }
             lds_write_b32((uint32_t)(uintptr_t)&smScale[parity][r], __float_as_uint(sc));
             lds_write_b32((uint32_t)(uintptr_t)&smRowsum[parity][r], (uint32_t)rs);
+        }
+        for (int c = threadIdx.x; c < BN; c += THREADS) {
+            int64_t n = n0 + c;
+            if (n > a.N - 1) n = a.N - 1;
+            const float b = a.beta[((uint32_t)n / (uint32_t)a.beta_rows) * a.beta_stride];
+            lds_write_b32((uint32_t)(uintptr_t)&smBeta[parity][c], __float_as_uint(b));
         }
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
@@ -390,7 +402,11 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
         }
 
         // ---- epilogue (Eq. 11): lane (j, g2) holds column n, rows 8*(r/4) + 4*g2 + r%4 ----
-        //   sum_k q s = 2 sum_k q b - sum_k q ;  y = that * (beta * gamma_m / 128)
+        //   sum_k q s = 2 sum_k q b - sum_k q ;  y = that * (beta_n * gamma_m / 128)
+        float bcol[NI];
+#pragma unroll
+        for (int s = 0; s < NI; ++s)
+            bcol[s] = lds_read_f32((uint32_t)(uintptr_t)&smBeta[parity][wn * WTN + 32 * s + j]);
         const uint32_t sc_base = (uint32_t)(uintptr_t)&smScale[parity][wm * WTM + 4 * g2];
         const uint32_t rs_base = (uint32_t)(uintptr_t)&smRowsum[parity][wm * WTM + 4 * g2];
 #pragma unroll
@@ -410,8 +426,14 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
                         const int64_t n = n0 + wn * WTN + 32 * s + j;
                         if (n >= a.N) continue;
                         const int pm = 2 * acc[mi][s][r] - rs4[rr];
-                        if (a.out_acc) reinterpret_cast<int*>(a.Y)[m * a.N + n] = pm;
-                        else a.Y[m * a.N + n] = (float)pm * sc4[rr];
+                        if (a.out_acc) {
+                            reinterpret_cast<int*>(a.Y)[m * a.N + n] = pm;
+                        } else {
+                            // y = acc * ((beta * gamma) / 128): the division by 128 is exact
+                            float y = (float)pm * ((bcol[s] * sc4[rr]) * 0.0078125f);
+                            if (a.accumulate) y += a.Y[m * a.N + n];  // a later K-group
+                            a.Y[m * a.N + n] = y;
+                        }
                     }
                 }
             }
@@ -449,7 +471,7 @@ static void launch_tile(const GemmArgs& a, hipStream_t s) {
 
 // K < 2^22 is required (the per-lane offset into a block of 256 rows is kept in 32 bits).
 hipError_t launch_gemm_prefill(const GemmArgs& a, hipStream_t s) {
-    if (a.K >= ((int64_t)1 << 22)) return hipErrorInvalidValue;
+    if (a.K >= ((int64_t)1 << 22) || a.ldq >= ((int64_t)1 << 22)) return hipErrorInvalidValue;
     const char* e = getenv("BITLINEAR_PREFILL_TILE");  // bench-only override: 0, 1, 2
     int pick;
     if (e) pick = atoi(e);

@@ -6,11 +6,14 @@
 namespace bl {
 
 // pack.hip
+// A block of `rows` x `cols` weights inside a matrix whose rows are `ldw` floats apart
+// (ldw == cols: the whole matrix).  `packed` receives tiles_n(rows) x tiles_k(cols) tiles.
 int reduce_grid(int64_t count4);
-hipError_t launch_pack(const float* W, int64_t N, int64_t K, bool beta_centered, uint32_t* packed,
-                       float* alpha, float* beta, double* partials, hipStream_t s);
+hipError_t launch_pack(const float* W, int64_t rows, int64_t cols, int64_t ldw, bool beta_centered,
+                       uint32_t* packed, float* alpha, float* beta, double* partials, hipStream_t s);
+// canonical words of the block go to canonical[n * ldc + kw], ldc in words
 hipError_t launch_to_canonical(const uint32_t* packed, int64_t N, int64_t K, uint32_t* canonical,
-                               hipStream_t s);
+                               int64_t ldc, hipStream_t s);
 
 // quant.hip
 struct QuantArgs {
@@ -26,7 +29,11 @@ struct QuantArgs {
     int32_t* rowsum;
     float* xhat_dump;
     double* rowstats;   // per-tensor only: [M][2] = (mean, rstd)
-    uint32_t* gmax_bits; // per-tensor only: [1], bit pattern of the running max
+    uint32_t* gmax_bits; // per-tensor only: [groups], bit pattern of the running max
+    // Group normalisation / quantisation (Eq. 14-15): a token of `groups` * K elements is
+    // handled as `groups` consecutive rows of K; row r belongs to group r % groups.  M counts
+    // those rows.  gain/bias hold groups * K entries.  groups = 1: the plain layer.
+    int groups;
 };
 bool quant_supported(int64_t K);
 hipError_t launch_quant(const QuantArgs& a, hipStream_t s);
@@ -42,6 +49,12 @@ struct GemmArgs {
     bool per_tensor;
     bool out_acc;
     float* Y;
+    // Group quantisation (Eq. 13-15); plain layer: ldq = K, gstride = 1, beta_rows = N.
+    int64_t ldq;          // bytes between consecutive rows of codes (>= K: a K-slice of wider rows)
+    int64_t gstride;      // gamma[m * gstride], rowsum[m * gstride] belong to token m
+    int64_t beta_rows;    // output columns n per beta group (a multiple of 16, or N)
+    int64_t beta_stride;  // beta[(n / beta_rows) * beta_stride] scales column n
+    bool accumulate;      // Y += result (a later K-group) instead of Y = result
 };
 hipError_t launch_gemm_decode(const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm_prefill(const GemmArgs& a, hipStream_t s);

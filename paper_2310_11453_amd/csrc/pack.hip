@@ -10,16 +10,20 @@ namespace bl {
 // ---- pass 1: per-block partial sums of W and |W - centre| in fp64 ----------
 // partials[2*b] = sum of W, partials[2*b+1] = sum of |W - centre| over the
 // block's grid-stride share.  centre_ptr == nullptr means centre = 0.
+// The block's rows are cols4 float4 long and ld4 float4 apart (ld4 == cols4: contiguous, the
+// index is used as it is).
 __global__ __launch_bounds__(256) void weight_partial_sums(const float4* __restrict__ W4,
-                                                           int64_t count4,
+                                                           int64_t count4, int64_t cols4,
+                                                           int64_t ld4,
                                                            const float* __restrict__ centre_ptr,
                                                            double* __restrict__ partials) {
     __shared__ double sm[4];
     const double centre = centre_ptr ? (double)*centre_ptr : 0.0;
     double s = 0.0, a = 0.0;
     const int64_t stride = (int64_t)gridDim.x * 256;
+    const bool strided = ld4 != cols4;
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count4; i += stride) {
-        const float4 w = W4[i];
+        const float4 w = W4[strided ? (i / cols4) * ld4 + i % cols4 : i];
         const double x = (double)w.x, y = (double)w.y, z = (double)w.z, u = (double)w.w;
         s += (x + y) + (z + u);
         a += (fabs(x - centre) + fabs(y - centre)) + (fabs(z - centre) + fabs(u - centre));
@@ -59,7 +63,8 @@ __global__ __launch_bounds__(256) void weight_finalize(const double* __restrict_
 // the same (lane % 16), which two xor-shuffles OR together.  The tile is
 // staged in LDS so the final store is one 16-byte write per lane.
 __global__ __launch_bounds__(256) void pack_tiles(const float* __restrict__ W, int64_t N,
-                                                  int64_t K, const float* __restrict__ alpha_ptr,
+                                                  int64_t K, int64_t ldw,
+                                                  const float* __restrict__ alpha_ptr,
                                                   uint32_t* __restrict__ packed) {
     __shared__ uint32_t sm[4][256];
     const int wave = threadIdx.x / kWave, l = threadIdx.x % kWave;
@@ -77,7 +82,7 @@ __global__ __launch_bounds__(256) void pack_tiles(const float* __restrict__ W, i
         for (int it = 0; it < 2; ++it) {
             const int64_t k = tk * kChunkK + 256 * it + 4 * l;
             if (live && n < N && k < K) {
-                const float4 w = *reinterpret_cast<const float4*>(W + n * K + k);
+                const float4 w = *reinterpret_cast<const float4*>(W + n * ldw + k);
                 const int i = 4 * it + (l >> 4);
                 part |= (uint32_t)(w.x > alpha) << i;
                 part |= (uint32_t)(w.y > alpha) << (8 + i);
@@ -100,7 +105,8 @@ __global__ __launch_bounds__(256) void pack_tiles(const float* __restrict__ W, i
 // canonical[n][kw] bit b  <->  sign bit of (n, k = 32*kw + b).
 __global__ __launch_bounds__(256) void tiles_to_canonical(const uint32_t* __restrict__ packed,
                                                           int64_t N, int64_t K,
-                                                          uint32_t* __restrict__ canonical) {
+                                                          uint32_t* __restrict__ canonical,
+                                                          int64_t ldc) {
     const int64_t KW = K / 32;
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= N * KW) return;
@@ -119,7 +125,7 @@ __global__ __launch_bounds__(256) void tiles_to_canonical(const uint32_t* __rest
         const uint32_t dw = tile[(g * 16 + c) * 4 + d];
         word |= ((dw >> (8 * j + i)) & 1u) << b;
     }
-    canonical[idx] = word;
+    canonical[n * ldc + kw] = word;
 }
 
 // ---------------------------------------------------------------------------
@@ -130,26 +136,27 @@ int reduce_grid(int64_t count4) {
     return (int)g;
 }
 
-hipError_t launch_pack(const float* W, int64_t N, int64_t K, bool beta_centered, uint32_t* packed,
-                       float* alpha, float* beta, double* partials, hipStream_t s) {
+hipError_t launch_pack(const float* W, int64_t N, int64_t K, int64_t ldw, bool beta_centered,
+                       uint32_t* packed, float* alpha, float* beta, double* partials, hipStream_t s) {
     const int64_t count4 = N * K / 4;
     const int G = reduce_grid(count4);
     const double cnt = (double)N * (double)K;
-    weight_partial_sums<<<G, 256, 0, s>>>((const float4*)W, count4, nullptr, partials);
+    const float4* W4 = (const float4*)W;
+    weight_partial_sums<<<G, 256, 0, s>>>(W4, count4, K / 4, ldw / 4, nullptr, partials);
     weight_finalize<<<1, 256, 0, s>>>(partials, G, cnt, 1, beta_centered ? 0 : 1, alpha, beta);
     if (beta_centered) {
-        weight_partial_sums<<<G, 256, 0, s>>>((const float4*)W, count4, alpha, partials);
+        weight_partial_sums<<<G, 256, 0, s>>>(W4, count4, K / 4, ldw / 4, alpha, partials);
         weight_finalize<<<1, 256, 0, s>>>(partials, G, cnt, 0, 1, alpha, beta);
     }
     const int64_t tasks = tiles_n(N) * tiles_k(K);
-    pack_tiles<<<(unsigned)((tasks + 3) / 4), 256, 0, s>>>(W, N, K, alpha, packed);
+    pack_tiles<<<(unsigned)((tasks + 3) / 4), 256, 0, s>>>(W, N, K, ldw, alpha, packed);
     return hipGetLastError();
 }
 
 hipError_t launch_to_canonical(const uint32_t* packed, int64_t N, int64_t K, uint32_t* canonical,
-                               hipStream_t s) {
+                               int64_t ldc, hipStream_t s) {
     const int64_t words = N * (K / 32);
-    tiles_to_canonical<<<(unsigned)((words + 255) / 256), 256, 0, s>>>(packed, N, K, canonical);
+    tiles_to_canonical<<<(unsigned)((words + 255) / 256), 256, 0, s>>>(packed, N, K, canonical, ldc);
     return hipGetLastError();
 }
 

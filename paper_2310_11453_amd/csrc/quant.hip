@@ -103,6 +103,7 @@ __global__ __launch_bounds__((WPR < 4 ? 4 : WPR) * kWave, 4) void ln_quant_rows(
     }
     const int K4 = (int)(a.K / 4);
     const float4* __restrict__ x4 = reinterpret_cast<const float4*>(a.X + row * a.K);
+    const int grp = a.groups > 1 ? (int)(row % a.groups) : 0;  // K-group of this row (Eq. 14-15)
 
     // The loads are unconditional (clamped index, value masked afterwards) so that all of
     // them are in flight before the first is needed.
@@ -206,11 +207,11 @@ __global__ __launch_bounds__((WPR < 4 ? 4 : WPR) * kWave, 4) void ln_quant_rows(
                 o.w = (float)(((double)v[j].w - mu) * rstd);
                 if (idx < K4) {
                     if (a.gain) {
-                        const float4 g = reinterpret_cast<const float4*>(a.gain)[idx];
+                        const float4 g = reinterpret_cast<const float4*>(a.gain + grp * a.K)[idx];
                         o.x = o.x * g.x; o.y = o.y * g.y; o.z = o.z * g.z; o.w = o.w * g.w;
                     }
                     if (a.bias) {
-                        const float4 b = reinterpret_cast<const float4*>(a.bias)[idx];
+                        const float4 b = reinterpret_cast<const float4*>(a.bias + grp * a.K)[idx];
                         o.x = o.x + b.x; o.y = o.y + b.y; o.z = o.z + b.z; o.w = o.w + b.w;
                     }
                     v[j] = o;
@@ -232,7 +233,7 @@ __global__ __launch_bounds__((WPR < 4 ? 4 : WPR) * kWave, 4) void ln_quant_rows(
 
     float gamma;
     if constexpr (MODE == kApply) {
-        gamma = fmaxf(__uint_as_float(*a.gmax_bits), 1e-5f);
+        gamma = fmaxf(__uint_as_float(a.gmax_bits[grp]), 1e-5f);
     } else {
         if (!have_amax) {  // uniform: no LayerNorm, or a gain/bias after it
             float m = 0.f;
@@ -246,7 +247,7 @@ __global__ __launch_bounds__((WPR < 4 ? 4 : WPR) * kWave, 4) void ln_quant_rows(
         }
         if constexpr (MODE == kStats) {
             // non-negative floats order like their bit patterns: integer max is exact
-            if (t == 0 && live) atomicMax(a.gmax_bits, __float_as_uint(amax));
+            if (t == 0 && live) atomicMax(a.gmax_bits + grp, __float_as_uint(amax));
             return;
         }
         gamma = fmaxf(amax, 1e-5f);
@@ -284,11 +285,13 @@ __global__ __launch_bounds__((WPR < 4 ? 4 : WPR) * kWave, 4) void ln_quant_rows(
     }
     if (t == 0 && live) {
         if (MODE == kFull) a.gamma[row] = gamma;
-        else if (row == 0) a.gamma[0] = gamma;
+        else if (row < a.groups) a.gamma[row] = gamma;  // rows 0 .. groups-1 cover every group
     }
 }
 
-__global__ void fill_u32(uint32_t* p, uint32_t v) { *p = v; }
+__global__ void fill_u32(uint32_t* p, uint32_t v, int n) {
+    if ((int)threadIdx.x < n) p[threadIdx.x] = v;
+}
 
 // rows of up to 32768 elements stay in registers (16 float4 per lane, up to 8 waves)
 bool quant_supported(int64_t K) { return K % 4 == 0 && K / 4 <= 8 * kWave * 16; }
@@ -300,7 +303,7 @@ static void launch_mode(const QuantArgs& a, hipStream_t s) {
     if (!a.per_tensor) {
         ln_quant_rows<WPR, NV, kFull><<<grid, NW * kWave, 0, s>>>(a);
     } else {
-        fill_u32<<<1, 1, 0, s>>>(a.gmax_bits, 0u);
+        fill_u32<<<1, 64, 0, s>>>(a.gmax_bits, 0u, a.groups);
         ln_quant_rows<WPR, NV, kStats><<<grid, NW * kWave, 0, s>>>(a);
         ln_quant_rows<WPR, NV, kApply><<<grid, NW * kWave, 0, s>>>(a);
     }

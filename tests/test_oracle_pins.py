@@ -353,3 +353,118 @@ def test_backward_is_gradient_of_the_ste_surrogate():
         e = np.zeros((N, K)); e[n, k] = h
         fd = (loss(xq, S + e) - loss(xq, S - e)) / (2 * h)
         assert abs(fd - dW[n, k]) <= 1e-6 * max(1, abs(fd))
+
+
+# ---------------------------------------------------------------- Eq. 13-15: groups
+def _rand_layer(seed, M, K, N, w_mean=0.0):
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((M, K)).astype(f32)
+    X[:, : K // 2] += f32(1.5)  # the two halves of a token have different statistics
+    W = (rng.standard_normal((N, K)) * 0.02 + w_mean).astype(f32)
+    W[: N // 2] += f32(0.01)    # and so do the halves of W
+    return X, W
+
+
+def test_groups_of_one_are_the_plain_layer():
+    """Eq. 13-15 with G = 1 are Eq. 3, 5, 12."""
+    X, W = _rand_layer(11, 5, 128, 48)
+    a, b = oracle.forward(X, W), oracle.forward_grouped(X, W, 1, 1)
+    for key in ("codes", "sign", "y", "xhat"):
+        assert np.array_equal(a[key], b[key]), key
+    assert b["alpha"][0, 0] == a["alpha"] and b["beta"][0, 0] == a["beta"]
+
+
+def test_group_parameters_eq13_are_block_means():
+    """Eq. 13: alpha_g = (G/nm) sum W^(g), beta_g = (G/nm) ||W^(g)||_1, per block."""
+    _, W = _rand_layer(12, 1, 96, 64)
+    alpha, beta = oracle.weight_stats_grouped(W, 4, 3)
+    for gn in range(4):
+        for gk in range(3):
+            blk = W[gn * 16:(gn + 1) * 16, gk * 32:(gk + 1) * 32].astype(np.float64)
+            assert abs(float(alpha[gn, gk]) - blk.mean()) <= 1e-9
+            assert abs(float(beta[gn, gk]) - np.abs(blk).mean()) <= 1e-9
+    sign = oracle.binarize_grouped(W, alpha)
+    for gn in range(4):
+        for gk in range(3):
+            blk = W[gn * 16:(gn + 1) * 16, gk * 32:(gk + 1) * 32]
+            ref = np.where(blk > alpha[gn, gk], 1, -1)
+            assert np.array_equal(sign[gn * 16:(gn + 1) * 16, gk * 32:(gk + 1) * 32], ref)
+
+
+@pytest.mark.parametrize("per_tensor", [False, True])
+def test_row_groups_are_independent_layers(per_tensor):
+    """Column-parallel split (groups of output rows): each group's outputs are those of a
+    BitLinear layer that holds only that group's rows - the point of Eq. 13."""
+    X, W = _rand_layer(13, 6, 128, 64)
+    r = oracle.forward_grouped(X, W, groups_n=4, groups_k=1, per_tensor=per_tensor)
+    for g in range(4):
+        solo = oracle.forward(X, W[g * 16:(g + 1) * 16], per_tensor=per_tensor)
+        assert np.array_equal(r["y"][:, g * 16:(g + 1) * 16], solo["y"])
+        assert r["beta"][g, 0] == solo["beta"]
+
+
+@pytest.mark.parametrize("per_tensor", [False, True])
+def test_column_groups_sum_independent_layers(per_tensor):
+    """Row-parallel split (groups of input columns): group LayerNorm (Eq. 15), gamma_g (Eq. 14)
+    and alpha_g, beta_g (Eq. 13) make each slice a BitLinear layer of its own; the output is
+    the sum of their outputs."""
+    X, W = _rand_layer(14, 6, 128, 32)
+    r = oracle.forward_grouped(X, W, groups_n=1, groups_k=4, per_tensor=per_tensor)
+    total = np.zeros((6, 32))
+    for g in range(4):
+        sl = slice(g * 32, (g + 1) * 32)
+        solo = oracle.forward(np.ascontiguousarray(X[:, sl]), np.ascontiguousarray(W[:, sl]),
+                              per_tensor=per_tensor)
+        total += solo["y"].astype(np.float64)
+        assert np.array_equal(r["codes"][:, sl], solo["codes"])
+        assert np.array_equal(r["xhat"][:, sl], solo["xhat"])
+    assert np.abs(r["y64"] - total).max() <= 1e-12
+    # Eq. 15: every slice of a token is normalised on its own
+    xh = r["xhat"].reshape(6, 4, 32).astype(np.float64)
+    assert np.abs(xh.mean(axis=2)).max() < 1e-6
+    assert np.abs(xh.var(axis=2) - 1.0).max() < 1e-4
+
+
+def test_groups_brute_force_tiny():
+    """Eq. 13-15 written out with Python loops on a 4x8 weight, 2 tokens, 2x2 groups."""
+    rng = np.random.default_rng(15)
+    M, K, N, GN, GK = 2, 8, 4, 2, 2
+    X = rng.standard_normal((M, K)).astype(f32)
+    W = (rng.standard_normal((N, K)) * 0.5).astype(f32)
+    eps = 1e-5
+    Ng, Kg = N // GN, K // GK
+    y = np.zeros((M, N))
+    for m in range(M):
+        for gk in range(GK):
+            xs = [float(X[m, gk * Kg + k]) for k in range(Kg)]
+            mu = sum(xs) / Kg
+            var = sum((v - mu) ** 2 for v in xs) / Kg
+            xh = [f32((v - mu) / np.sqrt(var + eps)) for v in xs]
+            gamma = max(abs(v) for v in xh)
+            scale = f32(128.0) / f32(gamma)
+            q = [int(np.clip(np.rint(f32(v) * scale), -128, 127)) for v in xh]
+            for n in range(N):
+                gn = n // Ng
+                blk = [float(W[r, gk * Kg + k]) for r in range(gn * Ng, (gn + 1) * Ng) for k in range(Kg)]
+                alpha = f32(sum(blk) / len(blk))
+                beta = f32(sum(abs(v) for v in blk) / len(blk))
+                acc = sum(q[k] * (1 if W[n, gk * Kg + k] > alpha else -1) for k in range(Kg))
+                y[m, n] += float(f32(acc) * ((beta * f32(gamma)) / f32(128.0)))
+    r = oracle.forward_grouped(X, W, GN, GK, eps=eps)
+    # the fp64 sums of mu/var may differ in the last bit from Python's order: 1e-6 relative
+    assert np.allclose(r["y64"], y, rtol=1e-6, atol=1e-7)
+
+
+def test_groups_do_not_leak():
+    """A change inside one block of W leaves every other block's bits and parameters alone."""
+    X, W = _rand_layer(16, 3, 64, 32)
+    r0 = oracle.forward_grouped(X, W, 2, 2)
+    W2 = W.copy()
+    W2[:16, :32] += f32(0.05)
+    r1 = oracle.forward_grouped(X, W2, 2, 2)
+    assert r0["alpha"][0, 0] != r1["alpha"][0, 0]
+    for gn, gk in ((0, 1), (1, 0), (1, 1)):
+        assert r0["alpha"][gn, gk] == r1["alpha"][gn, gk] and r0["beta"][gn, gk] == r1["beta"][gn, gk]
+    assert np.array_equal(r0["sign"][16:], r1["sign"][16:])
+    assert np.array_equal(r0["sign"][:16, 32:], r1["sign"][:16, 32:])
+    assert np.array_equal(r0["y"][:, 16:], r1["y"][:, 16:])
