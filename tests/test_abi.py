@@ -70,3 +70,32 @@ def test_argument_errors_are_found_on_the_host(lib):
     assert lib.bitlinear_forward(one, 0, 64, one, 16, one, None, None, 1e-5, 0, 0, one, one,
                                  1 << 20, None) == 0
     assert lib.bitlinear_status_string(-2).decode().startswith("bad shape")
+
+
+def test_grouped_host_checks(lib):
+    """Eq. 13-15 entry points: sizes and argument errors, all on the host."""
+    import paper_2310_11453_amd as bl
+    # K-groups are blobs of their own: 8 x [512, 256] slices, each padded to a 512-wide tile
+    assert bl.packed_bytes_grouped(512, 2048, 1, 1) == bl.packed_bytes(512, 2048)
+    assert bl.packed_bytes_grouped(512, 2048, 8, 8) == 8 * bl.packed_bytes(512, 256)
+    assert bl.packed_bytes_grouped(512, 2048, 3, 1) == 0   # 3 does not divide N
+    assert bl.packed_bytes_grouped(512, 96, 1, 2) == 0     # K/groups not a multiple of 32
+    assert bl.packed_bytes_grouped(96, 64, 4, 1) == 0      # 24-row groups are not whole tiles
+    assert bl.packed_bytes_grouped(512, 2048, 65, 1) == 0
+    assert bl.workspace_bytes_grouped(bl.OP_FORWARD, 8, 512, 2048, 2, 4) >= 8 * 2048 + 2 * 8 * 4 * 4
+    assert bl.workspace_bytes_grouped(bl.OP_BACKWARD, 8, 512, 2048, 2, 4) == 0
+    one = ctypes.c_void_p(256)
+    assert lib.bitlinear_pack_weights_grouped(one, 512, 2048, 3, 1, 0, one, one, one, one,
+                                              1 << 20, None) == -2
+    assert lib.bitlinear_pack_weights_grouped(one, 96, 64, 4, 1, 0, one, one, one, one,
+                                              1 << 20, None) == -3
+    assert lib.bitlinear_pack_weights_grouped(None, 512, 2048, 2, 2, 0, one, one, one, one,
+                                              1 << 20, None) == -1
+    assert lib.bitlinear_quant_act_grouped(one, 4, 96, 2, None, None, 1e-5, 0, 0, one, one, None,
+                                           None, one, 1 << 20, None) == -2
+    assert lib.bitlinear_forward_grouped(one, 4, 2048, one, 512, 2, 4, one, None, None, 1e-5, 0,
+                                         2, one, one, 1 << 20, None) == -3  # OUT_ACC_I32 not offered
+    assert lib.bitlinear_forward_grouped(one, 4, 2048, one, 512, 2, 4, one, None, None, 1e-5, 0,
+                                         0, one, one, 8, None) == -4
+    assert lib.bitlinear_forward_grouped(one, 0, 2048, one, 512, 2, 4, one, None, None, 1e-5, 0,
+                                         0, one, one, 1 << 20, None) == 0
