@@ -254,6 +254,63 @@ def main():
                                gbs=nbytes / (t * 1e-3) / 1e9,
                                frac_hbm=nbytes / (t * 1e-3) / 1e9 / HBM_PEAK_GBS, launch=mode))
         decode["layer_stream_1p3b"] = stream
+
+        # One decoding step of the 24-layer stack: LN + quantise + GEMM + dequant through QKV, O,
+        # up and down of every layer, each input being the previous output (the attention and the
+        # non-linearity between them are left out: only their place in the chain matters here).
+        # Four stacks of distinct weights, one HIP graph each, replayed in turn.
+        block = []
+        for Md in (1, 16):
+            h0 = torch.from_numpy(wl.make_activation(Md, 2048, wl.seed_for(1, 50))).to(dev)
+            bufs = {L2.name: torch.empty((Md, L2.N), dtype=torch.float32, device=dev)
+                    for (L2, _, _) in protos}
+            wss = {L2.name: torch.empty(bl.workspace_bytes(bl.OP_FORWARD, Md, L2.N, L2.K),
+                                        dtype=torch.uint8, device=dev) for (L2, _, _) in protos}
+
+            def run_stack(layers24):
+                h = h0
+                for layer in layers24:
+                    for (L2, p2, b2) in layer:
+                        x_in = h if h.shape[1] == L2.K else h.view(-1)[:Md * L2.K].view(Md, L2.K)
+                        h = bl.bitlinear_forward(x_in, p2, L2.N, b2, out=bufs[L2.name],
+                                                 workspace=wss[L2.name])
+                return h
+
+            stacks = [sets[i * 24:(i + 1) * 24] for i in range(4)]
+            ref = run_stack(stacks[0]).clone()
+            torch.cuda.synchronize()
+            mode = "eager launches"
+            runners = [lambda st=st: run_stack(st) for st in stacks]
+            try:
+                graphs = []
+                for st in stacks:
+                    side = torch.cuda.Stream()
+                    side.wait_stream(torch.cuda.current_stream())
+                    with torch.cuda.stream(side):
+                        run_stack(st)
+                    torch.cuda.current_stream().wait_stream(side)
+                    g2 = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g2):
+                        run_stack(st)
+                    graphs.append(g2)
+                graphs[0].replay()
+                torch.cuda.synchronize()
+                if torch.equal(ref, bufs["down"]):
+                    runners, mode = [g2.replay for g2 in graphs], "one HIP graph per stack, replayed"
+            except Exception as exc:
+                mode = f"eager launches (graph capture failed: {type(exc).__name__})"
+
+            def run_all():
+                for r in runners:
+                    r()
+
+            run_all()
+            t = event_ms(run_all, 5, torch) / len(runners)
+            nbytes = sum(gemm_bytes(Md, L2.K, L2.N) + 5 * Md * L2.K for (L2, _, _) in protos) * 24
+            block.append(dict(M=Md, layers=24, launches=24 * 2 * len(protos), us_per_step=t * 1e3,
+                              us_per_launch=t * 1e3 / (24 * 2 * len(protos)),
+                              gbs=nbytes / (t * 1e-3) / 1e9, launch=mode))
+        decode["block_decode_1p3b"] = block
         del sets, protos
         decode["value"] = best["gbs"]
         decode["unit"] = "GB/s"
