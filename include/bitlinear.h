@@ -60,7 +60,8 @@ enum {
 };
 
 /* Operation selector for bitlinear_workspace_bytes. */
-typedef enum { BL_OP_PACK = 0, BL_OP_QUANT = 1, BL_OP_FORWARD = 2, BL_OP_BACKWARD = 3 } bl_op;
+typedef enum { BL_OP_PACK = 0, BL_OP_QUANT = 1, BL_OP_FORWARD = 2, BL_OP_BACKWARD = 3,
+               BL_OP_LN_BACKWARD = 4 } bl_op;
 
 /* host: size in bytes of the packed-weight blob for an [N,K] matrix (0 on bad
  * shape).  The blob is the library's own tiled 1-bit layout (1 bit per weight,
@@ -172,6 +173,25 @@ int bitlinear_backward_ste(const float* dY, int64_t M, int64_t N, int64_t K, con
                            const float* gamma, int granularity, const void* packed,
                            const float* beta, float* dX, float* dW, void* workspace,
                            size_t workspace_bytes, void* stream);
+
+/* Backward of the LayerNorm of Eq. 12 (per K-group: Eq. 15).  With the straight-through
+ * estimator of Section 2.2 the dX of bitlinear_backward_ste is the gradient with respect
+ * to the LayerNorm output; this call carries it to the layer's input and, if asked, to the
+ * LayerNorm gain and bias:
+ *   xn = (x - mu) * rstd,  gh = dXhat * gain
+ *   dX = rstd * (gh - mean(gh) - xn * mean(gh * xn)),  means over a token's K (or K-group)
+ *   dgain[k] = sum_m dXhat[m,k] * xn[m,k],   dbias[k] = sum_m dXhat[m,k]
+ *   dXhat    in   fp32 [M,K]
+ *   X        in   fp32 [M,K], the input the forward call saw
+ *   ln_gain  in   fp32 [K] or NULL;  ln_eps as in the forward call;  groups_k >= 1 as there
+ *   dX       out  fp32 [M,K] or NULL; may be the same buffer as dXhat
+ *   dgain, dbias  out fp32 [K] or NULL; they need the workspace
+ *                 (bitlinear_workspace_bytes_grouped(BL_OP_LN_BACKWARD, M, N, K, 1, groups_k, 0))
+ * K/groups_k up to 16384 (else BL_ERR_UNSUPPORTED). */
+int bitlinear_layernorm_backward(const float* dXhat, const float* X, int64_t M, int64_t K,
+                                 int groups_k, const float* ln_gain, float ln_eps, float* dX,
+                                 float* dgain, float* dbias, void* workspace,
+                                 size_t workspace_bytes, void* stream);
 
 /* host: static description of a status code. */
 const char* bitlinear_status_string(int status);

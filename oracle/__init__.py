@@ -206,6 +206,21 @@ def backward_ste(dY, codes, gamma, sign, beta, per_tensor: bool, rows_dx=None, r
     return dX, dW
 
 
+def layernorm_backward(g, X, eps=1e-5, gain=None, groups: int = 1, want_affine: bool = False):
+    """Backward of Eq. 12 / Eq. 15 (STE: g is the gradient w.r.t. the LayerNorm output).
+    Returns dX, or (dX, dgain, dbias) with want_affine."""
+    g = _f32(g)
+    X = _f32(X)
+    M, K = X.shape
+    assert g.shape == (M, K) and K % groups == 0
+    gain = None if gain is None else _f32(gain)
+    dX = np.empty((M, K), np.float32)
+    dgain = np.empty(K, np.float32) if want_affine else None
+    dbias = np.empty(K, np.float32) if want_affine else None
+    _load().oracle_layernorm_backward(_p(g), _p(X), _i64(M), _i64(K), _i64(groups), _p(gain),
+                                      _c_float(eps), _p(dX), _p(dgain), _p(dbias))
+    return (dX, dgain, dbias) if want_affine else dX
+
 # ---- Eq. 11 end to end ----------------------------------------------------------------
 def forward(X, W, eps=1e-5, per_tensor=False, skip_ln=False, beta_centered=False,
             gain=None, bias=None):

@@ -32,6 +32,7 @@
 #include <math.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <stdlib.h>
 #include <string.h>
 
 #define QB 128.0f
@@ -302,6 +303,67 @@ void oracle_backward_ste(const float *dY, int64_t M, int64_t N, int64_t K,
             }
         }
     }
+}
+
+/* ---- Backward of Eq. 12 (and of its group form, Eq. 15) -------------------- */
+/* Under the straight-through estimator (Section 2.2) the gradient that reaches
+ * the quantiser is the gradient with respect to the LayerNorm output; this is
+ * the chain rule through  xn = (x - mu) * rstd,  out = xn * gain + bias  for each
+ * group of Kg = K/G elements of a token (mu, rstd over the group, biased variance):
+ *   gh  = g * gain                      (g = d loss / d out)
+ *   dx  = rstd * (gh - mean(gh) - xn * mean(gh * xn))
+ *   dgain[k] = sum_m g[m,k] * xn[m,k],   dbias[k] = sum_m g[m,k]
+ * All in fp64, rounded once to fp32.  dX, dgain, dbias may each be NULL. */
+void oracle_layernorm_backward(const float *g, const float *X, int64_t M, int64_t K, int64_t G,
+                               const float *gain, float eps, float *dX, float *dgain,
+                               float *dbias)
+{
+    const int64_t Kg = K / G;
+    double *dg = dgain ? (double *)calloc((size_t)K, sizeof(double)) : NULL;
+    double *db = dbias ? (double *)calloc((size_t)K, sizeof(double)) : NULL;
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t gi = 0; gi < G; ++gi) {
+            const float *x = X + m * K + gi * Kg;
+            const float *gr = g + m * K + gi * Kg;
+            double mu = 0.0;
+            for (int64_t k = 0; k < Kg; ++k)
+                mu += (double)x[k];
+            mu /= (double)Kg;
+            double var = 0.0;
+            for (int64_t k = 0; k < Kg; ++k) {
+                const double d = (double)x[k] - mu;
+                var += d * d;
+            }
+            var /= (double)Kg;
+            const double rstd = 1.0 / sqrt(var + (double)eps);
+            double c1 = 0.0, c2 = 0.0;
+            for (int64_t k = 0; k < Kg; ++k) {
+                const double xn = ((double)x[k] - mu) * rstd;
+                const double gh = (double)gr[k] * (gain ? (double)gain[gi * Kg + k] : 1.0);
+                c1 += gh;
+                c2 += gh * xn;
+                if (dg)
+                    dg[gi * Kg + k] += (double)gr[k] * xn;
+                if (db)
+                    db[gi * Kg + k] += (double)gr[k];
+            }
+            c1 /= (double)Kg;
+            c2 /= (double)Kg;
+            if (dX)
+                for (int64_t k = 0; k < Kg; ++k) {
+                    const double xn = ((double)x[k] - mu) * rstd;
+                    const double gh = (double)gr[k] * (gain ? (double)gain[gi * Kg + k] : 1.0);
+                    dX[m * K + gi * Kg + k] = (float)(rstd * (gh - c1 - xn * c2));
+                }
+        }
+    for (int64_t k = 0; k < K; ++k) {
+        if (dg)
+            dgain[k] = (float)dg[k];
+        if (db)
+            dbias[k] = (float)db[k];
+    }
+    free(dg);
+    free(db);
 }
 
 /* Number of OpenMP threads the parallel loops above will use. */

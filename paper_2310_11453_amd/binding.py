@@ -17,7 +17,7 @@ LIB_PATH = _PKG / "libbitlinear.so"
 BL_OK = 0
 GAMMA_PER_TOKEN, GAMMA_PER_TENSOR = 0, 1
 FLAG_SKIP_LN, FLAG_OUT_ACC_I32, FLAG_BETA_CENTERED = 1, 2, 4
-OP_PACK, OP_QUANT, OP_FORWARD, OP_BACKWARD = 0, 1, 2, 3
+OP_PACK, OP_QUANT, OP_FORWARD, OP_BACKWARD, OP_LN_BACKWARD = 0, 1, 2, 3, 4
 
 EXPORTS = (
     "bitlinear_packed_bytes", "bitlinear_workspace_bytes", "bitlinear_pack_weights",
@@ -25,7 +25,7 @@ EXPORTS = (
     "bitlinear_forward", "bitlinear_backward_ste", "bitlinear_status_string",
     "bitlinear_packed_bytes_grouped", "bitlinear_workspace_bytes_grouped",
     "bitlinear_pack_weights_grouped", "bitlinear_packed_to_canonical_grouped",
-    "bitlinear_quant_act_grouped", "bitlinear_forward_grouped",
+    "bitlinear_quant_act_grouped", "bitlinear_forward_grouped", "bitlinear_layernorm_backward",
 )
 
 _lib = None
@@ -75,6 +75,8 @@ def load_library() -> ctypes.CDLL:
     lib.bitlinear_forward_grouped.restype = ci
     lib.bitlinear_forward_grouped.argtypes = [vp, i64, i64, vp, i64, ci, ci, vp, vp, vp, cf, ci, u32,
                                               vp, vp, sz, vp]
+    lib.bitlinear_layernorm_backward.restype = ci
+    lib.bitlinear_layernorm_backward.argtypes = [vp, vp, i64, i64, ci, vp, cf, vp, vp, vp, vp, sz, vp]
     lib.bitlinear_status_string.restype = ctypes.c_char_p
     lib.bitlinear_status_string.argtypes = [ci]
     _lib = lib
@@ -289,3 +291,20 @@ def bitlinear_forward_grouped(X: torch.Tensor, packed: torch.Tensor, N: int, bet
         ln_eps, _gran(per_tensor), flags, _ptr(out), _ptr(ws), ws.numel(), _stream()),
         "bitlinear_forward_grouped")
     return out
+
+
+def bitlinear_layernorm_backward(dXhat: torch.Tensor, X: torch.Tensor, ln_eps: float = 1e-5,
+                                 ln_gain=None, groups_k: int = 1, want_affine: bool = False,
+                                 out: torch.Tensor | None = None):
+    """Backward of Eq. 12 / Eq. 15.  Returns dX, or (dX, dgain, dbias) with want_affine."""
+    M, K = X.shape
+    dev = X.device
+    dX = out if out is not None else torch.empty((M, K), dtype=torch.float32, device=dev)
+    dgain = torch.empty(K, dtype=torch.float32, device=dev) if want_affine else None
+    dbias = torch.empty(K, dtype=torch.float32, device=dev) if want_affine else None
+    ws = _workspace(workspace_bytes_grouped(OP_LN_BACKWARD, M, 16, K, 1, groups_k), dev)
+    _check(load_library().bitlinear_layernorm_backward(
+        _ptr(dXhat, torch.float32), _ptr(X, torch.float32), M, K, groups_k,
+        _ptr(ln_gain, torch.float32), ln_eps, _ptr(dX, torch.float32), _ptr(dgain), _ptr(dbias),
+        _ptr(ws), ws.numel(), _stream()), "bitlinear_layernorm_backward")
+    return (dX, dgain, dbias) if want_affine else dX

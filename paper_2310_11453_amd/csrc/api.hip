@@ -83,6 +83,19 @@ ForwardWs forward_ws_grouped(int64_t M, int64_t K, int groups_k, int granularity
     w.total = off;
     return w;
 }
+struct LnBackwardWs {
+    size_t rowstats, partials, total;
+};
+LnBackwardWs ln_backward_ws(int64_t M, int64_t K, int groups_k) {
+    LnBackwardWs w{};
+    size_t off = 0;
+    w.rowstats = off;
+    off += align256((size_t)M * groups_k * 16);
+    w.partials = off;
+    off += align256((size_t)ln_backward_chunks(M) * 2 * (size_t)K * 8);
+    w.total = off;
+    return w;
+}
 void plain_fields(GemmArgs& a) {
     a.ldq = a.K;
     a.gstride = 1;
@@ -117,6 +130,9 @@ size_t bitlinear_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int gr
         case BL_OP_BACKWARD:
             if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return 0;
             return backward_workspace_bytes(M, N, K) + 256;
+        case BL_OP_LN_BACKWARD:
+            if (M < 0 || M > kMaxDim || K <= 0 || K > kMaxDim || K % 32) return 0;
+            return ln_backward_ws(M, K, 1).total;
         default:
             return 0;
     }
@@ -224,6 +240,8 @@ size_t bitlinear_workspace_bytes_grouped(int op, int64_t M, int64_t N, int64_t K
             return quant_ws_grouped(M, groups_k, granularity).total;
         case BL_OP_FORWARD:
             return forward_ws_grouped(M, K, groups_k, granularity).total;
+        case BL_OP_LN_BACKWARD:
+            return ln_backward_ws(M, K, groups_k).total;
         default:
             return 0;
     }
@@ -355,6 +373,28 @@ int bitlinear_backward_ste(const float* dY, int64_t M, int64_t N, int64_t K, con
     a.packed = (const uint32_t*)packed; a.beta = beta; a.dX = dX; a.dW = dW;
     a.workspace = (void*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255);
     return check_hip(launch_backward(a, (hipStream_t)stream));
+}
+
+int bitlinear_layernorm_backward(const float* dXhat, const float* X, int64_t M, int64_t K,
+                                 int groups_k, const float* ln_gain, float ln_eps, float* dX,
+                                 float* dgain, float* dbias, void* workspace,
+                                 size_t workspace_bytes, void* stream) {
+    if (M < 0 || M > kMaxDim || K <= 0 || K > kMaxDim || K % 32) return BL_ERR_SHAPE;
+    if (groups_k < 1 || groups_k > kMaxGroups || K % groups_k || (K / groups_k) % 32)
+        return BL_ERR_SHAPE;
+    const int64_t Kg = K / groups_k;
+    if (!ln_backward_supported(Kg) || M * groups_k > kMaxDim) return BL_ERR_UNSUPPORTED;
+    if (M == 0 || (!dX && !dgain && !dbias)) return BL_OK;
+    if (!dXhat || !X) return BL_ERR_NULL;
+    const LnBackwardWs ws = ln_backward_ws(M, K, groups_k);
+    const bool affine = dgain || dbias;
+    if (affine && (!workspace || workspace_bytes < ws.total)) return BL_ERR_WORKSPACE;
+    LnBackwardArgs a{};
+    a.g = dXhat; a.X = X; a.M = M * groups_k; a.K = Kg; a.gain = ln_gain; a.eps = ln_eps;
+    a.groups = groups_k; a.dX = dX;
+    a.rowstats = affine ? (double*)((char*)workspace + ws.rowstats) : nullptr;
+    double* partials = affine ? (double*)((char*)workspace + ws.partials) : nullptr;
+    return check_hip(launch_ln_backward(a, dgain, dbias, partials, (hipStream_t)stream));
 }
 
 const char* bitlinear_status_string(int status) {

@@ -75,4 +75,20 @@ struct BackwardArgs {
 size_t backward_workspace_bytes(int64_t M, int64_t N, int64_t K);
 hipError_t launch_backward(const BackwardArgs& a, hipStream_t s);
 
+// ln_backward.hip
+struct LnBackwardArgs {
+    const float* g;    // gradient w.r.t. the LayerNorm output, [M][K]
+    const float* X;    // the layer's input, [M][K]
+    int64_t M, K;      // rows of K elements: tokens * groups rows, K = elements per group
+    const float* gain; // [groups * K] or nullptr
+    float eps;
+    int groups;        // row r belongs to K-group r % groups
+    float* dX;         // [M][K] or nullptr (statistics only)
+    double* rowstats;  // [M][2] = (mean, rstd), or nullptr
+};
+bool ln_backward_supported(int64_t K);
+int ln_backward_chunks(int64_t tokens);
+hipError_t launch_ln_backward(const LnBackwardArgs& a, float* dgain, float* dbias, double* partials,
+                              hipStream_t s);
+
 }  // namespace bl

@@ -468,3 +468,56 @@ def test_groups_do_not_leak():
     assert np.array_equal(r0["sign"][16:], r1["sign"][16:])
     assert np.array_equal(r0["sign"][:16, 32:], r1["sign"][:16, 32:])
     assert np.array_equal(r0["y"][:, 16:], r1["y"][:, 16:])
+
+
+# ---------------------------------------------------------------- backward of Eq. 12 / Eq. 15
+@pytest.mark.parametrize("groups", [1, 4])
+def test_layernorm_backward_matches_autograd(groups):
+    """Chain rule through Eq. 12 (groups = 1: layer_norm; groups > 1: group_norm, Eq. 15),
+    against torch's fp64 autograd of its own LayerNorm / GroupNorm."""
+    rng = np.random.default_rng(21)
+    M, K = 7, 96
+    X = (rng.standard_normal((M, K)) * 2 + 0.5).astype(f32)
+    g = rng.standard_normal((M, K)).astype(f32)
+    gain = (1 + 0.2 * rng.standard_normal(K)).astype(f32)
+    dX, dgain, dbias = oracle.layernorm_backward(g, X, gain=gain, groups=groups, want_affine=True)
+    xt = torch.tensor(X, dtype=torch.float64, requires_grad=True)
+    gt = torch.tensor(gain, dtype=torch.float64, requires_grad=True)
+    bt = torch.zeros(K, dtype=torch.float64, requires_grad=True)
+    if groups == 1:
+        out = torch.nn.functional.layer_norm(xt, (K,), gt, bt, 1e-5)
+    else:
+        out = torch.nn.functional.group_norm(xt.reshape(M, groups, K // groups), groups, eps=1e-5)
+        out = out.reshape(M, K) * gt + bt
+    out.backward(torch.tensor(g, dtype=torch.float64))
+    assert np.abs(dX - xt.grad.numpy()).max() <= 1e-6
+    assert np.abs(dgain - gt.grad.numpy()).max() <= 2e-6
+    assert np.abs(dbias - bt.grad.numpy()).max() <= 2e-6
+
+
+def test_layernorm_backward_finite_differences_and_projections():
+    """dX is the derivative of sum(g * LN(x)) (central differences on the oracle's forward in
+    fp64-friendly sizes), and it is orthogonal to the two directions LN removes: the constant
+    vector and the normalised row itself."""
+    rng = np.random.default_rng(22)
+    M, K = 3, 32
+    X = rng.standard_normal((M, K)).astype(f32)
+    g = rng.standard_normal((M, K)).astype(f32)
+    dX = oracle.layernorm_backward(g, X).astype(np.float64)
+
+    def loss(Xd):
+        mu = Xd.mean(axis=1, keepdims=True)
+        var = Xd.var(axis=1, keepdims=True)
+        return float((g.astype(np.float64) * (Xd - mu) / np.sqrt(var + 1e-5)).sum())
+
+    Xd = X.astype(np.float64)
+    h = 1e-5
+    for (m, k) in [(0, 0), (1, 7), (2, 31), (0, 16)]:
+        e = np.zeros_like(Xd)
+        e[m, k] = h
+        fd = (loss(Xd + e) - loss(Xd - e)) / (2 * h)
+        assert abs(fd - dX[m, k]) <= 1e-5 * max(1.0, abs(fd))
+    xn = oracle.layernorm(X).astype(np.float64)
+    assert np.abs(dX.sum(axis=1)).max() <= 1e-5
+    # exact only for eps = 0: the residual is rstd * sum(g * xn) * eps / (var + eps) ~ 1e-4 here
+    assert np.abs((dX * xn).sum(axis=1)).max() <= 1e-3
