@@ -61,7 +61,7 @@ enum {
 
 /* Operation selector for bitlinear_workspace_bytes. */
 typedef enum { BL_OP_PACK = 0, BL_OP_QUANT = 1, BL_OP_FORWARD = 2, BL_OP_BACKWARD = 3,
-               BL_OP_LN_BACKWARD = 4 } bl_op;
+               BL_OP_LN_BACKWARD = 4, BL_OP_FORWARD_NONNEG = 5 } bl_op;
 
 /* host: size in bytes of the packed-weight blob for an [N,K] matrix (0 on bad
  * shape).  The blob is the library's own tiled 1-bit layout (1 bit per weight,
@@ -173,6 +173,35 @@ int bitlinear_backward_ste(const float* dY, int64_t M, int64_t N, int64_t K, con
                            const float* gamma, int granularity, const void* packed,
                            const float* beta, float* dX, float* dW, void* workspace,
                            size_t workspace_bytes, void* stream);
+
+/* ---- The non-negative quantiser of Eq. 6 ----------------------------------------------
+ * For inputs of non-linear functions the paper shifts the activations by their minimum and
+ * scales them into [0, Q_b]:  x~ = Clip((x - eta) * Q_b / gamma, eps, Q_b - eps), eta = min x.
+ * Read here as: gamma = max(x - eta) (the value that makes the range [0, Q_b]), floored at
+ * 1e-5; codes = clamp(rne((x^ - eta) * (128 / gamma)), 0, 127), x^ the LayerNorm output.
+ * The paper does not write the matching dequantisation; putting x ~ x~ gamma/Q_b + eta into
+ * Eq. 11 gives
+ *   Y[m,n] = acc[m,n] * (beta * gamma_m / 128) + (beta * eta_m) * wsum[n],
+ *   wsum[n] = sum_k W~[n,k]   (bitlinear_weight_rowsums, once per weight).
+ * Per token only (granularity BL_GAMMA_PER_TOKEN, else BL_ERR_UNSUPPORTED).
+ *   eta   out/in  fp32 [M];   wsum  out/in  int32 [N];   the rest as in the functions above.
+ * bitlinear_forward_nonneg needs the workspace of
+ * bitlinear_workspace_bytes(BL_OP_FORWARD_NONNEG, M, N, K, BL_GAMMA_PER_TOKEN, 0). */
+int bitlinear_weight_rowsums(const void* packed, int64_t N, int64_t K, int32_t* wsum,
+                             void* stream);
+int bitlinear_quant_act_nonneg(const float* X, int64_t M, int64_t K, const float* ln_gain,
+                               const float* ln_bias, float ln_eps, int granularity,
+                               unsigned flags, int8_t* codes, float* gamma, float* eta,
+                               int32_t* rowsum, float* xhat_dump, void* workspace,
+                               size_t workspace_bytes, void* stream);
+int bitlinear_matmul_nonneg(const int8_t* codes, const float* gamma, const float* eta,
+                            const int32_t* rowsum, int64_t M, int64_t K, const void* packed,
+                            int64_t N, const float* beta, const int32_t* wsum, int granularity,
+                            unsigned flags, float* Y, void* stream);
+int bitlinear_forward_nonneg(const float* X, int64_t M, int64_t K, const void* packed, int64_t N,
+                             const float* beta, const int32_t* wsum, const float* ln_gain,
+                             const float* ln_bias, float ln_eps, int granularity, unsigned flags,
+                             float* Y, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Backward of the LayerNorm of Eq. 12 (per K-group: Eq. 15).  With the straight-through
  * estimator of Section 2.2 the dX of bitlinear_backward_ste is the gradient with respect

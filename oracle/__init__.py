@@ -299,3 +299,57 @@ def forward_grouped(X, W, groups_n: int = 1, groups_k: int = 1, eps=1e-5, per_te
     return dict(alpha=alpha, beta=beta, sign=sign, words=pack_canonical(sign), xhat=xhat,
                 gamma=gam if not per_tensor else gam.reshape(groups_k), codes=codes, acc=accs,
                 y=ysum.astype(np.float32), y64=ysum)
+
+
+# ---- Eq. 6: the non-negative quantiser ------------------------------------------------
+def minmax_nonneg(xhat, per_tensor: bool = False):
+    """eta = min, gamma = max(x - eta) floored at 1e-5; [M] each per token, [1] per tensor."""
+    xhat = _f32(xhat)
+    M, K = xhat.shape
+    n = 1 if per_tensor else M
+    eta = np.empty(n, np.float32)
+    gamma = np.empty(n, np.float32)
+    _load().oracle_minmax_nonneg(_p(xhat), _i64(M), _i64(K), _c_int(int(per_tensor)), _p(eta),
+                                 _p(gamma))
+    return eta, gamma
+
+
+def quantize_nonneg(xhat, eta, gamma, per_tensor: bool = False):
+    xhat = _f32(xhat)
+    M, K = xhat.shape
+    codes = np.empty((M, K), np.int8)
+    _load().oracle_quantize_nonneg(_p(xhat), _i64(M), _i64(K), _c_int(int(per_tensor)),
+                                   _p(_f32(eta)), _p(_f32(gamma)), _p(codes))
+    return codes
+
+
+def weight_rowsum(sign):
+    sign = np.ascontiguousarray(sign, dtype=np.int8)
+    N, K = sign.shape
+    out = np.empty(N, np.int32)
+    _load().oracle_weight_rowsum(_p(sign), _i64(N), _i64(K), _p(out))
+    return out
+
+
+def dequant_nonneg(acc, gamma, eta, beta, wsum, per_tensor: bool = False):
+    acc = np.ascontiguousarray(acc, dtype=np.int32)
+    M, N = acc.shape
+    Y = np.empty((M, N), np.float32)
+    _load().oracle_dequant_nonneg(_p(acc), _i64(M), _i64(N), _p(_f32(gamma)), _p(_f32(eta)),
+                                  _i64(0 if per_tensor else 1), _c_float(float(beta)),
+                                  _p(np.ascontiguousarray(wsum, dtype=np.int32)), _p(Y))
+    return Y
+
+
+def forward_nonneg(X, W, eps=1e-5, per_tensor=False, skip_ln=False, gain=None, bias=None):
+    """BitLinear forward with the quantiser of Eq. 6 in place of Eq. 4."""
+    alpha, beta = weight_stats(W)
+    sign = binarize(W, alpha)
+    xhat = _f32(X) if skip_ln else layernorm(X, eps, gain, bias)
+    eta, gamma = minmax_nonneg(xhat, per_tensor)
+    codes = quantize_nonneg(xhat, eta, gamma, per_tensor)
+    acc = matmul_i32(codes, sign)
+    wsum = weight_rowsum(sign)
+    y = dequant_nonneg(acc, gamma, eta, beta, wsum, per_tensor)
+    return dict(alpha=alpha, beta=beta, sign=sign, xhat=xhat, eta=eta, gamma=gamma, codes=codes,
+                acc=acc, wsum=wsum, y=y)

@@ -171,6 +171,85 @@ void oracle_quantize(const float *xhat, int64_t M, int64_t K, int64_t G, int gra
         }
 }
 
+/* ---- Eq. 6: non-negative activation quantiser ------------------------------ */
+/* x~ = Clip((x - eta) * Q_b / gamma, eps, Q_b - eps), eta = min x.  The text says the values
+ * are scaled into [0, Q_b], which fixes gamma as the largest shifted value, max(x - eta)
+ * (with gamma = ||x||_inf of the unshifted input the range would be missed).  As for Eq. 4:
+ * 128 / gamma is one fp32 division, the shift and the scaling are one fp32 operation each,
+ * round half to even, integer clamp to [0, 127]; gamma is floored at 1e-5.
+ * granularity 0: eta[m], gamma[m] per token; 1: eta[0], gamma[0] over the whole tensor. */
+void oracle_minmax_nonneg(const float *xhat, int64_t M, int64_t K, int granularity, float *eta,
+                          float *gamma)
+{
+    const int64_t cnt = granularity == 0 ? M : 1;
+    for (int64_t i = 0; i < cnt; ++i) {
+        const int64_t r0 = granularity == 0 ? i : 0, r1 = granularity == 0 ? i + 1 : M;
+        float lo = xhat[r0 * K], hi = xhat[r0 * K];
+        for (int64_t m = r0; m < r1; ++m)
+            for (int64_t k = 0; k < K; ++k) {
+                const float v = xhat[m * K + k];
+                if (v < lo)
+                    lo = v;
+                if (v > hi)
+                    hi = v;
+            }
+        float g = hi - lo;
+        if (!(g >= 1e-5f))
+            g = 1e-5f;
+        eta[i] = lo;
+        gamma[i] = g;
+    }
+}
+
+void oracle_quantize_nonneg(const float *xhat, int64_t M, int64_t K, int granularity,
+                            const float *eta, const float *gamma, int8_t *codes)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m) {
+        const float e = granularity == 0 ? eta[m] : eta[0];
+        const float scale = QB / (granularity == 0 ? gamma[m] : gamma[0]);
+        for (int64_t k = 0; k < K; ++k) {
+            const float d = xhat[m * K + k] - e;
+            float r = nearbyintf(d * scale);
+            if (r < 0.0f)
+                r = 0.0f;
+            if (r > 127.0f)
+                r = 127.0f;
+            codes[m * K + k] = (int8_t)r;
+        }
+    }
+}
+
+/* wsum[n] = sum_k sign[n,k]: what a constant shift of the activations contributes to output n */
+void oracle_weight_rowsum(const int8_t *sign, int64_t N, int64_t K, int32_t *wsum)
+{
+    for (int64_t n = 0; n < N; ++n) {
+        int32_t s = 0;
+        for (int64_t k = 0; k < K; ++k)
+            s += sign[n * K + k];
+        wsum[n] = s;
+    }
+}
+
+/* Dequantisation for Eq. 6.  The paper does not write it; it follows from Eq. 11 once
+ * x ~ x~ * gamma / Q_b + eta is put back into y = beta * sum_k s_nk x_k:
+ *   y[m,n] = acc[m,n] * (beta * gamma_m / 128)  +  (beta * eta_m) * wsum[n]
+ * each product and the sum one fp32 operation, in this order. */
+void oracle_dequant_nonneg(const int32_t *acc, int64_t M, int64_t N, const float *gamma,
+                           const float *eta, int64_t stride, float beta, const int32_t *wsum,
+                           float *Y)
+{
+    for (int64_t m = 0; m < M; ++m) {
+        const float s = (beta * gamma[m * stride]) / QB;
+        const float be = beta * eta[m * stride];
+        for (int64_t n = 0; n < N; ++n) {
+            const float t1 = (float)acc[m * N + n] * s;
+            const float t2 = be * (float)wsum[n];
+            Y[m * N + n] = t1 + t2;
+        }
+    }
+}
+
 /* ---- Eq. 7: y = W~ x~ in integers ---------------------------------------- */
 /* acc[m,n] = sum_{k in [k0,k1)} codes[m,k] * sign[n,k], int32.
  * (k0,k1) = (0,K) for the plain layer; a K-group of Eq. 13-15 passes its slice. */

@@ -17,7 +17,7 @@ LIB_PATH = _PKG / "libbitlinear.so"
 BL_OK = 0
 GAMMA_PER_TOKEN, GAMMA_PER_TENSOR = 0, 1
 FLAG_SKIP_LN, FLAG_OUT_ACC_I32, FLAG_BETA_CENTERED = 1, 2, 4
-OP_PACK, OP_QUANT, OP_FORWARD, OP_BACKWARD, OP_LN_BACKWARD = 0, 1, 2, 3, 4
+OP_PACK, OP_QUANT, OP_FORWARD, OP_BACKWARD, OP_LN_BACKWARD, OP_FORWARD_NONNEG = 0, 1, 2, 3, 4, 5
 
 EXPORTS = (
     "bitlinear_packed_bytes", "bitlinear_workspace_bytes", "bitlinear_pack_weights",
@@ -26,6 +26,8 @@ EXPORTS = (
     "bitlinear_packed_bytes_grouped", "bitlinear_workspace_bytes_grouped",
     "bitlinear_pack_weights_grouped", "bitlinear_packed_to_canonical_grouped",
     "bitlinear_quant_act_grouped", "bitlinear_forward_grouped", "bitlinear_layernorm_backward",
+    "bitlinear_weight_rowsums", "bitlinear_quant_act_nonneg", "bitlinear_matmul_nonneg",
+    "bitlinear_forward_nonneg",
 )
 
 _lib = None
@@ -77,6 +79,16 @@ def load_library() -> ctypes.CDLL:
                                               vp, vp, sz, vp]
     lib.bitlinear_layernorm_backward.restype = ci
     lib.bitlinear_layernorm_backward.argtypes = [vp, vp, i64, i64, ci, vp, cf, vp, vp, vp, vp, sz, vp]
+    lib.bitlinear_weight_rowsums.restype = ci
+    lib.bitlinear_weight_rowsums.argtypes = [vp, i64, i64, vp, vp]
+    lib.bitlinear_quant_act_nonneg.restype = ci
+    lib.bitlinear_quant_act_nonneg.argtypes = [vp, i64, i64, vp, vp, cf, ci, u32, vp, vp, vp, vp, vp,
+                                               vp, sz, vp]
+    lib.bitlinear_matmul_nonneg.restype = ci
+    lib.bitlinear_matmul_nonneg.argtypes = [vp, vp, vp, vp, i64, i64, vp, i64, vp, vp, ci, u32, vp, vp]
+    lib.bitlinear_forward_nonneg.restype = ci
+    lib.bitlinear_forward_nonneg.argtypes = [vp, i64, i64, vp, i64, vp, vp, vp, vp, cf, ci, u32, vp,
+                                             vp, sz, vp]
     lib.bitlinear_status_string.restype = ctypes.c_char_p
     lib.bitlinear_status_string.argtypes = [ci]
     _lib = lib
@@ -308,3 +320,58 @@ def bitlinear_layernorm_backward(dXhat: torch.Tensor, X: torch.Tensor, ln_eps: f
         _ptr(ln_gain, torch.float32), ln_eps, _ptr(dX, torch.float32), _ptr(dgain), _ptr(dbias),
         _ptr(ws), ws.numel(), _stream()), "bitlinear_layernorm_backward")
     return (dX, dgain, dbias) if want_affine else dX
+
+
+# ---- Eq. 6: the non-negative quantiser --------------------------------------------------
+def bitlinear_weight_rowsums(packed: torch.Tensor, N: int, K: int) -> torch.Tensor:
+    """wsum[n] = sum_k W~[n,k], int32 [N]."""
+    out = torch.empty(N, dtype=torch.int32, device=packed.device)
+    _check(load_library().bitlinear_weight_rowsums(_ptr(packed), N, K, _ptr(out), _stream()),
+           "bitlinear_weight_rowsums")
+    return out
+
+
+def bitlinear_quant_act_nonneg(X: torch.Tensor, ln_eps: float = 1e-5, flags: int = 0, ln_gain=None,
+                               ln_bias=None, want_xhat: bool = False):
+    """Eq. 12 + Eq. 6.  Returns (codes in 0..127, gamma [M], eta [M], rowsum [M], xhat or None)."""
+    M, K = X.shape
+    dev = X.device
+    codes = torch.empty((M, K), dtype=torch.int8, device=dev)
+    gamma = torch.empty(max(M, 1), dtype=torch.float32, device=dev)
+    eta = torch.empty(max(M, 1), dtype=torch.float32, device=dev)
+    rowsum = torch.empty(max(M, 1), dtype=torch.int32, device=dev)
+    xhat = torch.empty((M, K), dtype=torch.float32, device=dev) if want_xhat else None
+    _check(load_library().bitlinear_quant_act_nonneg(
+        _ptr(X, torch.float32), M, K, _ptr(ln_gain, torch.float32), _ptr(ln_bias, torch.float32),
+        ln_eps, GAMMA_PER_TOKEN, flags, _ptr(codes), _ptr(gamma), _ptr(eta), _ptr(rowsum),
+        _ptr(xhat), None, 0, _stream()), "bitlinear_quant_act_nonneg")
+    return codes, gamma, eta, rowsum, xhat
+
+
+def bitlinear_matmul_nonneg(codes, gamma, eta, rowsum, packed, N: int, beta, wsum,
+                            out: torch.Tensor | None = None) -> torch.Tensor:
+    M, K = codes.shape
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=codes.device)
+    _check(load_library().bitlinear_matmul_nonneg(
+        _ptr(codes, torch.int8), _ptr(gamma, torch.float32), _ptr(eta, torch.float32),
+        _ptr(rowsum, torch.int32), M, K, _ptr(packed), N, _ptr(beta, torch.float32),
+        _ptr(wsum, torch.int32), GAMMA_PER_TOKEN, 0, _ptr(out), _stream()),
+        "bitlinear_matmul_nonneg")
+    return out
+
+
+def bitlinear_forward_nonneg(X: torch.Tensor, packed: torch.Tensor, N: int, beta: torch.Tensor,
+                             wsum: torch.Tensor, ln_eps: float = 1e-5, flags: int = 0, ln_gain=None,
+                             ln_bias=None, out: torch.Tensor | None = None) -> torch.Tensor:
+    """Eq. 11 with the quantiser of Eq. 6."""
+    M, K = X.shape
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=X.device)
+    ws = _workspace(workspace_bytes(OP_FORWARD_NONNEG, M, N, K), X.device)
+    _check(load_library().bitlinear_forward_nonneg(
+        _ptr(X, torch.float32), M, K, _ptr(packed), N, _ptr(beta, torch.float32),
+        _ptr(wsum, torch.int32), _ptr(ln_gain, torch.float32), _ptr(ln_bias, torch.float32), ln_eps,
+        GAMMA_PER_TOKEN, flags, _ptr(out), _ptr(ws), ws.numel(), _stream()),
+        "bitlinear_forward_nonneg")
+    return out

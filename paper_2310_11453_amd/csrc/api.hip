@@ -96,6 +96,20 @@ LnBackwardWs ln_backward_ws(int64_t M, int64_t K, int groups_k) {
     w.total = off;
     return w;
 }
+// codes, then gamma and eta side by side, then row sums
+ForwardWs forward_ws_nonneg(int64_t M, int64_t K) {
+    ForwardWs w{};
+    size_t off = 0;
+    w.codes = off;
+    off += align256((size_t)M * (size_t)K);
+    w.gamma = off;
+    off += align256((size_t)M * 8);
+    w.rowsum = off;
+    off += align256((size_t)M * 4);
+    w.quant = off;
+    w.total = off;
+    return w;
+}
 void plain_fields(GemmArgs& a) {
     a.ldq = a.K;
     a.gstride = 1;
@@ -133,6 +147,9 @@ size_t bitlinear_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int gr
         case BL_OP_LN_BACKWARD:
             if (M < 0 || M > kMaxDim || K <= 0 || K > kMaxDim || K % 32) return 0;
             return ln_backward_ws(M, K, 1).total;
+        case BL_OP_FORWARD_NONNEG:
+            if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return 0;
+            return forward_ws_nonneg(M, K).total;
         default:
             return 0;
     }
@@ -373,6 +390,83 @@ int bitlinear_backward_ste(const float* dY, int64_t M, int64_t N, int64_t K, con
     a.packed = (const uint32_t*)packed; a.beta = beta; a.dX = dX; a.dW = dW;
     a.workspace = (void*)(((uintptr_t)workspace + 255) & ~(uintptr_t)255);
     return check_hip(launch_backward(a, (hipStream_t)stream));
+}
+
+// ---- the non-negative quantiser (Eq. 6) ------------------------------------------------
+
+int bitlinear_weight_rowsums(const void* packed, int64_t N, int64_t K, int32_t* wsum,
+                             void* stream) {
+    if (!shape_ok(N, K)) return BL_ERR_SHAPE;
+    if (!packed || !wsum) return BL_ERR_NULL;
+    return check_hip(launch_weight_rowsums((const uint32_t*)packed, N, K, wsum,
+                                           (hipStream_t)stream));
+}
+
+int bitlinear_quant_act_nonneg(const float* X, int64_t M, int64_t K, const float* ln_gain,
+                               const float* ln_bias, float ln_eps, int granularity,
+                               unsigned flags, int8_t* codes, float* gamma, float* eta,
+                               int32_t* rowsum, float* xhat_dump, void* workspace,
+                               size_t workspace_bytes, void* stream) {
+    (void)workspace;
+    (void)workspace_bytes;
+    if (M < 0 || M > kMaxDim || K <= 0 || K > kMaxDim || K % 32) return BL_ERR_SHAPE;
+    if (granularity != BL_GAMMA_PER_TOKEN || (flags & ~BL_FLAG_SKIP_LN)) return BL_ERR_UNSUPPORTED;
+    if (!quant_supported(K)) return BL_ERR_UNSUPPORTED;
+    if (M == 0) return BL_OK;
+    if (!X || !codes || !gamma || !eta) return BL_ERR_NULL;
+    QuantArgs a{};
+    a.X = X; a.M = M; a.K = K; a.gain = ln_gain; a.bias = ln_bias; a.eps = ln_eps;
+    a.skip_ln = (flags & BL_FLAG_SKIP_LN) != 0;
+    a.per_tensor = false;
+    a.codes = codes; a.gamma = gamma; a.rowsum = rowsum; a.xhat_dump = xhat_dump;
+    a.groups = 1;
+    a.nonneg = true;
+    a.eta = eta;
+    return check_hip(launch_quant(a, (hipStream_t)stream));
+}
+
+int bitlinear_matmul_nonneg(const int8_t* codes, const float* gamma, const float* eta,
+                            const int32_t* rowsum, int64_t M, int64_t K, const void* packed,
+                            int64_t N, const float* beta, const int32_t* wsum, int granularity,
+                            unsigned flags, float* Y, void* stream) {
+    if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return BL_ERR_SHAPE;
+    if (granularity != BL_GAMMA_PER_TOKEN || flags) return BL_ERR_UNSUPPORTED;
+    if (M == 0) return BL_OK;
+    if (!codes || !gamma || !eta || !rowsum || !packed || !beta || !wsum || !Y) return BL_ERR_NULL;
+    GemmArgs a{};
+    a.codes = codes; a.gamma = gamma; a.rowsum = rowsum; a.M = M; a.K = K; a.N = N;
+    a.packed = (const uint32_t*)packed; a.beta = beta;
+    a.per_tensor = false;
+    a.out_acc = false;
+    a.Y = Y;
+    plain_fields(a);
+    a.eta = eta;
+    a.wsum = wsum;
+    if (M <= 16) return check_hip(launch_gemm_decode(a, (hipStream_t)stream));
+    return check_hip(launch_gemm_prefill(a, (hipStream_t)stream));
+}
+
+int bitlinear_forward_nonneg(const float* X, int64_t M, int64_t K, const void* packed, int64_t N,
+                             const float* beta, const int32_t* wsum, const float* ln_gain,
+                             const float* ln_bias, float ln_eps, int granularity, unsigned flags,
+                             float* Y, void* workspace, size_t workspace_bytes, void* stream) {
+    if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return BL_ERR_SHAPE;
+    if (granularity != BL_GAMMA_PER_TOKEN || (flags & ~BL_FLAG_SKIP_LN)) return BL_ERR_UNSUPPORTED;
+    if (M == 0) return BL_OK;
+    if (!X || !packed || !beta || !wsum || !Y) return BL_ERR_NULL;
+    const ForwardWs ws = forward_ws_nonneg(M, K);
+    if (!workspace || workspace_bytes < ws.total) return BL_ERR_WORKSPACE;
+    char* base = (char*)workspace;
+    int8_t* codes = (int8_t*)(base + ws.codes);
+    float* gamma = (float*)(base + ws.gamma);
+    float* eta = gamma + M;
+    int32_t* rowsum = (int32_t*)(base + ws.rowsum);
+    int rc = bitlinear_quant_act_nonneg(X, M, K, ln_gain, ln_bias, ln_eps, granularity,
+                                        flags & BL_FLAG_SKIP_LN, codes, gamma, eta, rowsum, nullptr,
+                                        nullptr, 0, stream);
+    if (rc != BL_OK) return rc;
+    return bitlinear_matmul_nonneg(codes, gamma, eta, rowsum, M, K, packed, N, beta, wsum,
+                                   granularity, 0, Y, stream);
 }
 
 int bitlinear_layernorm_backward(const float* dXhat, const float* X, int64_t M, int64_t K,

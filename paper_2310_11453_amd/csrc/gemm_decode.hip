@@ -46,6 +46,7 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
     const int mc = m < M ? m : M - 1;
     const int rs = a.rowsum[mc * a.gstride];
     const float gm = a.per_tensor ? a.gamma[0] : a.gamma[mc * a.gstride];
+    const float eta = a.eta ? a.eta[mc * a.gstride] : 0.f;  // Eq. 6 only
 
     int part[ONE_ROUND ? 1 : T][4];
     if (!ONE_ROUND) {
@@ -175,6 +176,11 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
             const float beta = t == w ? beta_first : beta_of(tn);
             const float sc = (beta * gm) / 128.0f;
             v4f o = {(float)pm[0] * sc, (float)pm[1] * sc, (float)pm[2] * sc, (float)pm[3] * sc};
+            if (a.eta) {  // Eq. 6: the shift eta of the activations adds (beta * eta) * sum_k s[n,k]
+                const float be = beta * eta;
+                for (int r = 0; r < 4; ++r)
+                    o[r] = o[r] + be * (float)a.wsum[n + r < a.N ? n + r : a.N - 1];
+            }
             if ((a.N & 3) == 0) {
                 if (a.accumulate) o += *reinterpret_cast<const v4f*>(y);  // a later K-group
                 *reinterpret_cast<v4f*>(y) = o;

@@ -202,6 +202,8 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
     __shared__ __attribute__((aligned(1024))) uint8_t smB[(BN / 16) * 1024];
     __shared__ __attribute__((aligned(16))) float smScale[2][BM];  // gamma_m, per tile parity
     __shared__ __attribute__((aligned(16))) float smBeta[2][BN];   // beta of each column's group
+    __shared__ __attribute__((aligned(16))) float smEta[2][BM];    // Eq. 6 only: eta_m
+    __shared__ __attribute__((aligned(16))) int smWsum[2][BN];     // Eq. 6 only: sum_k s[n,k]
     __shared__ __attribute__((aligned(16))) int smRowsum[2][BM];   // sum_k q[m,k]
 
     const int w = threadIdx.x / kWave, l = threadIdx.x % kWave;
@@ -361,6 +363,14 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
             if (n > a.N - 1) n = a.N - 1;
             const float b = a.beta[((uint32_t)n / (uint32_t)a.beta_rows) * a.beta_stride];
             lds_write_b32((uint32_t)(uintptr_t)&smBeta[parity][c], __float_as_uint(b));
+            if (a.eta) lds_write_b32((uint32_t)(uintptr_t)&smWsum[parity][c], (uint32_t)a.wsum[n]);
+        }
+        if (a.eta) {
+            for (int r = threadIdx.x; r < BM; r += THREADS) {
+                const int64_t m = m0 + r < M ? m0 + r : M - 1;
+                lds_write_b32((uint32_t)(uintptr_t)&smEta[parity][r],
+                              __float_as_uint(a.eta[m * a.gstride]));
+            }
         }
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
@@ -409,6 +419,16 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
             bcol[s] = lds_read_f32((uint32_t)(uintptr_t)&smBeta[parity][wn * WTN + 32 * s + j]);
         const uint32_t sc_base = (uint32_t)(uintptr_t)&smScale[parity][wm * WTM + 4 * g2];
         const uint32_t rs_base = (uint32_t)(uintptr_t)&smRowsum[parity][wm * WTM + 4 * g2];
+        float wcol[NI];  // Eq. 6 only
+#pragma unroll
+        for (int s = 0; s < NI; ++s)
+            wcol[s] = a.eta ? (float)__float_as_int(lds_read_f32(
+                                  (uint32_t)(uintptr_t)&smWsum[parity][wn * WTN + 32 * s + j]))
+                            : 0.f;
+        // Register allocation here is at the limit of 256 and sensitive to the form of these
+        // loops: hoisting the uniform branches into a second copy of the loops, or naming the
+        // row index as a 32-bit temporary, makes the compiler precompute the store addresses and
+        // spill over a hundred registers.  Check the resource usage after any change.
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
@@ -431,6 +451,11 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
                         } else {
                             // y = acc * ((beta * gamma) / 128): the division by 128 is exact
                             float y = (float)pm * ((bcol[s] * sc4[rr]) * 0.0078125f);
+                            if (a.eta) {  // Eq. 6: + (beta * eta_m) * sum_k s[n,k]
+                                const float e = lds_read_f32(
+                                    (uint32_t)(uintptr_t)&smEta[parity][wm * WTM + 32 * mi + 8 * rq + 4 * g2 + rr]);
+                                y = y + (bcol[s] * e) * wcol[s];
+                            }
                             if (a.accumulate) y += a.Y[m * a.N + n];  // a later K-group
                             a.Y[m * a.N + n] = y;
                         }

@@ -12,6 +12,8 @@ int reduce_grid(int64_t count4);
 hipError_t launch_pack(const float* W, int64_t rows, int64_t cols, int64_t ldw, bool beta_centered,
                        uint32_t* packed, float* alpha, float* beta, double* partials, hipStream_t s);
 // canonical words of the block go to canonical[n * ldc + kw], ldc in words
+hipError_t launch_weight_rowsums(const uint32_t* packed, int64_t N, int64_t K, int32_t* wsum,
+                                 hipStream_t s);
 hipError_t launch_to_canonical(const uint32_t* packed, int64_t N, int64_t K, uint32_t* canonical,
                                int64_t ldc, hipStream_t s);
 
@@ -34,6 +36,10 @@ struct QuantArgs {
     // handled as `groups` consecutive rows of K; row r belongs to group r % groups.  M counts
     // those rows.  gain/bias hold groups * K entries.  groups = 1: the plain layer.
     int groups;
+    // Eq. 6 (per token only): codes = clamp(rne((x^ - eta) * 128 / gamma), 0, 127) with
+    // eta = min x^, gamma = max(x^ - eta); eta[M] receives the minima.
+    bool nonneg;
+    float* eta;
 };
 bool quant_supported(int64_t K);
 hipError_t launch_quant(const QuantArgs& a, hipStream_t s);
@@ -55,6 +61,9 @@ struct GemmArgs {
     int64_t beta_rows;    // output columns n per beta group (a multiple of 16, or N)
     int64_t beta_stride;  // beta[(n / beta_rows) * beta_stride] scales column n
     bool accumulate;      // Y += result (a later K-group) instead of Y = result
+    // Eq. 6: Y += (beta * eta[m * gstride]) * wsum[n], wsum[n] = sum_k s[n,k]; nullptr otherwise
+    const float* eta;
+    const int32_t* wsum;
 };
 hipError_t launch_gemm_decode(const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm_prefill(const GemmArgs& a, hipStream_t s);

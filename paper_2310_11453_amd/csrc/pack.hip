@@ -128,6 +128,28 @@ __global__ __launch_bounds__(256) void tiles_to_canonical(const uint32_t* __rest
     canonical[n * ldc + kw] = word;
 }
 
+// ---- wsum[n] = sum_k s[n,k] = 2 * popcount(row n) - K, from the packed tiles ----------
+// One wave per tile row: it walks the row's tiles (1 KiB, coalesced), every lane counts the set
+// bits of its 4 dwords (16 columns of weight row lane%16), the four lanes of a row add up.
+// Padding bits are zero, so only real columns are counted.
+__global__ __launch_bounds__(256) void weight_rowsums(const uint32_t* __restrict__ packed,
+                                                      int64_t N, int64_t K,
+                                                      int32_t* __restrict__ wsum) {
+    const int wave = threadIdx.x / kWave, l = threadIdx.x % kWave;
+    const int64_t TN = tiles_n(N), TK = tiles_k(K);
+    const int64_t tn = (int64_t)blockIdx.x * 4 + wave;
+    if (tn >= TN) return;
+    int pop = 0;
+    for (int64_t tk = 0; tk < TK; ++tk) {
+        const uint4 v = *reinterpret_cast<const uint4*>(packed + tile_dword_offset(tn, tk, TK) + l * 4);
+        pop += __popc(v.x) + __popc(v.y) + __popc(v.z) + __popc(v.w);
+    }
+    pop += __shfl_xor(pop, 16, kWave);
+    pop += __shfl_xor(pop, 32, kWave);
+    const int64_t n = tn * kTileN + l;
+    if (l < kTileN && n < N) wsum[n] = 2 * pop - (int)K;
+}
+
 // ---------------------------------------------------------------------------
 int reduce_grid(int64_t count4) {
     int64_t g = (count4 + 256 * 8 - 1) / (256 * 8);
@@ -150,6 +172,12 @@ hipError_t launch_pack(const float* W, int64_t N, int64_t K, int64_t ldw, bool b
     }
     const int64_t tasks = tiles_n(N) * tiles_k(K);
     pack_tiles<<<(unsigned)((tasks + 3) / 4), 256, 0, s>>>(W, N, K, ldw, alpha, packed);
+    return hipGetLastError();
+}
+
+hipError_t launch_weight_rowsums(const uint32_t* packed, int64_t N, int64_t K, int32_t* wsum,
+                                 hipStream_t s) {
+    weight_rowsums<<<(unsigned)((tiles_n(N) + 3) / 4), 256, 0, s>>>(packed, N, K, wsum);
     return hipGetLastError();
 }
 

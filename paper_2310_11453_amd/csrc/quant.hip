@@ -32,7 +32,7 @@ __global__ __launch_bounds__((WPR < 4 ? 4 : WPR) * kWave, 4) void ln_quant_rows(
     constexpr int RPW = NW / WPR;          // rows per workgroup
     constexpr int RT = WPR * kWave;        // lanes per row
     __shared__ double smd[2][NW];
-    __shared__ float smf[3][NW];
+    __shared__ float smf[4][NW];
     __shared__ int smi[NW];
 
     const int wave = threadIdx.x / kWave;
@@ -68,6 +68,7 @@ __global__ __launch_bounds__((WPR < 4 ? 4 : WPR) * kWave, 4) void ln_quant_rows(
     const bool affine = a.gain != nullptr || a.bias != nullptr;
     bool have_amax = false;
     float amax = 0.f;
+    float lo = 0.f;  // Eq. 6 only: the row's minimum (eta); amax then holds max - min
 
     if (!a.skip_ln) {
         double mu, rstd;
@@ -133,9 +134,9 @@ __global__ __launch_bounds__((WPR < 4 ? 4 : WPR) * kWave, 4) void ln_quant_rows(
             if (!affine) {
                 // x -> fl32((x - mu) * rstd) is monotone, so the largest magnitude of the
                 // normalised row is reached at the row's minimum or maximum.
-                const float lo = (float)(((double)mn - mu) * rstd);
+                lo = (float)(((double)mn - mu) * rstd);
                 const float hi = (float)(((double)mx - mu) * rstd);
-                amax = fmaxf(fabsf(lo), fabsf(hi));
+                amax = a.nonneg ? hi - lo : fmaxf(fabsf(lo), fabsf(hi));
                 have_amax = true;
             }
         }
@@ -179,7 +180,7 @@ __global__ __launch_bounds__((WPR < 4 ? 4 : WPR) * kWave, 4) void ln_quant_rows(
     if constexpr (MODE == kApply) {
         gamma = fmaxf(__uint_as_float(a.gmax_bits[grp]), 1e-5f);
     } else {
-        if (!have_amax) {  // uniform: no LayerNorm, or a gain/bias after it
+        if (!have_amax && !a.nonneg) {  // uniform: no LayerNorm, or a gain/bias after it
             float m = 0.f;
 #pragma unroll
             for (int j = 0; j < NV; ++j) {
@@ -188,6 +189,21 @@ __global__ __launch_bounds__((WPR < 4 ? 4 : WPR) * kWave, 4) void ln_quant_rows(
                                        fmaxf(fabsf(v[j].z), fabsf(v[j].w))));
             }
             amax = row_reduce<WPR>(m, OpMax{}, smf[2], rw, wr);
+        } else if (!have_amax) {  // Eq. 6 on such a row: minimum and maximum of the values
+            float mn = v[0].x, mx = v[0].x;  // lane 0's first element always exists
+#pragma unroll
+            for (int j = 0; j < NV; ++j) {
+                if (t + j * RT < K4) {
+                    mn = fminf(fminf(mn, v[j].x), fminf(fminf(v[j].y, v[j].z), v[j].w));
+                    mx = fmaxf(fmaxf(mx, v[j].x), fmaxf(fmaxf(v[j].y, v[j].z), v[j].w));
+                }
+            }
+            if (t >= K4) {  // a lane without elements must not contribute the padding it holds
+                mn = __builtin_inff();
+                mx = -__builtin_inff();
+            }
+            lo = row_reduce<WPR>(mn, OpMin{}, smf[2], rw, wr);
+            amax = row_reduce<WPR>(mx, OpMax{}, smf[3], rw, wr) - lo;
         }
         if constexpr (MODE == kStats) {
             // non-negative floats order like their bit patterns: integer max is exact
@@ -203,6 +219,16 @@ __global__ __launch_bounds__((WPR < 4 ? 4 : WPR) * kWave, 4) void ln_quant_rows(
     // code = clamp(rne(x^ * scale), -128, 127), one fp32 operation per step.  The integral
     // float plus 128 lies in 0..255 and goes straight into its byte of the output word;
     // flipping the top bit of each byte turns that offset form into two's complement.
+    auto code_word_nonneg = [&](const float4& x) {  // Eq. 6: shift by eta, clamp to [0, 127]
+        const float q0 = fminf(fmaxf(rintf((x.x - lo) * scale), 0.f), 127.f);
+        const float q1 = fminf(fmaxf(rintf((x.y - lo) * scale), 0.f), 127.f);
+        const float q2 = fminf(fmaxf(rintf((x.z - lo) * scale), 0.f), 127.f);
+        const float q3 = fminf(fmaxf(rintf((x.w - lo) * scale), 0.f), 127.f);
+        uint32_t wd = __builtin_amdgcn_cvt_pk_u8_f32(q0, 0, 0u);
+        wd = __builtin_amdgcn_cvt_pk_u8_f32(q1, 1, wd);
+        wd = __builtin_amdgcn_cvt_pk_u8_f32(q2, 2, wd);
+        return __builtin_amdgcn_cvt_pk_u8_f32(q3, 3, wd);
+    };
     auto code_word = [&](const float4& x) {
         const float q0 = fminf(fmaxf(rintf(x.x * scale), -128.f), 127.f) + 128.f;
         const float q1 = fminf(fmaxf(rintf(x.y * scale), -128.f), 127.f) + 128.f;
@@ -217,7 +243,7 @@ __global__ __launch_bounds__((WPR < 4 ? 4 : WPR) * kWave, 4) void ln_quant_rows(
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
         const int idx = t + j * RT;
-        const uint32_t wd = code_word(v[j]);
+        const uint32_t wd = a.nonneg ? code_word_nonneg(v[j]) : code_word(v[j]);
         if (idx < K4) {
             rs = __builtin_amdgcn_sdot4((int)wd, 0x01010101, rs, false);  // sum of the four codes
             if (live) c4[idx] = wd;
@@ -228,6 +254,7 @@ __global__ __launch_bounds__((WPR < 4 ? 4 : WPR) * kWave, 4) void ln_quant_rows(
         if (t == 0 && live) a.rowsum[row] = rs;
     }
     if (t == 0 && live) {
+        if (a.nonneg) a.eta[row] = lo;
         if (MODE == kFull) a.gamma[row] = gamma;
         else if (row < a.groups) a.gamma[row] = gamma;  // rows 0 .. groups-1 cover every group
     }

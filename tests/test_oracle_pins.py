@@ -521,3 +521,58 @@ def test_layernorm_backward_finite_differences_and_projections():
     assert np.abs(dX.sum(axis=1)).max() <= 1e-5
     # exact only for eps = 0: the residual is rstd * sum(g * xn) * eps / (var + eps) ~ 1e-4 here
     assert np.abs((dX * xn).sum(axis=1)).max() <= 1e-3
+
+
+# ---------------------------------------------------------------- Eq. 6: non-negative quantiser
+def test_eq6_range_and_reconstruction():
+    """Eq. 6: the shifted activations fill [0, Q_b]; the minimum maps to code 0, the maximum to
+    the top code, and q * gamma / 128 + eta reconstructs x to half a step."""
+    rng = np.random.default_rng(31)
+    x = (rng.standard_normal((6, 256)) * 1.7 + 0.4).astype(f32)
+    eta, gamma = oracle.minmax_nonneg(x)
+    assert np.array_equal(eta, x.min(axis=1)) and np.array_equal(gamma, (x.max(axis=1) - x.min(axis=1)))
+    q = oracle.quantize_nonneg(x, eta, gamma)
+    assert q.min() == 0 and q.max() == 127
+    assert np.all(q[np.arange(6), x.argmin(axis=1)] == 0)
+    assert np.all(q[np.arange(6), x.argmax(axis=1)] == 127)   # rne gives 128, the clamp 127
+    rec = q.astype(np.float64) * gamma[:, None] / 128.0 + eta[:, None]
+    step = gamma[:, None].astype(np.float64) / 128.0
+    err = np.abs(rec - x)
+    # half a step, plus the fp32 roundings of x - eta and of the scaling (a few ulps of |x|)
+    assert np.all(err <= 0.5 * step + 4e-6 + (q == 127) * 0.5 * step)
+
+
+def test_eq6_reduces_to_eq4_on_nonnegative_rows_with_a_zero():
+    """With min x = 0 the shift vanishes and gamma = max x = ||x||_inf: Eq. 6 is Eq. 4."""
+    rng = np.random.default_rng(32)
+    x = np.abs(rng.standard_normal((5, 128))).astype(f32)
+    x[:, 3] = 0.0
+    eta, gamma = oracle.minmax_nonneg(x)
+    assert np.all(eta == 0)
+    assert np.array_equal(gamma, oracle.absmax(x))
+    assert np.array_equal(oracle.quantize_nonneg(x, eta, gamma), oracle.quantize(x, gamma))
+
+
+def test_eq6_shift_invariance():
+    """eta absorbs a constant: x + c has the codes of x (integer-valued data, exact shift)."""
+    rng = np.random.default_rng(33)
+    x = rng.integers(-50, 50, (4, 64)).astype(f32)
+    a = oracle.quantize_nonneg(x, *oracle.minmax_nonneg(x))
+    b = oracle.quantize_nonneg(x + f32(1024), *oracle.minmax_nonneg(x + f32(1024)))
+    assert np.array_equal(a, b)
+
+
+def test_eq6_forward_matches_float_matmul_of_dequantised_activations():
+    """The dequantisation proposed for Eq. 6: y = beta * W~ (x~ gamma / Q_b + eta), checked
+    against numpy's fp64 matmul of the reconstructed activations."""
+    rng = np.random.default_rng(34)
+    X = (rng.standard_normal((9, 96)) + 0.3).astype(f32)
+    W = (rng.standard_normal((40, 96)) * 0.02).astype(f32)
+    r = oracle.forward_nonneg(X, W)
+    assert np.array_equal(r["wsum"], r["sign"].astype(np.int64).sum(axis=1))
+    rec = r["codes"].astype(np.float64) * r["gamma"][:, None] / 128.0 + r["eta"][:, None]
+    y = float(r["beta"]) * rec @ r["sign"].astype(np.float64).T
+    assert np.abs(r["y"] - y).max() <= 1e-5 * np.abs(y).max()
+    # and the quantised layer stays close to the unquantised one (8-bit activations)
+    yf = float(r["beta"]) * r["xhat"].astype(np.float64) @ r["sign"].astype(np.float64).T
+    assert np.linalg.norm(r["y"] - yf) / np.linalg.norm(yf) < 0.05
