@@ -37,8 +37,7 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
 
     // epilogue operands, requested up front so their latency hides under the weight stream.
     // beta belongs to the group of output rows that holds a tile (Eq. 13; one group: beta[0]).
-    auto beta_of = [&](int64_t tn) {
-        if (a.beta_rows >= a.N) return a.beta[0];  // one group: no division on the plain path
+    auto beta_of = [&](int64_t tn) {  // branch-free: nothing may delay the loads that follow
         if (tn > TN - 1) tn = TN - 1;
         return a.beta[((uint32_t)(tn * kTileN) / (uint32_t)a.beta_rows) * a.beta_stride];  // N <= 2^30
     };
@@ -46,7 +45,8 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
     const int mc = m < M ? m : M - 1;
     const int rs = a.rowsum[mc * a.gstride];
     const float gm = a.per_tensor ? a.gamma[0] : a.gamma[mc * a.gstride];
-    const float eta = a.eta ? a.eta[mc * a.gstride] : 0.f;  // Eq. 6 only
+    // Eq. 6 only; without it the load goes to gamma (always valid) and the value is not used
+    const float eta = *(a.eta ? a.eta + mc * a.gstride : a.gamma);
 
     int part[ONE_ROUND ? 1 : T][4];
     if (!ONE_ROUND) {
@@ -105,10 +105,7 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
         auto load_tile = [&](int t) {
             const uint32_t off = (uint32_t)(t < t_last ? t : t_last) * tile_stride;
 #pragma unroll
-            for (int c = 0; c < C; ++c) {
-                const v4i z = *reinterpret_cast<const v4i*>(wbase[c] + off);
-                wt[t][c] = (C == 1 && ONE_ROUND) ? z : (z & livem[c]);
-            }
+            for (int c = 0; c < C; ++c) wt[t][c] = *reinterpret_cast<const v4i*>(wbase[c] + off);
         };
 #pragma unroll
         for (int t = 0; t < kDepth; ++t) load_tile(t);
@@ -120,12 +117,18 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
             v4i acc[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) acc[i] = (v4i){0, 0, 0, 0};
+            // chunks past the end of K are masked here, at the point of use: masking at the load
+            // would tie a wait for the whole stream to the first tile
+            v4i wv[C];
+#pragma unroll
+            for (int c = 0; c < C; ++c)
+                wv[c] = (C == 1 && ONE_ROUND) ? wt[t][c] : (wt[t][c] & livem[c]);
 #pragma unroll
             for (int c = 0; c < C; ++c)
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     const int mask = (int)(0x01010101u << i);
-                    const v4i plane = wt[t][c] & mask;
+                    const v4i plane = wv[c] & mask;
                     // rows of the MFMA = weights (n), columns = tokens (m)
                     acc[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(plane, act[c][i], acc[i], 0, 0, 0);
                 }

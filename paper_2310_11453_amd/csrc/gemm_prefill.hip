@@ -200,7 +200,7 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
 
     __shared__ __attribute__((aligned(1024))) uint8_t smA[NS * STAGE_BYTES];
     __shared__ __attribute__((aligned(1024))) uint8_t smB[(BN / 16) * 1024];
-    __shared__ __attribute__((aligned(16))) float smScale[2][BM];  // gamma_m, per tile parity
+    __shared__ __attribute__((aligned(16))) float smScale[2][BM];  // gamma_m / 128, per tile parity
     __shared__ __attribute__((aligned(16))) float smBeta[2][BN];   // beta of each column's group
     __shared__ __attribute__((aligned(16))) float smEta[2][BM];    // Eq. 6 only: eta_m
     __shared__ __attribute__((aligned(16))) int smWsum[2][BN];     // Eq. 6 only: sum_k s[n,k]
@@ -352,7 +352,8 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
             float sc = 0.f;
             int rs = 0;
             if (m < M) {
-                sc = a.per_tensor ? a.gamma[0] : a.gamma[m * a.gstride];
+                // gamma / 128 is exact, so beta * (gamma / 128) below has the bits of (beta * gamma) / 128
+                sc = (a.per_tensor ? a.gamma[0] : a.gamma[m * a.gstride]) * 0.0078125f;
                 rs = a.rowsum[m * a.gstride];
             }
             lds_write_b32((uint32_t)(uintptr_t)&smScale[parity][r], __float_as_uint(sc));
@@ -419,6 +420,7 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
             bcol[s] = lds_read_f32((uint32_t)(uintptr_t)&smBeta[parity][wn * WTN + 32 * s + j]);
         const uint32_t sc_base = (uint32_t)(uintptr_t)&smScale[parity][wm * WTM + 4 * g2];
         const uint32_t rs_base = (uint32_t)(uintptr_t)&smRowsum[parity][wm * WTM + 4 * g2];
+        const bool special = a.out_acc || a.eta != nullptr || a.accumulate;
         float wcol[NI];  // Eq. 6 only
 #pragma unroll
         for (int s = 0; s < NI; ++s)
@@ -446,19 +448,21 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
                         const int64_t n = n0 + wn * WTN + 32 * s + j;
                         if (n >= a.N) continue;
                         const int pm = 2 * acc[mi][s][r] - rs4[rr];
-                        if (a.out_acc) {
-                            reinterpret_cast<int*>(a.Y)[m * a.N + n] = pm;
-                        } else {
-                            // y = acc * ((beta * gamma) / 128): the division by 128 is exact
-                            float y = (float)pm * ((bcol[s] * sc4[rr]) * 0.0078125f);
+                        // y = acc * ((beta * gamma) / 128)
+                        float y = (float)pm * (bcol[s] * sc4[rr]);
+                        if (special) {  // uniform
+                            if (a.out_acc) {
+                                reinterpret_cast<int*>(a.Y)[m * a.N + n] = pm;
+                                continue;
+                            }
                             if (a.eta) {  // Eq. 6: + (beta * eta_m) * sum_k s[n,k]
                                 const float e = lds_read_f32(
                                     (uint32_t)(uintptr_t)&smEta[parity][wm * WTM + 32 * mi + 8 * rq + 4 * g2 + rr]);
                                 y = y + (bcol[s] * e) * wcol[s];
                             }
                             if (a.accumulate) y += a.Y[m * a.N + n];  // a later K-group
-                            a.Y[m * a.N + n] = y;
                         }
+                        a.Y[m * a.N + n] = y;
                     }
                 }
             }
