@@ -181,11 +181,13 @@ def main():
                 X3 = torch.from_numpy(wl.make_activation(Md, L3.K, wl.seed_for(3, li))).to(dev)
                 codes3, gamma3, rowsum3, _ = bl.bitlinear_quant_act(X3)
                 Y3 = torch.empty((Md, L3.N), dtype=torch.float32, device=dev)
+                ws3 = torch.empty(max(256, bl.workspace_bytes(bl.OP_MATMUL, Md, L3.N, L3.K)),
+                                  dtype=torch.uint8, device=dev)
                 state = {"i": 0}
 
                 def run():
                     bl.bitlinear_matmul(codes3, gamma3, rowsum3, copies[state["i"] % ncopy], L3.N,
-                                        b3, out=Y3)
+                                        b3, out=Y3, workspace=ws3)
                     state["i"] += 1
 
                 for _ in range(ncopy):

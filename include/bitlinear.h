@@ -61,7 +61,7 @@ enum {
 
 /* Operation selector for bitlinear_workspace_bytes. */
 typedef enum { BL_OP_PACK = 0, BL_OP_QUANT = 1, BL_OP_FORWARD = 2, BL_OP_BACKWARD = 3,
-               BL_OP_LN_BACKWARD = 4, BL_OP_FORWARD_NONNEG = 5 } bl_op;
+               BL_OP_LN_BACKWARD = 4, BL_OP_FORWARD_NONNEG = 5, BL_OP_MATMUL = 6 } bl_op;
 
 /* host: size in bytes of the packed-weight blob for an [N,K] matrix (0 on bad
  * shape).  The blob is the library's own tiled 1-bit layout (1 bit per weight,
@@ -104,10 +104,14 @@ int bitlinear_quant_act(const float* X, int64_t M, int64_t K, const float* ln_ga
 /* Eq. 7 + Eq. 11 on already-quantised activations:
  *   Y[m,n] = (sum_k codes[m,k] * W~[n,k]) * (beta * gamma_m / 128).
  *   rowsum  in  int32 [M] as produced by bitlinear_quant_act (required)
- *   Y       out fp32 [M,N] (int32 accumulators with BL_FLAG_OUT_ACC_I32) */
+ *   Y       out fp32 [M,N] (int32 accumulators with BL_FLAG_OUT_ACC_I32)
+ *   workspace   optional (may be NULL): with bitlinear_workspace_bytes(BL_OP_MATMUL, ...) bytes
+ *               the library may split a long K (> 16384 at M <= 16) over more workgroups and
+ *               fold the slices in a second kernel; the result is the same bit for bit */
 int bitlinear_matmul(const int8_t* codes, const float* gamma, const int32_t* rowsum, int64_t M,
                      int64_t K, const void* packed, int64_t N, const float* beta, int granularity,
-                     unsigned flags, float* Y, void* stream);
+                     unsigned flags, float* Y, void* workspace, size_t workspace_bytes,
+                     void* stream);
 
 /* Eq. 11, the whole layer: bitlinear_quant_act into the workspace, then
  * bitlinear_matmul.  Arguments as above. */

@@ -3,7 +3,7 @@ behind the C ABI of include/bitlinear.h, with a ctypes binding of the same names
 from .binding import (  # noqa: F401
     BitLinearError, EXPORTS, LIB_PATH,
     FLAG_BETA_CENTERED, FLAG_OUT_ACC_I32, FLAG_SKIP_LN,
-    OP_BACKWARD, OP_FORWARD, OP_FORWARD_NONNEG, OP_LN_BACKWARD, OP_PACK, OP_QUANT,
+    OP_BACKWARD, OP_FORWARD, OP_FORWARD_NONNEG, OP_LN_BACKWARD, OP_MATMUL, OP_PACK, OP_QUANT,
     bitlinear_backward_ste, bitlinear_forward, bitlinear_matmul, bitlinear_pack_weights,
     bitlinear_packed_to_canonical, bitlinear_quant_act, load_library, packed_bytes,
     status_string, workspace_bytes,

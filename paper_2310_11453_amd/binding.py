@@ -18,6 +18,7 @@ BL_OK = 0
 GAMMA_PER_TOKEN, GAMMA_PER_TENSOR = 0, 1
 FLAG_SKIP_LN, FLAG_OUT_ACC_I32, FLAG_BETA_CENTERED = 1, 2, 4
 OP_PACK, OP_QUANT, OP_FORWARD, OP_BACKWARD, OP_LN_BACKWARD, OP_FORWARD_NONNEG = 0, 1, 2, 3, 4, 5
+OP_MATMUL = 6
 
 EXPORTS = (
     "bitlinear_packed_bytes", "bitlinear_workspace_bytes", "bitlinear_pack_weights",
@@ -58,7 +59,7 @@ def load_library() -> ctypes.CDLL:
     lib.bitlinear_quant_act.restype = ci
     lib.bitlinear_quant_act.argtypes = [vp, i64, i64, vp, vp, cf, ci, u32, vp, vp, vp, vp, vp, sz, vp]
     lib.bitlinear_matmul.restype = ci
-    lib.bitlinear_matmul.argtypes = [vp, vp, vp, i64, i64, vp, i64, vp, ci, u32, vp, vp]
+    lib.bitlinear_matmul.argtypes = [vp, vp, vp, i64, i64, vp, i64, vp, ci, u32, vp, vp, sz, vp]
     lib.bitlinear_forward.restype = ci
     lib.bitlinear_forward.argtypes = [vp, i64, i64, vp, i64, vp, vp, vp, cf, ci, u32, vp, vp, sz, vp]
     lib.bitlinear_backward_ste.restype = ci
@@ -182,8 +183,10 @@ def bitlinear_quant_act(X: torch.Tensor, ln_eps: float = 1e-5, per_tensor: bool 
 
 def bitlinear_matmul(codes: torch.Tensor, gamma: torch.Tensor, rowsum: torch.Tensor,
                      packed: torch.Tensor, N: int, beta: torch.Tensor, per_tensor: bool = False,
-                     flags: int = 0, out: torch.Tensor | None = None) -> torch.Tensor:
-    """Eq. 7 + Eq. 11 on quantised activations.  fp32 [M,N], or int32 with FLAG_OUT_ACC_I32."""
+                     flags: int = 0, out: torch.Tensor | None = None,
+                     workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """Eq. 7 + Eq. 11 on quantised activations.  fp32 [M,N], or int32 with FLAG_OUT_ACC_I32.
+    `workspace` (workspace_bytes(OP_MATMUL, ...) bytes) is optional: see include/bitlinear.h."""
     M, K = codes.shape
     want_int = bool(flags & FLAG_OUT_ACC_I32)
     if out is None:
@@ -191,7 +194,8 @@ def bitlinear_matmul(codes: torch.Tensor, gamma: torch.Tensor, rowsum: torch.Ten
                           device=codes.device)
     _check(load_library().bitlinear_matmul(
         _ptr(codes, torch.int8), _ptr(gamma, torch.float32), _ptr(rowsum, torch.int32), M, K,
-        _ptr(packed), N, _ptr(beta, torch.float32), _gran(per_tensor), flags, _ptr(out), _stream()),
+        _ptr(packed), N, _ptr(beta, torch.float32), _gran(per_tensor), flags, _ptr(out),
+        _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream()),
         "bitlinear_matmul")
     return out
 

@@ -36,9 +36,9 @@ QuantWs quant_ws(int64_t M, int granularity) {
     return w;
 }
 struct ForwardWs {
-    size_t codes, gamma, rowsum, quant, total;
+    size_t codes, gamma, rowsum, quant, split, split_bytes, total;
 };
-ForwardWs forward_ws(int64_t M, int64_t K, int granularity) {
+ForwardWs forward_ws(int64_t M, int64_t N, int64_t K, int granularity) {
     ForwardWs w{};
     size_t off = 0;
     w.codes = off;
@@ -49,6 +49,9 @@ ForwardWs forward_ws(int64_t M, int64_t K, int granularity) {
     off += align256((size_t)M * 4);
     w.quant = off;
     off += quant_ws(M, granularity).total;
+    w.split = off;  // partial sums of a K split (small M, long K), else empty
+    w.split_bytes = gemm_split_ws_bytes(M, N, K);
+    off += align256(w.split_bytes);
     w.total = off;
     return w;
 }
@@ -140,7 +143,7 @@ size_t bitlinear_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int gr
             return quant_ws(M, granularity).total;
         case BL_OP_FORWARD:
             if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return 0;
-            return forward_ws(M, K, granularity).total;
+            return forward_ws(M, N, K, granularity).total;
         case BL_OP_BACKWARD:
             if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return 0;
             return backward_workspace_bytes(M, N, K) + 256;
@@ -150,6 +153,9 @@ size_t bitlinear_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int gr
         case BL_OP_FORWARD_NONNEG:
             if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return 0;
             return forward_ws_nonneg(M, K).total;
+        case BL_OP_MATMUL:
+            if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return 0;
+            return gemm_split_ws_bytes(M, N, K);  // 0 for most shapes: nothing is needed
         default:
             return 0;
     }
@@ -200,7 +206,8 @@ int bitlinear_quant_act(const float* X, int64_t M, int64_t K, const float* ln_ga
 
 int bitlinear_matmul(const int8_t* codes, const float* gamma, const int32_t* rowsum, int64_t M,
                      int64_t K, const void* packed, int64_t N, const float* beta, int granularity,
-                     unsigned flags, float* Y, void* stream) {
+                     unsigned flags, float* Y, void* workspace, size_t workspace_bytes,
+                     void* stream) {
     if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return BL_ERR_SHAPE;
     if (!gran_ok(granularity) || (flags & ~BL_FLAG_OUT_ACC_I32)) return BL_ERR_UNSUPPORTED;
     if (M == 0) return BL_OK;
@@ -212,6 +219,8 @@ int bitlinear_matmul(const int8_t* codes, const float* gamma, const int32_t* row
     a.out_acc = (flags & BL_FLAG_OUT_ACC_I32) != 0;
     a.Y = Y;
     plain_fields(a);
+    a.split_ws = (int32_t*)workspace;  // optional: without it K is never split
+    a.split_ws_bytes = workspace ? workspace_bytes : 0;
     if (M <= 16) return check_hip(launch_gemm_decode(a, (hipStream_t)stream));
     return check_hip(launch_gemm_prefill(a, (hipStream_t)stream));
 }
@@ -225,7 +234,7 @@ int bitlinear_forward(const float* X, int64_t M, int64_t K, const void* packed, 
         return BL_ERR_UNSUPPORTED;
     if (M == 0) return BL_OK;
     if (!X || !packed || !beta || !Y) return BL_ERR_NULL;
-    const ForwardWs ws = forward_ws(M, K, granularity);
+    const ForwardWs ws = forward_ws(M, N, K, granularity);
     if (!workspace || workspace_bytes < ws.total) return BL_ERR_WORKSPACE;
     char* base = (char*)workspace;
     int8_t* codes = (int8_t*)(base + ws.codes);
@@ -233,10 +242,19 @@ int bitlinear_forward(const float* X, int64_t M, int64_t K, const void* packed, 
     int32_t* rowsum = (int32_t*)(base + ws.rowsum);
     int rc = bitlinear_quant_act(X, M, K, ln_gain, ln_bias, ln_eps, granularity,
                                  flags & BL_FLAG_SKIP_LN, codes, gamma, rowsum, nullptr,
-                                 base + ws.quant, workspace_bytes - ws.quant, stream);
+                                 base + ws.quant, ws.split - ws.quant, stream);
     if (rc != BL_OK) return rc;
-    return bitlinear_matmul(codes, gamma, rowsum, M, K, packed, N, beta, granularity,
-                            flags & BL_FLAG_OUT_ACC_I32, Y, stream);
+    GemmArgs a{};
+    a.codes = codes; a.gamma = gamma; a.rowsum = rowsum; a.M = M; a.K = K; a.N = N;
+    a.packed = (const uint32_t*)packed; a.beta = beta;
+    a.per_tensor = granularity == BL_GAMMA_PER_TENSOR;
+    a.out_acc = (flags & BL_FLAG_OUT_ACC_I32) != 0;
+    a.Y = Y;
+    plain_fields(a);
+    a.split_ws = ws.split_bytes ? (int32_t*)(base + ws.split) : nullptr;
+    a.split_ws_bytes = ws.split_bytes;
+    if (M <= 16) return check_hip(launch_gemm_decode(a, (hipStream_t)stream));
+    return check_hip(launch_gemm_prefill(a, (hipStream_t)stream));
 }
 
 // ---- Group Quantization and Normalization (Eq. 13-15) ----------------------------------

@@ -31,6 +31,13 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
     const int W = blockDim.x / kWave;
     const int w = threadIdx.x / kWave, l = threadIdx.x % kWave;
     const int m = l & 15, g = l >> 4;
+    const int64_t TKp = a.tk_pitch ? a.tk_pitch : tiles_k(a.K);  // tiles per tile row in memory
+    if (a.split_k) {  // this workgroup's slice of K (uniform)
+        const int64_t k0 = (int64_t)blockIdx.y * a.split_k;
+        a.codes += k0;
+        a.packed += (k0 / kChunkK) * 256;
+        a.K = a.K - k0 < a.split_k ? a.K - k0 : a.split_k;
+    }
     const int64_t TN = tiles_n(a.N), TK = tiles_k(a.K);
     const int M = (int)a.M;
     const int64_t tn0 = (int64_t)blockIdx.x * tpb;
@@ -100,8 +107,8 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
         const int t_last = (int)((tn0 + tpb - 1 < TN - 1 ? tn0 + tpb - 1 : TN - 1) - tn0);
         const uint32_t* wbase[C];
 #pragma unroll
-        for (int c = 0; c < C; ++c) wbase[c] = a.packed + (tn0 * TK + tkc[c]) * 256 + l * 4;
-        const uint32_t tile_stride = (uint32_t)TK * 256;  // dwords; K < 2^22 keeps it in 32 bits
+        for (int c = 0; c < C; ++c) wbase[c] = a.packed + (tn0 * TKp + tkc[c]) * 256 + l * 4;
+        const uint32_t tile_stride = (uint32_t)TKp * 256;  // dwords; K < 2^22 keeps it in 32 bits
         auto load_tile = [&](int t) {
             const uint32_t off = (uint32_t)(t < t_last ? t : t_last) * tile_stride;
 #pragma unroll
@@ -167,6 +174,15 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
         const int64_t tn = tn0 + t;
         const int64_t n = tn * kTileN + 4 * g;
         if (tn >= TN || m >= M || n >= a.N) continue;
+        if (a.split_k) {  // partial sum of this K-slice: 2 * sum_k q b, folded by splitk_reduce
+            int* p = a.split_ws + ((int64_t)blockIdx.y * M + m) * a.N + n;
+            const v4i h = sum >> 6;
+            if ((a.N & 3) == 0) *reinterpret_cast<v4i*>(p) = h;
+            else
+                for (int r = 0; r < 4; ++r)
+                    if (n + r < a.N) p[r] = h[r];
+            continue;
+        }
         const v4i pm = (sum >> 6) - rs;  // sum_k q s = 2 * (sum / 128) - sum_k q, exact shift
         float* y = a.Y + (int64_t)m * a.N + n;
         if (a.out_acc) {
@@ -195,6 +211,26 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
     }
 }
 
+// Second step of a K split: Y[m,n] = epilogue(sum_s partial[s][m][n] - rowsum[m]).
+__global__ __launch_bounds__(256) void splitk_reduce(GemmArgs a, int splits) {
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= a.M * a.N) return;
+    const int64_t m = idx / a.N, n = idx % a.N;
+    int sum = 0;
+    for (int sp = 0; sp < splits; ++sp) sum += a.split_ws[((int64_t)sp * a.M + m) * a.N + n];
+    const int pm = sum - a.rowsum[m * a.gstride];
+    if (a.out_acc) {
+        reinterpret_cast<int*>(a.Y)[idx] = pm;
+        return;
+    }
+    const float beta = a.beta[((uint32_t)n / (uint32_t)a.beta_rows) * a.beta_stride];
+    const float gm = a.per_tensor ? a.gamma[0] : a.gamma[m * a.gstride];
+    float y = (float)pm * ((beta * gm) / 128.0f);
+    if (a.eta) y = y + (beta * a.eta[m * a.gstride]) * (float)a.wsum[n];
+    if (a.accumulate) y += a.Y[idx];
+    a.Y[idx] = y;
+}
+
 static int env_int(const char* name, int dflt) {
     const char* e = getenv(name);
     return e ? atoi(e) : dflt;
@@ -215,7 +251,8 @@ static int num_cus() {
 template <int C, int T, int MAXT, bool ONE_ROUND>
 static void launch_one(const GemmArgs& a, int W, int tpb, hipStream_t s) {
     const int64_t TN = tiles_n(a.N);
-    const unsigned grid = (unsigned)((TN + tpb - 1) / tpb);
+    const unsigned splits = a.split_k ? (unsigned)((a.K + a.split_k - 1) / a.split_k) : 1u;
+    const dim3 grid((unsigned)((TN + tpb - 1) / tpb), splits);
     gemm_decode_kernel<C, T, MAXT, ONE_ROUND><<<grid, W * kWave, 0, s>>>(a, tpb);
 }
 
@@ -234,13 +271,36 @@ static void launch_tiles(const GemmArgs& a, int W, int tpb, hipStream_t s) {
     }
 }
 
-hipError_t launch_gemm_decode(const GemmArgs& a, hipStream_t s) {
-    const int64_t TN = tiles_n(a.N), TK = tiles_k(a.K);
+// K > 16384 with a workspace: split K over workgroups so that every slice takes the one-round
+// path with two chunks per wave (at most 16 chunks a slice), and fold the slices afterwards.
+size_t gemm_split_ws_bytes(int64_t M, int64_t N, int64_t K) {
+    const int64_t TK = tiles_k(K);
+    if (M > 16 || TK <= 32) return 0;
+    const int64_t splits = (TK + 15) / 16;
+    return (size_t)splits * (size_t)M * (size_t)N * 4;
+}
+
+hipError_t launch_gemm_decode(const GemmArgs& a_in, hipStream_t s) {
+    GemmArgs a = a_in;
+    const int64_t TN = tiles_n(a.N);
+    int64_t TK = tiles_k(a.K);
+    int splits = 1;
+    const size_t need = gemm_split_ws_bytes(a.M, a.N, a.K);
+    if (need && a.split_ws && a.split_ws_bytes >= need && !env_int("BITLINEAR_DECODE_NOSPLIT", 0)) {
+        splits = (int)((TK + 15) / 16);
+        const int64_t per = (TK + splits - 1) / splits;  // tiles per slice, evenly
+        splits = (int)((TK + per - 1) / per);            // slices that actually hold tiles
+        a.tk_pitch = a.tk_pitch ? a.tk_pitch : TK;
+        a.split_k = per * kChunkK;
+        TK = per;
+    } else {
+        a.split_k = 0;
+    }
     // The whole matrix is a few microseconds of HBM time, so the kernel is built to have every
     // byte requested at once: one round of workgroups (about one per CU), each wave asking for
     // all of its weight tiles before the first MFMA.
     auto tiles_per_group = [&](int cap) {
-        int tpb = (int)((TN + num_cus() - 1) / num_cus());
+        int tpb = (int)((TN * splits + num_cus() - 1) / num_cus());
         tpb = tpb > cap ? cap : tpb < 1 ? 1 : tpb;
         return env_int("BITLINEAR_DECODE_T", tpb);
     };
@@ -268,6 +328,7 @@ hipError_t launch_gemm_decode(const GemmArgs& a, hipStream_t s) {
         const int W = (int)((slots + rounds - 1) / rounds);
         launch_one<2, 1, 1024, false>(a, W, 1, s);
     }
+    if (splits > 1) splitk_reduce<<<(unsigned)((a.M * a.N + 255) / 256), 256, 0, s>>>(a, splits);
     return hipGetLastError();
 }
 

@@ -64,7 +64,16 @@ struct GemmArgs {
     // Eq. 6: Y += (beta * eta[m * gstride]) * wsum[n], wsum[n] = sum_k s[n,k]; nullptr otherwise
     const float* eta;
     const int32_t* wsum;
+    // Packed tiles of one tile row are tk_pitch KiB apart (0: tiles_k(K), the whole matrix).
+    int64_t tk_pitch;
+    // K split across workgroups (set by the launchers, not by callers): blockIdx.y = split,
+    // split_k elements of K each; partial sums 2 * sum_k q b go to split_ws[split][M][N] (int32)
+    // and a second kernel folds them and applies the epilogue.
+    int64_t split_k;
+    int32_t* split_ws;
+    size_t split_ws_bytes;  // what the caller offers; too small or nullptr: no split
 };
+size_t gemm_split_ws_bytes(int64_t M, int64_t N, int64_t K);
 hipError_t launch_gemm_decode(const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm_prefill(const GemmArgs& a, hipStream_t s);
 

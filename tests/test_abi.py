@@ -63,7 +63,7 @@ def test_argument_errors_are_found_on_the_host(lib):
                                  1 << 20, None) == -2
     assert lib.bitlinear_forward(one, 4, 64, one, 16, one, None, None, 1e-5, 0, 0, one, None,
                                  0, None) == -4
-    assert lib.bitlinear_matmul(one, one, None, 4, 64, one, 16, one, 0, 0, one, None) == -1
+    assert lib.bitlinear_matmul(one, one, None, 4, 64, one, 16, one, 0, 0, one, None, 0, None) == -1
     assert lib.bitlinear_backward_ste(None, 4, 16, 64, one, one, 0, one, one, one, one, one,
                                       1 << 20, None) == -1
     # M == 0 is a successful no-op

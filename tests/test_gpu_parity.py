@@ -233,3 +233,31 @@ def test_full_size_30b_batched_decode(bl, li, M):
     L = wl.CONFIGS[3].layers[li]
     print(f"full 30b {L} M={M}", flush=True)
     _sampled_check(bl, M, L.K, L.N, 0.01, 0, 1, wl.seed_for(3, li), n_samples=2048)
+
+
+# ------------------------------------------------------------------ K split across workgroups
+@pytest.mark.parametrize("M,K,N", [(1, 28672, 7168), (16, 28672, 7168), (5, 16896, 200),
+                                   (16, 17920, 1040), (3, 32768, 64)])
+def test_forward_long_k_split_matches_single_pass(bl, M, K, N):
+    """K > 16384 at M <= 16: bitlinear_forward splits K over workgroups and folds the slices in
+    a second kernel; the result must equal the single-pass kernel's (bitlinear_matmul has no
+    workspace and never splits) bit for bit, and the oracle's on sampled outputs."""
+    print(f"split-K forward M={M} K={K} N={N}", flush=True)
+    X = wl.make_activation(M, K, seed=wl.seed_for(3, K + N + M))
+    W = wl.make_weight(N, K, 0.01, seed=wl.seed_for(3, K + N))
+    packed, alpha, beta = bl.bitlinear_pack_weights(dev(W))
+    Xd = dev(X)
+    y_split = bl.bitlinear_forward(Xd, packed, N, beta)
+    codes, gamma, rowsum, _ = bl.bitlinear_quant_act(Xd)
+    y_single = bl.bitlinear_matmul(codes, gamma, rowsum, packed, N, beta)
+    assert torch.equal(y_split, y_single)
+    acc_split = bl.bitlinear_forward(Xd, packed, N, beta, flags=bl.FLAG_OUT_ACC_I32)
+    acc_single = bl.bitlinear_matmul(codes, gamma, rowsum, packed, N, beta, flags=bl.FLAG_OUT_ACC_I32)
+    assert torch.equal(acc_split, acc_single)
+    # sampled outputs against the oracle, from the GPU's own codes
+    rng = np.random.default_rng(K)
+    rows = rng.integers(0, M, 64)
+    cols = rng.integers(0, N, 64)
+    sign = oracle.binarize(W, host(alpha)[0])
+    ref = oracle.matmul_i32_sampled(host(codes), sign, rows, cols)
+    assert np.array_equal(host(acc_split)[rows, cols], ref)
