@@ -275,9 +275,17 @@ static void launch_tiles(const GemmArgs& a, int W, int tpb, hipStream_t s) {
 // path with two chunks per wave (at most 16 chunks a slice), and fold the slices afterwards.
 size_t gemm_split_ws_bytes(int64_t M, int64_t N, int64_t K) {
     const int64_t TK = tiles_k(K);
-    if (M > 16 || TK <= 32) return 0;
-    const int64_t splits = (TK + 15) / 16;
+    int64_t splits = 0;
+    if (M <= 16) {
+        if (TK > 32) splits = (TK + 15) / 16;
+    } else if (const int64_t per = prefill_split_tiles(M, N, K)) {
+        splits = (TK + per - 1) / per;
+    }
     return (size_t)splits * (size_t)M * (size_t)N * 4;
+}
+
+void launch_splitk_reduce(const GemmArgs& a, int splits, hipStream_t s) {
+    splitk_reduce<<<(unsigned)((a.M * a.N + 255) / 256), 256, 0, s>>>(a, splits);
 }
 
 hipError_t launch_gemm_decode(const GemmArgs& a_in, hipStream_t s) {
@@ -328,7 +336,7 @@ hipError_t launch_gemm_decode(const GemmArgs& a_in, hipStream_t s) {
         const int W = (int)((slots + rounds - 1) / rounds);
         launch_one<2, 1, 1024, false>(a, W, 1, s);
     }
-    if (splits > 1) splitk_reduce<<<(unsigned)((a.M * a.N + 255) / 256), 256, 0, s>>>(a, splits);
+    if (splits > 1) launch_splitk_reduce(a, splits, s);
     return hipGetLastError();
 }
 

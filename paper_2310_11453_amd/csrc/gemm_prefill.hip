@@ -182,9 +182,12 @@ __device__ inline void lds_write_b32(uint32_t ad, uint32_t v) {
 
 // NS = stages in the LDS ring (4 or 8: it must divide the 8 stages of a chunk).
 // Persistent: gridDim.x workgroups (one per CU) walk the tiles t = blockIdx.x, + gridDim.x, ...
-template <int BM, int BN, int WM, int WN, int NS>
+// GEN = false: the plain layer (one beta, Y = result): nothing of what follows costs anything.
+// GEN = true adds beta per column group (Eq. 13), accumulation over K-groups, the shift term of
+// Eq. 6 and K split over work items.
+template <int BM, int BN, int WM, int WN, int NS, bool GEN>
 __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs a, int grid_m,
-                                                                        int grid_n) {
+                                                                        int grid_n, int splits) {
     constexpr int THREADS = WM * WN * kWave;
     constexpr int WTM = BM / WM, WTN = BN / WN;
     constexpr int MI = WTM / 32, NI = WTN / 32;
@@ -201,24 +204,40 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
     __shared__ __attribute__((aligned(1024))) uint8_t smA[NS * STAGE_BYTES];
     __shared__ __attribute__((aligned(1024))) uint8_t smB[(BN / 16) * 1024];
     __shared__ __attribute__((aligned(16))) float smScale[2][BM];  // gamma_m / 128, per tile parity
-    __shared__ __attribute__((aligned(16))) float smBeta[2][BN];   // beta of each column's group
-    __shared__ __attribute__((aligned(16))) float smEta[2][BM];    // Eq. 6 only: eta_m
-    __shared__ __attribute__((aligned(16))) int smWsum[2][BN];     // Eq. 6 only: sum_k s[n,k]
+    __shared__ __attribute__((aligned(16))) float smBeta[2][GEN ? BN : 4];  // beta of each column's group
+    __shared__ __attribute__((aligned(16))) float smEta[2][GEN ? BM : 4];   // Eq. 6 only: eta_m
+    __shared__ __attribute__((aligned(16))) int smWsum[2][GEN ? BN : 4];    // Eq. 6 only: sum_k s[n,k]
     __shared__ __attribute__((aligned(16))) int smRowsum[2][BM];   // sum_k q[m,k]
 
     const int w = threadIdx.x / kWave, l = threadIdx.x % kWave;
     const int wm = w / WN, wn = w % WN;
     const int j = l & 31, g2 = l >> 5;
-    const int64_t TN = tiles_n(a.N), TK = tiles_k(a.K);
-    const int64_t M = a.M, K = a.K;
-    const int nst = (int)((K + kStageK - 1) / kStageK);
-    const int ntiles = grid_m * grid_n;
+    const int64_t TN = tiles_n(a.N);
+    const int64_t M = a.M;
+    // K, and what follows from it, belong to the work item: with a.split_k an item is one
+    // K-slice of one tile (splits slices per tile), else the whole K.
+    int64_t K = a.K, TK = tiles_k(K), k0 = 0;
+    int nst = (int)((K + kStageK - 1) / kStageK);
+    int64_t kfull = K / kStageK;
+    // chunks whose look-ahead stays inside K and that have a successor chunk
+    int64_t main_chunks = kfull >= NS + 7 ? (kfull - NS - 7) / 8 + 1 : 0;
+    const int64_t TKp = a.tk_pitch ? a.tk_pitch : tiles_k(a.K);  // tiles per tile row in memory
+    auto set_split = [&](int sp) {
+        if (!GEN || !a.split_k) return;
+        k0 = (int64_t)sp * a.split_k;
+        K = a.K - k0 < a.split_k ? a.K - k0 : a.split_k;
+        TK = tiles_k(K);
+        nst = (int)((K + kStageK - 1) / kStageK);
+        kfull = K / kStageK;
+        main_chunks = kfull >= NS + 7 ? (kfull - NS - 7) / 8 + 1 : 0;
+    };
+    const int ntiles = grid_m * grid_n * splits;  // work items
 
     // Tile order.  Workgroups are dealt round-robin to the 8 XCDs, each with its own L2; give
     // each XCD one contiguous range of tiles, N fastest, so that the tiles running together
     // on an XCD read the same rows of codes (the large operand: 16 KiB per stage against 2 KiB
     // of packed weights) and those rows come out of HBM once per XCD.
-    auto tile_origin = [&](int t, int64_t& m0, int64_t& n0) {
+    auto tile_origin = [&](int t, int64_t& m0, int64_t& n0, int& sp) {
         int logical = t;
         const int G = (int)gridDim.x;
         if ((ntiles & 7) == 0 && (G & 7) == 0) {
@@ -226,6 +245,12 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
             logical = (t & 7) * (ntiles >> 3) + q;
             // the XCD's range may end before the last round does
             if (q >= (ntiles >> 3)) logical = -1;
+        }
+        // items of one K-slice are neighbours: they share that slice of the codes
+        sp = 0;
+        if (GEN && splits > 1 && logical >= 0) {  // no division on the usual path
+            sp = logical / (grid_m * grid_n);
+            logical -= sp * (grid_m * grid_n);
         }
         m0 = logical < 0 ? -1 : (int64_t)(logical / grid_n) * BM;
         n0 = logical < 0 ? -1 : (int64_t)(logical % grid_n) * BN;
@@ -248,14 +273,14 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
             if (m0 + row > M - 1) row = (int)(M - 1 - m0);
             goff[q] = (uint32_t)row * (uint32_t)a.ldq + gseg[q];
         }
-        gbase = a.codes + m0 * a.ldq;
+        gbase = a.codes + m0 * a.ldq + k0;
         // packed weights: tile t of the block goes to smB + t KiB, lane for lane as it lies in
         // memory; wave w moves tiles w, w + NWAVES, ...  Columns past N read a valid tile.
 #pragma unroll
         for (int q = 0; q < NBW; ++q) {
             int64_t tn = (n0 >> 4) + w + q * NWAVES;
             if (tn > TN - 1) tn = TN - 1;
-            bsrc[q] = a.packed + tile_dword_offset(tn, 0, TK) + l * 4;
+            bsrc[q] = a.packed + tile_dword_offset(tn, k0 / kChunkK, TKp) + l * 4;
         }
     };
     const uint32_t lds_wave = (uint32_t)(w * kWave * 16);
@@ -333,44 +358,58 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
         }
     };
 
-    const int64_t kfull = K / kStageK;
-    // chunks whose look-ahead stays inside K and that have a successor chunk
-    const int64_t main_chunks = kfull >= NS + 7 ? (kfull - NS - 7) / 8 + 1 : 0;
-
-    int t = (int)blockIdx.x, parity = 0;
+    int t = (int)blockIdx.x, parity = 0, sp = 0;
     int64_t m0, n0;
-    tile_origin(t, m0, n0);
+    tile_origin(t, m0, n0, sp);
     if (m0 < 0) return;  // uniform for the whole workgroup
+    set_split(sp);
     setup_dma(m0, n0);
     issue_tile_start();
 
     while (true) {
-        // per-row gamma and row sum of the codes, per-column beta (Eq. 11, Eq. 13), for the
-        // epilogue
-        for (int r = threadIdx.x; r < BM; r += THREADS) {
-            const int64_t m = m0 + r;
-            float sc = 0.f;
-            int rs = 0;
-            if (m < M) {
-                // gamma / 128 is exact, so beta * (gamma / 128) below has the bits of (beta * gamma) / 128
-                sc = (a.per_tensor ? a.gamma[0] : a.gamma[m * a.gstride]) * 0.0078125f;
-                rs = a.rowsum[m * a.gstride];
+        if constexpr (GEN) {
+            // Per-row gamma and row sum of the codes, per-column beta (Eq. 11, Eq. 13), for the
+            // epilogue.  Thread i serves row i and column i (BM, BN <= THREADS); every load is
+            // issued before the first value is needed, so the tile pays one memory latency here.
+            {
+                static_assert(BM <= THREADS && BN <= THREADS, "one row and one column per thread");
+                const int i = threadIdx.x;
+                const int64_t m = m0 + i < M ? m0 + i : M - 1;
+                int64_t n = n0 + i;
+                if (n > a.N - 1) n = a.N - 1;
+                // branch-free (a branch here makes the compiler drain the loads issued so far):
+                // with one beta for the matrix the quotient is 0 by itself; the Eq. 6 operands are
+                // read from a valid stand-in address when they are not in use
+                const uint32_t bg = (uint32_t)n / (uint32_t)a.beta_rows;
+                const float gm = a.gamma[a.per_tensor ? 0 : m * a.gstride];
+                const int rs = a.rowsum[m * a.gstride];
+                const float b = a.beta[bg * a.beta_stride];
+                const float e = *(a.eta ? a.eta + m * a.gstride : a.gamma);
+                const int ws = *(a.eta ? a.wsum + n : a.rowsum);
+                if (i < BM) {
+                    // gamma / 128 is exact, so beta * (gamma / 128) has the bits of (beta * gamma) / 128
+                    lds_write_b32((uint32_t)(uintptr_t)&smScale[parity][i], __float_as_uint(gm * 0.0078125f));
+                    lds_write_b32((uint32_t)(uintptr_t)&smRowsum[parity][i], (uint32_t)rs);
+                    lds_write_b32((uint32_t)(uintptr_t)&smEta[parity][i], __float_as_uint(e));
+                }
+                if (i < BN) {
+                    lds_write_b32((uint32_t)(uintptr_t)&smBeta[parity][i], __float_as_uint(b));
+                    lds_write_b32((uint32_t)(uintptr_t)&smWsum[parity][i], (uint32_t)ws);
+                }
             }
-            lds_write_b32((uint32_t)(uintptr_t)&smScale[parity][r], __float_as_uint(sc));
-            lds_write_b32((uint32_t)(uintptr_t)&smRowsum[parity][r], (uint32_t)rs);
-        }
-        for (int c = threadIdx.x; c < BN; c += THREADS) {
-            int64_t n = n0 + c;
-            if (n > a.N - 1) n = a.N - 1;
-            const float b = a.beta[((uint32_t)n / (uint32_t)a.beta_rows) * a.beta_stride];
-            lds_write_b32((uint32_t)(uintptr_t)&smBeta[parity][c], __float_as_uint(b));
-            if (a.eta) lds_write_b32((uint32_t)(uintptr_t)&smWsum[parity][c], (uint32_t)a.wsum[n]);
-        }
-        if (a.eta) {
+        } else {
+            // per-row dequantisation scale (Eq. 11) and row sum of the codes, for the epilogue
+            const float beta = *a.beta;
             for (int r = threadIdx.x; r < BM; r += THREADS) {
-                const int64_t m = m0 + r < M ? m0 + r : M - 1;
-                lds_write_b32((uint32_t)(uintptr_t)&smEta[parity][r],
-                              __float_as_uint(a.eta[m * a.gstride]));
+                const int64_t m = m0 + r;
+                float sc = 0.f;
+                int rs = 0;
+                if (m < M) {
+                    sc = (beta * (a.per_tensor ? a.gamma[0] : a.gamma[m])) / 128.0f;
+                    rs = a.rowsum[m];
+                }
+                lds_write_b32((uint32_t)(uintptr_t)&smScale[parity][r], __float_as_uint(sc));
+                lds_write_b32((uint32_t)(uintptr_t)&smRowsum[parity][r], (uint32_t)rs);
             }
         }
 #pragma unroll
@@ -406,8 +445,11 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
         block_barrier();
         const int t_next = t + (int)gridDim.x;
         int64_t m0n = -1, n0n = -1;
-        if (t_next < ntiles) tile_origin(t_next, m0n, n0n);
+        int spn = 0;
+        const int sp_cur = sp;  // the epilogue below still belongs to this item
+        if (t_next < ntiles) tile_origin(t_next, m0n, n0n, spn);
         if (m0n >= 0) {
+            set_split(spn);
             setup_dma(m0n, n0n);
             issue_tile_start();
         }
@@ -417,14 +459,15 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
         float bcol[NI];
 #pragma unroll
         for (int s = 0; s < NI; ++s)
-            bcol[s] = lds_read_f32((uint32_t)(uintptr_t)&smBeta[parity][wn * WTN + 32 * s + j]);
+            bcol[s] = GEN ? lds_read_f32((uint32_t)(uintptr_t)&smBeta[parity][wn * WTN + 32 * s + j])
+                          : 1.f;
         const uint32_t sc_base = (uint32_t)(uintptr_t)&smScale[parity][wm * WTM + 4 * g2];
         const uint32_t rs_base = (uint32_t)(uintptr_t)&smRowsum[parity][wm * WTM + 4 * g2];
-        const bool special = a.out_acc || a.eta != nullptr || a.accumulate;
+        const bool special = a.out_acc || (GEN && (a.eta != nullptr || a.accumulate || a.split_k != 0));
         float wcol[NI];  // Eq. 6 only
 #pragma unroll
         for (int s = 0; s < NI; ++s)
-            wcol[s] = a.eta ? (float)__float_as_int(lds_read_f32(
+            wcol[s] = (GEN && a.eta) ? (float)__float_as_int(lds_read_f32(
                                   (uint32_t)(uintptr_t)&smWsum[parity][wn * WTN + 32 * s + j]))
                             : 0.f;
         // Register allocation here is at the limit of 256 and sensitive to the form of these
@@ -449,18 +492,23 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
                         if (n >= a.N) continue;
                         const int pm = 2 * acc[mi][s][r] - rs4[rr];
                         // y = acc * ((beta * gamma) / 128)
-                        float y = (float)pm * (bcol[s] * sc4[rr]);
+                        // (GEN: sc4 holds gamma / 128, else the whole scale)
+                        float y = GEN ? (float)pm * (bcol[s] * sc4[rr]) : (float)pm * sc4[rr];
                         if (special) {  // uniform
+                            if (GEN && a.split_k) {  // K-slice: 2 * sum_k q b, folded by the reduce kernel
+                                a.split_ws[((int64_t)sp_cur * M + m) * a.N + n] = 2 * acc[mi][s][r];
+                                continue;
+                            }
                             if (a.out_acc) {
                                 reinterpret_cast<int*>(a.Y)[m * a.N + n] = pm;
                                 continue;
                             }
-                            if (a.eta) {  // Eq. 6: + (beta * eta_m) * sum_k s[n,k]
+                            if (GEN && a.eta) {  // Eq. 6: + (beta * eta_m) * sum_k s[n,k]
                                 const float e = lds_read_f32(
                                     (uint32_t)(uintptr_t)&smEta[parity][wm * WTM + 32 * mi + 8 * rq + 4 * g2 + rr]);
                                 y = y + (bcol[s] * e) * wcol[s];
                             }
-                            if (a.accumulate) y += a.Y[m * a.N + n];  // a later K-group
+                            if (GEN && a.accumulate) y += a.Y[m * a.N + n];  // a later K-group
                         }
                         a.Y[m * a.N + n] = y;
                     }
@@ -468,6 +516,7 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
             }
         if (m0n < 0) break;
         t = t_next;
+        sp = spn;
         m0 = m0n;
         n0 = n0n;
         parity ^= 1;
@@ -487,19 +536,50 @@ static int num_cus() {
 }
 
 template <int BM, int BN, int WM, int WN, int NS>
-static void launch_tile(const GemmArgs& a, hipStream_t s) {
+static void launch_tile(const GemmArgs& a, hipStream_t s, int splits = 1) {
+    const bool plain = a.beta_rows >= a.N && a.gstride == 1 && !a.eta && !a.accumulate &&
+                       !a.split_k && splits == 1;
     const int grid_m = (int)((a.M + BM - 1) / BM), grid_n = (int)((a.N + BN - 1) / BN);
-    const int ntiles = grid_m * grid_n;
+    const int ntiles = grid_m * grid_n * splits;
     // one workgroup per CU for the 8-wave tiles; the small 4-wave tile fits four per CU
     int grid = num_cus() * (WM * WN <= 4 ? 4 : 1);
     if (const char* e = getenv("BITLINEAR_PREFILL_GRID")) grid = atoi(e);  // bench-only override
     if (grid > ntiles) grid = ntiles;
-    gemm_prefill_kernel<BM, BN, WM, WN, NS>
-        <<<(unsigned)grid, WM * WN * kWave, 0, s>>>(a, grid_m, grid_n);
+    if (plain)
+        gemm_prefill_kernel<BM, BN, WM, WN, NS, false>
+            <<<(unsigned)grid, WM * WN * kWave, 0, s>>>(a, grid_m, grid_n, 1);
+    else
+        gemm_prefill_kernel<BM, BN, WM, WN, NS, true>
+            <<<(unsigned)grid, WM * WN * kWave, 0, s>>>(a, grid_m, grid_n, splits);
+}
+
+// Small batches (16 < M <= 64) leave most of the chip idle when N supplies few 64 x 128 tiles
+// (fewer than half the CUs): K is then split so that about two work items run per CU, as long
+// as the partial sums (M*N*4 bytes a slice) stay below the packed weights.  Measured on the
+// 28672 -> 7168 layer at M = 64: 95 us unsplit, 33 us in 8 slices; with 168 tiles or more a
+// split only adds traffic.  256 CUs are assumed (the workspace is sized from this too).
+// Returns tiles of K per slice, 0 = no split.
+int64_t prefill_split_tiles(int64_t M, int64_t N, int64_t K) {
+    if (M <= 16 || M > 64) return 0;
+    if (const char* e = getenv("BITLINEAR_PREFILL_SPLIT_TILES")) {  // bench-only override
+        const int64_t per = atoi(e);
+        return per > 0 && per < tiles_k(K) ? per : 0;
+    }
+    const int64_t tiles = ((M + 63) / 64) * ((N + 127) / 128), TK = tiles_k(K);
+    if (tiles > 128) return 0;
+    int64_t smax = 512 / tiles;
+    if (smax > K / (32 * M)) smax = K / (32 * M);
+    if (smax > 16) smax = 16;
+    if (smax < 2) return 0;
+    int64_t per = (TK + smax - 1) / smax;
+    if (per < 2) per = 2;
+    return (TK + per - 1) / per >= 2 ? per : 0;
 }
 
 // K < 2^22 is required (the per-lane offset into a block of 256 rows is kept in 32 bits).
-hipError_t launch_gemm_prefill(const GemmArgs& a, hipStream_t s) {
+hipError_t launch_gemm_prefill(const GemmArgs& a_in, hipStream_t s) {
+    GemmArgs a = a_in;
+    a.split_k = 0;  // set here only
     if (a.K >= ((int64_t)1 << 22) || a.ldq >= ((int64_t)1 << 22)) return hipErrorInvalidValue;
     const char* e = getenv("BITLINEAR_PREFILL_TILE");  // bench-only override: 0, 1, 2
     int pick;
@@ -513,8 +593,20 @@ hipError_t launch_gemm_prefill(const GemmArgs& a, hipStream_t s) {
         };
         pick = cost(128, 256) < cost(256, 256) ? 1 : 2;
     }
-    if (pick == 0) launch_tile<64, 128, 1, 4, 4>(a, s);
-    else if (pick == 1) launch_tile<128, 256, 2, 4, 8>(a, s);
+    if (pick == 0) {
+        const int64_t per = prefill_split_tiles(a.M, a.N, a.K);
+        const size_t need = gemm_split_ws_bytes(a.M, a.N, a.K);
+        if (per && a.split_ws && a.split_ws_bytes >= need && !getenv("BITLINEAR_PREFILL_NOSPLIT")) {
+            GemmArgs b = a;
+            const int splits = (int)((tiles_k(a.K) + per - 1) / per);
+            b.tk_pitch = a.tk_pitch ? a.tk_pitch : tiles_k(a.K);
+            b.split_k = per * kChunkK;
+            launch_tile<64, 128, 1, 4, 4>(b, s, splits);
+            launch_splitk_reduce(b, splits, s);
+        } else {
+            launch_tile<64, 128, 1, 4, 4>(a, s);
+        }
+    } else if (pick == 1) launch_tile<128, 256, 2, 4, 8>(a, s);
     else launch_tile<256, 256, 2, 4, 8>(a, s);
     return hipGetLastError();
 }

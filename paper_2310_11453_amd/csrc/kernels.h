@@ -74,6 +74,8 @@ struct GemmArgs {
     size_t split_ws_bytes;  // what the caller offers; too small or nullptr: no split
 };
 size_t gemm_split_ws_bytes(int64_t M, int64_t N, int64_t K);
+int64_t prefill_split_tiles(int64_t M, int64_t N, int64_t K);
+void launch_splitk_reduce(const GemmArgs& a, int splits, hipStream_t s);
 hipError_t launch_gemm_decode(const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm_prefill(const GemmArgs& a, hipStream_t s);
 

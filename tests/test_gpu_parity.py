@@ -237,11 +237,13 @@ def test_full_size_30b_batched_decode(bl, li, M):
 
 # ------------------------------------------------------------------ K split across workgroups
 @pytest.mark.parametrize("M,K,N", [(1, 28672, 7168), (16, 28672, 7168), (5, 16896, 200),
-                                   (16, 17920, 1040), (3, 32768, 64)])
+                                   (16, 17920, 1040), (3, 32768, 64), (64, 7168, 2048),
+                                   (40, 4096, 384), (64, 28672, 7168), (50, 3616, 130)])
 def test_forward_long_k_split_matches_single_pass(bl, M, K, N):
-    """K > 16384 at M <= 16: bitlinear_forward splits K over workgroups and folds the slices in
-    a second kernel; the result must equal the single-pass kernel's (bitlinear_matmul has no
-    workspace and never splits) bit for bit, and the oracle's on sampled outputs."""
+    """Long K at small M (K > 16384 at M <= 16; 16 < M <= 64 when N alone leaves workgroup slots
+    empty): bitlinear_forward splits K over workgroups and folds the slices in a second kernel;
+    the result must equal the single-pass kernel's (bitlinear_matmul without a workspace never
+    splits) bit for bit, and the oracle's on sampled outputs."""
     print(f"split-K forward M={M} K={K} N={N}", flush=True)
     X = wl.make_activation(M, K, seed=wl.seed_for(3, K + N + M))
     W = wl.make_weight(N, K, 0.01, seed=wl.seed_for(3, K + N))
