@@ -13,10 +13,15 @@
 //   St  [K][Np]   +-1 from the packed bits         (B operand of dX)
 //   gwT [N][Mp]   dY transposed, scaled, cast      (A operand of dW, reduction over M)
 //   qT  [K][Mp]   codes transposed, cast           (B operand of dW)
-// and one kernel, C[I][J] = scale * sum_r A[I][r] B[J][r], serves both products.  The
-// preparation passes are HBM-bound and small next to the 2*M*N*K flops of each product.
+// (one pass over dY writes g and gwT) and one product, C[I][J] = scale * sum_r A[I][r] B[J][r],
+// serves both: a persistent 256 x 256 kernel fed by DMA for large operands, a plain 256 x 128
+// kernel otherwise.  The preparation passes are HBM-bound and small next to the 2*M*N*K flops
+// of each product.
+#include <stdlib.h>
+
 #include "common.h"
 #include "kernels.h"
+#include "ring.h"
 
 namespace bl {
 
@@ -29,50 +34,94 @@ __device__ inline uint32_t bf16_bits(float v) {
     return u >> 16;
 }
 
-// ---- g[M][Np] = bf16(dY[M][N]), zero padding ------------------------------------------
-__global__ __launch_bounds__(256) void cast_rows_bf16(const float* __restrict__ dY, int64_t M,
-                                                      int64_t N, int64_t Np,
-                                                      uint16_t* __restrict__ g) {
-    const int64_t pairs = Np / 2;
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= M * pairs) return;
-    const int64_t m = idx / pairs, n = (idx % pairs) * 2;
-    const float a = n < N ? dY[m * N + n] : 0.f;
-    const float b = n + 1 < N ? dY[m * N + n + 1] : 0.f;
-    reinterpret_cast<uint32_t*>(g)[idx] = bf16_bits(a) | (bf16_bits(b) << 16);
+// Rows of the bf16 copies are `ld` elements apart, ld >= the padded length: see row_pitch().
+//
+// ---- in[R][C] (fp32 or int8) -> bf16 copies, one read of the input ----------------------------
+//   rows[R][Cp]  = bf16(in)                      (row pitch ld_rows; columns C..Cp-1 zero)
+//   tr  [C][Rp]  = bf16(scale_r * in)^T          (row pitch ld_tr; columns R..Rp-1 zero)
+// scale_r = row_gamma[r] / 128 or 1.  Either output may be null.  A workgroup takes a 64 x 64
+// tile: each thread reads 4 x 4 consecutive elements, writes its 8-byte pieces of `rows`, and
+// the transpose goes through LDS (row pitch 66 halfwords: the 4-row steps of the 16 lanes that
+// build one output row fall on distinct banks) and leaves as 8-byte pieces too.
+// VEC: C % 4 == 0 and `in` 16-byte aligned, so that a thread's 4 elements are one load.
+template <typename IN, bool VEC>
+__global__ __launch_bounds__(256) void cast_transpose_bf16(const IN* __restrict__ in, int64_t R,
+                                                           int64_t C, int64_t Cp, int64_t ld_rows,
+                                                           int64_t Rp, int64_t ld_tr,
+                                                           const float* __restrict__ row_gamma,
+                                                           uint16_t* __restrict__ rows,
+                                                           uint16_t* __restrict__ tr) {
+    __shared__ __attribute__((aligned(8))) uint16_t tile[64][66];
+    const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int idx = it * 256 + threadIdx.x;
+        const int rl = idx >> 4, cl = (idx & 15) * 4;
+        const int64_t r = r0 + rl, c = c0 + cl;
+        float v[4] = {0.f, 0.f, 0.f, 0.f};
+        if (r < R) {
+            if (VEC && c + 3 < C) {
+                if constexpr (sizeof(IN) == 4) {
+                    const float4 t = *reinterpret_cast<const float4*>(in + r * C + c);
+                    v[0] = t.x, v[1] = t.y, v[2] = t.z, v[3] = t.w;
+                } else {
+                    const char4 t = *reinterpret_cast<const char4*>(in + r * C + c);
+                    v[0] = (float)t.x, v[1] = (float)t.y, v[2] = (float)t.z, v[3] = (float)t.w;
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (c + e < C) v[e] = (float)in[r * C + c + e];
+            }
+        }
+        if (rows && r < R && c < Cp)
+            *reinterpret_cast<uint2*>(rows + r * ld_rows + c) =
+                make_uint2(bf16_bits(v[0]) | (bf16_bits(v[1]) << 16),
+                           bf16_bits(v[2]) | (bf16_bits(v[3]) << 16));
+        if (row_gamma && r < R) {
+            const float sc = row_gamma[r] / 128.0f;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = v[e] * sc;
+        }
+        uint32_t* t32 = reinterpret_cast<uint32_t*>(&tile[rl][cl]);
+        t32[0] = bf16_bits(v[0]) | (bf16_bits(v[1]) << 16);
+        t32[1] = bf16_bits(v[2]) | (bf16_bits(v[3]) << 16);
+    }
+    if (!tr) return;
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int idx = it * 256 + threadIdx.x;
+        const int cl = idx >> 4, rl = (idx & 15) * 4;
+        const int64_t c = c0 + cl, r = r0 + rl;
+        if (c < C && r < Rp)
+            *reinterpret_cast<uint2*>(tr + c * ld_tr + r) =
+                make_uint2((uint32_t)tile[rl][cl] | ((uint32_t)tile[rl + 1][cl] << 16),
+                           (uint32_t)tile[rl + 2][cl] | ((uint32_t)tile[rl + 3][cl] << 16));
+    }
 }
 
-// ---- out[C][Rp] = bf16(scale_r * in[R][C])^T, 64x64 tiles through LDS ---------------------
-// IN = float (dY, optional per-row scale gamma_r/128) or int8_t (codes).
 template <typename IN>
-__global__ __launch_bounds__(256) void transpose_cast_bf16(const IN* __restrict__ in, int64_t R,
-                                                           int64_t C, int64_t Rp,
-                                                           const float* __restrict__ row_gamma,
-                                                           uint16_t* __restrict__ out) {
-    __shared__ uint16_t tile[64][66];
-    const int64_t r0 = (int64_t)blockIdx.y * 64, c0 = (int64_t)blockIdx.x * 64;
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    for (int rr = ty; rr < 64; rr += 4) {
-        const int64_t r = r0 + rr, c = c0 + tx;
-        float v = 0.f;
-        if (r < R && c < C) {
-            v = (float)in[r * C + c];
-            if (row_gamma) v = v * (row_gamma[r] / 128.0f);
-        }
-        tile[rr][tx] = (uint16_t)bf16_bits(v);
-    }
-    __syncthreads();
-    for (int cc = ty; cc < 64; cc += 4) {
-        const int64_t c = c0 + cc, r = r0 + tx;
-        if (c < C && r < Rp) out[c * Rp + r] = tile[tx][cc];
-    }
+static void launch_cast_transpose(const IN* in, int64_t R, int64_t C, int64_t Cp, int64_t ld_rows,
+                                  int64_t Rp, int64_t ld_tr, const float* row_gamma, uint16_t* rows,
+                                  uint16_t* tr, hipStream_t s) {
+    // the grid covers the padded extents of whichever outputs are written
+    const int64_t cols = rows ? Cp : C, rws = tr ? Rp : R;
+    dim3 grid((unsigned)((cols + 63) / 64), (unsigned)((rws + 63) / 64));
+    const bool vec = C % 4 == 0 && ((uintptr_t)in & 15) == 0;
+    if (vec)
+        cast_transpose_bf16<IN, true><<<grid, 256, 0, s>>>(in, R, C, Cp, ld_rows, Rp, ld_tr,
+                                                           row_gamma, rows, tr);
+    else
+        cast_transpose_bf16<IN, false><<<grid, 256, 0, s>>>(in, R, C, Cp, ld_rows, Rp, ld_tr,
+                                                            row_gamma, rows, tr);
 }
 
 // ---- St[K][Np] = +-1 as bf16 from the packed tiles ------------------------------------------
 // One workgroup expands 64 weight rows (4 tiles) x 512 columns: thread -> (k, 8 rows), 16 bytes.
 __global__ __launch_bounds__(256) void bits_transpose_bf16(const uint32_t* __restrict__ packed,
                                                            int64_t N, int64_t K, int64_t Np,
-                                                           uint16_t* __restrict__ St) {
+                                                           int64_t ld, uint16_t* __restrict__ St) {
     __shared__ uint32_t sm[4][256];
     const int64_t TN = tiles_n(N), TK = tiles_k(K);
     const int64_t tn0 = (int64_t)blockIdx.x * 4, tk = blockIdx.y;
@@ -102,7 +151,7 @@ __global__ __launch_bounds__(256) void bits_transpose_bf16(const uint32_t* __res
             }
             w[p] = pair;
         }
-        *reinterpret_cast<uint4*>(St + k * Np + n) = make_uint4(w[0], w[1], w[2], w[3]);
+        *reinterpret_cast<uint4*>(St + k * ld + n) = make_uint4(w[0], w[1], w[2], w[3]);
     }
 }
 
@@ -116,7 +165,7 @@ constexpr int kBwdPitch = 80;
 template <int BM, int BN>
 __global__ __launch_bounds__(256, 2) void gemm_tn_bf16(const uint16_t* __restrict__ A,
                                                        const uint16_t* __restrict__ B, int64_t I,
-                                                       int64_t J, int64_t Rp,
+                                                       int64_t J, int64_t Rp, int64_t ld,
                                                        const float* __restrict__ scale_ptr,
                                                        float scale_mul, float* __restrict__ C) {
     constexpr int WTM = BM / 2, WTN = BN / 2, MI = WTM / 32, NI = WTN / 32;
@@ -136,14 +185,14 @@ __global__ __launch_bounds__(256, 2) void gemm_tn_bf16(const uint16_t* __restric
             const int p = threadIdx.x + q * 256;
             int64_t row = i0 + (p >> 2);
             if (row > I - 1) row = I - 1;
-            ra[q] = *reinterpret_cast<const v4i*>(A + row * Rp + r0 + (p & 3) * 8);
+            ra[q] = *reinterpret_cast<const v4i*>(A + row * ld + r0 + (p & 3) * 8);
         }
 #pragma unroll
         for (int q = 0; q < PB; ++q) {
             const int p = threadIdx.x + q * 256;
             int64_t row = j0 + (p >> 2);
             if (row > J - 1) row = J - 1;
-            rb[q] = *reinterpret_cast<const v4i*>(B + row * Rp + r0 + (p & 3) * 8);
+            rb[q] = *reinterpret_cast<const v4i*>(B + row * ld + r0 + (p & 3) * 8);
         }
     };
     auto store_stage = [&](int buf) {
@@ -212,44 +261,288 @@ __global__ __launch_bounds__(256, 2) void gemm_tn_bf16(const uint16_t* __restric
         }
 }
 
+// ---- the same product for large operands: LDS ring fed by DMA --------------------------------
+// Workgroup tile 256 x 256, eight waves of 128 x 64 (4 x 2 MFMA tiles), one workgroup per CU,
+// persistent over the tiles.  A stage is 32 reduction elements: 64-byte rows of A and of B,
+// streamed global -> LDS by global_load_lds_dwordx4 into a ring of NS stages; the 16-byte
+// segments of a row are XOR-swizzled with (row/4)%4, so the operand reads of 16 consecutive rows
+// touch every bank once.  The unit of work is a half-step (16 elements, 8 MFMAs): one asm block
+// issues the LDS reads of the next half-step's operands, then the MFMAs of the current one, then
+// waits for the reads.  Between the half-steps of stage st every wave waits for its own DMA of
+// stage st+1 (s_waitcnt vmcnt(n), n counted by hand), meets the others at a bare s_barrier, and
+// the DMA of stage st+NS-1 goes to the buffer stage st-1 has left.
+__device__ inline void bf16_read_ops(v4i (&a)[4], v4i (&b)[2], uint32_t ad_a, uint32_t ad_b) {
+    asm volatile(
+        "ds_read_b128 %0, %6\n\t"
+        "ds_read_b128 %1, %6 offset:2048\n\t"
+        "ds_read_b128 %2, %6 offset:4096\n\t"
+        "ds_read_b128 %3, %6 offset:6144\n\t"
+        "ds_read_b128 %4, %7\n\t"
+        "ds_read_b128 %5, %7 offset:2048\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(a[0]), "=&v"(a[1]), "=&v"(a[2]), "=&v"(a[3]), "=&v"(b[0]), "=&v"(b[1])
+        : "v"(ad_a), "v"(ad_b));
+}
+// acc[mi][s] += ac[mi] x bc[s]; an, bn = operands at ad_a, ad_b, complete on exit
+__device__ inline void bf16_half_step(v16f (&acc)[4][2], const v4i (&ac)[4], const v4i (&bc)[2],
+                                      v4i (&an)[4], v4i (&bn)[2], uint32_t ad_a, uint32_t ad_b) {
+    asm volatile(
+        "ds_read_b128 %8, %20\n\t"
+        "ds_read_b128 %9, %20 offset:2048\n\t"
+        "ds_read_b128 %12, %21\n\t"
+        "ds_read_b128 %13, %21 offset:2048\n\t"
+        "ds_read_b128 %10, %20 offset:4096\n\t"
+        "ds_read_b128 %11, %20 offset:6144\n\t"
+        "v_mfma_f32_32x32x16_bf16 %0, %14, %18, %0\n\t"
+        "v_mfma_f32_32x32x16_bf16 %1, %14, %19, %1\n\t"
+        "v_mfma_f32_32x32x16_bf16 %2, %15, %18, %2\n\t"
+        "v_mfma_f32_32x32x16_bf16 %3, %15, %19, %3\n\t"
+        "v_mfma_f32_32x32x16_bf16 %4, %16, %18, %4\n\t"
+        "v_mfma_f32_32x32x16_bf16 %5, %16, %19, %5\n\t"
+        "v_mfma_f32_32x32x16_bf16 %6, %17, %18, %6\n\t"
+        "v_mfma_f32_32x32x16_bf16 %7, %17, %19, %7\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "+v"(acc[0][0]), "+v"(acc[0][1]), "+v"(acc[1][0]), "+v"(acc[1][1]), "+v"(acc[2][0]),
+          "+v"(acc[2][1]), "+v"(acc[3][0]), "+v"(acc[3][1]), "=&v"(an[0]), "=&v"(an[1]),
+          "=&v"(an[2]), "=&v"(an[3]), "=&v"(bn[0]), "=&v"(bn[1])
+        : "v"(ac[0]), "v"(ac[1]), "v"(ac[2]), "v"(ac[3]), "v"(bc[0]), "v"(bc[1]), "v"(ad_a),
+          "v"(ad_b));
+}
+
+template <int NS>
+__global__ __launch_bounds__(512, 2) void gemm_tn_bf16_ring(const uint16_t* __restrict__ A,
+                                                            const uint16_t* __restrict__ B,
+                                                            int64_t I, int64_t J, int64_t Rp,
+                                                            int64_t ld,
+                                                            const float* __restrict__ scale_ptr,
+                                                            float scale_mul, float* __restrict__ C,
+                                                            int grid_i, int grid_j) {
+    constexpr int BM = 256, BN = 256, WN = 4, THREADS = 512, WTM = 128, WTN = 64, MI = 4, NI = 2;
+    constexpr int PA = BM * 4 / THREADS, PB = BN * 4 / THREADS, P = PA + PB;
+    constexpr int A_BYTES = BM * 64, STAGE_BYTES = (BM + BN) * 64;
+    static_assert((NS - 1) * P < 64, "vmcnt range");
+    __shared__ __attribute__((aligned(1024))) uint8_t sm[NS * STAGE_BYTES];
+
+    const int w = threadIdx.x / kWave, l = threadIdx.x % kWave;
+    const int wm = w / WN, wn = w % WN;
+    const int j = l & 31, g2 = l >> 5;
+    const int nst = (int)(Rp / 32);
+    const int ntiles = grid_i * grid_j;
+    // groups of NS stages whose look-ahead stage st+NS-1 exists for every stage of the group
+    const int main_groups = nst >= 2 * NS - 1 ? (nst - (2 * NS - 1)) / NS + 1 : 0;
+
+    // Workgroups are dealt round-robin to the 8 XCDs (one L2 each): an XCD gets one contiguous
+    // range of tiles, J fastest, so that the tiles it runs together share rows of A.
+    auto tile_origin = [&](int t, int64_t& i0, int64_t& j0) {
+        int logical = t;
+        const int G = (int)gridDim.x;
+        if ((ntiles & 7) == 0 && (G & 7) == 0) {
+            const int q = ((t % G) >> 3) + (t / G) * (G >> 3);
+            logical = (t & 7) * (ntiles >> 3) + q;
+            if (q >= (ntiles >> 3)) logical = -1;
+        }
+        i0 = logical < 0 ? -1 : (int64_t)(logical / grid_j) * BM;
+        j0 = logical < 0 ? -1 : (int64_t)(logical % grid_j) * BN;
+    };
+
+    // DMA: thread -> PA + PB pieces of 16 bytes per stage; piece = (row, swizzled segment).
+    // Rows past the matrix re-read its last row (their results are never stored).
+    uint32_t goffA[PA], goffB[PB];
+    const uint8_t *baseA = nullptr, *baseB = nullptr;
+    const uint32_t pitch = (uint32_t)ld * 2;
+    auto setup_dma = [&](int64_t i0, int64_t j0) {
+#pragma unroll
+        for (int q = 0; q < PA; ++q) {
+            const int slot = q * THREADS + threadIdx.x;
+            int row = slot >> 2;
+            const int seg = ((slot & 3) ^ ((row >> 2) & 3)) * 16;
+            if (i0 + row > I - 1) row = (int)(I - 1 - i0);
+            goffA[q] = (uint32_t)row * pitch + seg;
+        }
+#pragma unroll
+        for (int q = 0; q < PB; ++q) {
+            const int slot = q * THREADS + threadIdx.x;
+            int row = slot >> 2;
+            const int seg = ((slot & 3) ^ ((row >> 2) & 3)) * 16;
+            if (j0 + row > J - 1) row = (int)(J - 1 - j0);
+            goffB[q] = (uint32_t)row * pitch + seg;
+        }
+        baseA = reinterpret_cast<const uint8_t*>(A) + i0 * (int64_t)pitch;
+        baseB = reinterpret_cast<const uint8_t*>(B) + j0 * (int64_t)pitch;
+    };
+    const uint32_t lds_wave = (uint32_t)(w * kWave * 16);
+    // stage `st` into ring slot st % NS; `src_st` is the stage whose bytes are read (== st, or
+    // the last stage when st does not exist: the slot is filled with bytes nobody uses)
+    auto issue = [&](int st, int src_st) {
+        uint8_t* dst = sm + (st % NS) * STAGE_BYTES + lds_wave;
+#pragma unroll
+        for (int q = 0; q < PA; ++q)
+            __builtin_amdgcn_global_load_lds(
+                (const void*)(baseA + (int64_t)src_st * 64 + goffA[q]),
+                (__attribute__((address_space(3))) void*)(dst + q * THREADS * 16), 16, 0, 0);
+#pragma unroll
+        for (int q = 0; q < PB; ++q)
+            __builtin_amdgcn_global_load_lds(
+                (const void*)(baseB + (int64_t)src_st * 64 + goffB[q]),
+                (__attribute__((address_space(3))) void*)(dst + A_BYTES + q * THREADS * 16), 16, 0,
+                0);
+    };
+    auto issue_tile_start = [&]() {
+#pragma unroll
+        for (int s = 0; s < NS - 1; ++s) issue(s, s < nst ? s : nst - 1);
+    };
+
+    // lane's operand addresses inside a stage: row, segment (2h + g2) ^ swizzle
+    const int sw = (j >> 2) & 3;
+    const uint32_t smb = (uint32_t)(uintptr_t)sm;
+    const uint32_t a_lane[2] = {smb + (wm * WTM + j) * 64 + ((g2) ^ sw) * 16,
+                                smb + (wm * WTM + j) * 64 + ((2 + g2) ^ sw) * 16};
+    const uint32_t b_lane[2] = {smb + A_BYTES + (wn * WTN + j) * 64 + ((g2) ^ sw) * 16,
+                                smb + A_BYTES + (wn * WTN + j) * 64 + ((2 + g2) ^ sw) * 16};
+    auto ring = [&](int st) { return (uint32_t)((st % NS) * STAGE_BYTES); };
+
+    v16f acc[MI][NI];
+    v4i ax[MI], ay[MI], bx[NI], by[NI];
+    // In: ax/bx = operands of (st, half 0).  Out: operands of (st+1, half 0); for the last stage
+    // these are stale ring bytes that nobody uses.
+    auto stage = [&](int st, bool ahead) {
+        bf16_half_step(acc, ax, bx, ay, by, a_lane[1] + ring(st), b_lane[1] + ring(st));
+        // younger than stage st+1: stages st+2 .. st+NS-2
+        if (ahead) wait_vmcnt<(NS - 3) * P>();
+        else wait_vmcnt<0>();
+        block_barrier();
+        if (ahead) issue(st + NS - 1, st + NS - 1);
+        bf16_half_step(acc, ay, by, ax, bx, a_lane[0] + ring(st + 1), b_lane[0] + ring(st + 1));
+    };
+
+    const float scale = (scale_ptr ? *scale_ptr : 1.0f) * scale_mul;
+    int t = (int)blockIdx.x;
+    int64_t i0, j0;
+    tile_origin(t, i0, j0);
+    if (i0 < 0) return;  // uniform for the whole workgroup
+    setup_dma(i0, j0);
+    issue_tile_start();
+
+    while (true) {
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int s = 0; s < NI; ++s)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[mi][s][r] = 0.f;
+
+        wait_vmcnt<(NS - 2) * P>();  // younger than stage 0: stages 1 .. NS-2
+        block_barrier();
+        bf16_read_ops(ax, bx, a_lane[0], b_lane[0]);
+
+        for (int gidx = 0; gidx < main_groups; ++gidx)
+            static_for<0, NS>([&](auto ic) { stage(gidx * NS + decltype(ic)::value, true); });
+        for (int st = main_groups * NS; st < nst; ++st) stage(st, st + NS - 1 < nst);
+
+        // the accumulators were last written inside an asm block: let the matrix pipeline
+        // retire them before ordinary instructions read them
+        asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
+
+        // every wave is done with the ring: start the next tile's stream, then store
+        block_barrier();
+        const int t_next = t + (int)gridDim.x;
+        int64_t i0n = -1, j0n = -1;
+        if (t_next < ntiles) tile_origin(t_next, i0n, j0n);
+        if (i0n >= 0) {
+            setup_dma(i0n, j0n);
+            issue_tile_start();
+        }
+
+        // lane (j, g2) holds column j0 + .. + j, rows 8*(r/4) + 4*g2 + r%4 of each sub-tile
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t i = i0 + wm * WTM + 32 * mi + 8 * (r >> 2) + 4 * g2 + (r & 3);
+                if (i >= I) continue;
+#pragma unroll
+                for (int s = 0; s < NI; ++s) {
+                    const int64_t jj = j0 + wn * WTN + 32 * s + j;
+                    if (jj < J) C[i * J + jj] = scale * acc[mi][s][r];
+                }
+            }
+        if (i0n < 0) break;
+        t = t_next;
+        i0 = i0n;
+        j0 = j0n;
+    }
+}
+
+static int bwd_num_cus() {
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess)
+            n = prop.multiProcessorCount;
+        if (n <= 0) n = 256;
+    }
+    return n;
+}
+
+// C[I][J] = scale * A[I][:] . B[J][:]: the ring kernel when its 256 x 256 tiles fill at least half
+// the CUs, else the 256 x 128 kernel with a workgroup per tile.
+static void launch_gemm_tn(const uint16_t* A, const uint16_t* B, int64_t I, int64_t J, int64_t Rp,
+                           int64_t ld, const float* scale_ptr, float scale_mul, float* C,
+                           hipStream_t s) {
+    const int64_t gi = (I + 255) / 256, gj = (J + 255) / 256;
+    // the ring kernel keeps a lane's byte offset into a block of 256 rows in 32 bits
+    int ring = gi * gj * 2 >= bwd_num_cus() && ld < ((int64_t)1 << 22);
+    if (const char* e = getenv("BITLINEAR_BWD_RING")) ring = atoi(e) != 0 && ld < ((int64_t)1 << 22);
+    if (ring) {
+        int grid = bwd_num_cus();
+        if (const char* e = getenv("BITLINEAR_BWD_GRID")) grid = atoi(e) > 0 ? atoi(e) : grid;  // tests
+        if (grid > gi * gj) grid = (int)(gi * gj);
+        gemm_tn_bf16_ring<4><<<(unsigned)grid, 512, 0, s>>>(A, B, I, J, Rp, ld, scale_ptr, scale_mul,
+                                                             C, (int)gi, (int)gj);
+    } else {
+        const unsigned blocks = (unsigned)(((I + 255) / 256) * ((J + 127) / 128));
+        gemm_tn_bf16<256, 128><<<blocks, 256, 0, s>>>(A, B, I, J, Rp, ld, scale_ptr, scale_mul, C);
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 static inline int64_t pad32(int64_t v) { return (v + 31) / 32 * 32; }
+// Row pitch (elements) of a bf16 copy whose rows hold Rp elements.  A GEMM stage reads 64 bytes
+// from each of 512 rows; with rows a multiple of 4 KiB apart those reads would all fall on the
+// same memory channel, so such rows are set 128 bytes further apart.
+static inline int64_t row_pitch(int64_t Rp) { return Rp % 2048 == 0 ? Rp + 64 : Rp; }
 
 size_t backward_workspace_bytes(int64_t M, int64_t N, int64_t K) {
-    const int64_t Np = pad32(N), Mp = pad32(M);
-    // g[M][Np], St[K][Np], gwT[N][Mp], qT[K][Mp], each bf16, each region 256-byte aligned
+    const int64_t Nl = row_pitch(pad32(N)), Ml = row_pitch(pad32(M));
+    // g[M][Nl], St[K][Nl], gwT[N][Ml], qT[K][Ml], each bf16, each region 256-byte aligned
     auto al = [](size_t v) { return (v + 255) & ~(size_t)255; };
-    return al((size_t)M * Np * 2) + al((size_t)K * Np * 2) + al((size_t)N * Mp * 2) +
-           al((size_t)K * Mp * 2);
+    return al((size_t)M * Nl * 2) + al((size_t)K * Nl * 2) + al((size_t)N * Ml * 2) +
+           al((size_t)K * Ml * 2);
 }
 
 hipError_t launch_backward(const BackwardArgs& a, hipStream_t s) {
     const int64_t M = a.M, N = a.N, K = a.K, Np = pad32(N), Mp = pad32(M);
+    const int64_t Nl = row_pitch(Np), Ml = row_pitch(Mp);
     auto al = [](size_t v) { return (v + 255) & ~(size_t)255; };
     char* ws = (char*)a.workspace;
     uint16_t* g = (uint16_t*)ws;
-    uint16_t* St = (uint16_t*)(ws + al((size_t)M * Np * 2));
-    uint16_t* gwT = (uint16_t*)((char*)St + al((size_t)K * Np * 2));
-    uint16_t* qT = (uint16_t*)((char*)gwT + al((size_t)N * Mp * 2));
+    uint16_t* St = (uint16_t*)(ws + al((size_t)M * Nl * 2));
+    uint16_t* gwT = (uint16_t*)((char*)St + al((size_t)K * Nl * 2));
+    uint16_t* qT = (uint16_t*)((char*)gwT + al((size_t)N * Ml * 2));
 
+    // dY is read once: g for dX and gwT for dW come out of the same pass when both are wanted
+    launch_cast_transpose<float>(a.dY, M, N, Np, Nl, Mp, Ml, a.per_tensor ? nullptr : a.gamma,
+                                 a.dX ? g : nullptr, a.dW ? gwT : nullptr, s);
     if (a.dX) {
-        const int64_t pairs = M * (Np / 2);
-        cast_rows_bf16<<<(unsigned)((pairs + 255) / 256), 256, 0, s>>>(a.dY, M, N, Np, g);
         dim3 gb((unsigned)((tiles_n(N) + 3) / 4), (unsigned)tiles_k(K));
-        bits_transpose_bf16<<<gb, 256, 0, s>>>(a.packed, N, K, Np, St);
-        const unsigned blocks = (unsigned)(((M + 255) / 256) * ((K + 127) / 128));
-        gemm_tn_bf16<256, 128><<<blocks, 256, 0, s>>>(g, St, M, K, Np, a.beta, 1.0f, a.dX);
+        bits_transpose_bf16<<<gb, 256, 0, s>>>(a.packed, N, K, Np, Nl, St);
+        launch_gemm_tn(g, St, M, K, Np, Nl, a.beta, 1.0f, a.dX, s);
     }
     if (a.dW) {
-        dim3 gt((unsigned)((N + 63) / 64), (unsigned)((Mp + 63) / 64));
-        transpose_cast_bf16<float><<<gt, 256, 0, s>>>(a.dY, M, N, Mp,
-                                                       a.per_tensor ? nullptr : a.gamma, gwT);
-        dim3 gq((unsigned)((K + 63) / 64), (unsigned)((Mp + 63) / 64));
-        transpose_cast_bf16<int8_t><<<gq, 256, 0, s>>>(a.codes, M, K, Mp, nullptr, qT);
-        const unsigned blocks = (unsigned)(((N + 255) / 256) * ((K + 127) / 128));
-        gemm_tn_bf16<256, 128><<<blocks, 256, 0, s>>>(gwT, qT, N, K, Mp,
-                                                      a.per_tensor ? a.gamma : nullptr,
-                                                      a.per_tensor ? 1.0f / 128.0f : 1.0f, a.dW);
+        launch_cast_transpose<int8_t>(a.codes, M, K, K, 0, Mp, Ml, nullptr, nullptr, qT, s);
+        launch_gemm_tn(gwT, qT, N, K, Mp, Ml, a.per_tensor ? a.gamma : nullptr,
+                       a.per_tensor ? 1.0f / 128.0f : 1.0f, a.dW, s);
     }
     return hipGetLastError();
 }

@@ -37,10 +37,14 @@ SHAPES = [(8, 512, 256), (12, 20, 64), (300, 200, 96), (64, 136, 1056), (257, 51
           (1024, 640, 512)]
 
 
+# The library picks the GEMM kernel from the shape (the persistent 256 x 256 ring kernel needs
+# many tiles); BITLINEAR_BWD_RING forces either one so that both see the ragged shapes.
 @pytest.mark.parametrize("M,N,K", SHAPES)
 @pytest.mark.parametrize("per_tensor", [True, False])
-def test_backward_ste_matches_oracle(bl, M, N, K, per_tensor):
-    print(f"backward M={M} N={N} K={K} per_tensor={per_tensor}", flush=True)
+@pytest.mark.parametrize("ring", ["0", "1"])
+def test_backward_ste_matches_oracle(bl, monkeypatch, M, N, K, per_tensor, ring):
+    print(f"backward M={M} N={N} K={K} per_tensor={per_tensor} ring={ring}", flush=True)
+    monkeypatch.setenv("BITLINEAR_BWD_RING", ring)
     sd = wl.seed_for(4, M + N + K)
     W = wl.make_weight(N, K, 0.02, sd)
     X = wl.make_activation(M, K, sd)
@@ -63,10 +67,34 @@ def test_backward_ste_matches_oracle(bl, M, N, K, per_tensor):
     assert none is None and torch.equal(dW2, dW)
 
 
-def test_backward_exact_when_dy_is_bf16_representable(bl):
+def test_backward_ring_kernel_walks_several_tiles(bl, monkeypatch):
+    """The persistent kernel with fewer workgroups than tiles (BITLINEAR_BWD_GRID): dX has 16
+    tiles on 8 workgroups (the tile order that groups tiles by L2 applies), dW 12 on 8."""
+    monkeypatch.setenv("BITLINEAR_BWD_RING", "1")
+    monkeypatch.setenv("BITLINEAR_BWD_GRID", "8")
+    M, N, K = 1024, 520, 1024
+    sd = wl.seed_for(4, 77)
+    print(f"backward ring grid=8 M={M} N={N} K={K}", flush=True)
+    W = wl.make_weight(N, K, 0.02, sd)
+    X = wl.make_activation(M, K, sd)
+    dY = wl.make_grad(M, N, sd)
+    packed, alpha, beta = bl.bitlinear_pack_weights(dev(W))
+    codes, gamma, rowsum, _ = bl.bitlinear_quant_act(dev(X), per_tensor=False)
+    dX, dW = bl.bitlinear_backward_ste(dev(dY), codes, gamma, packed, beta, False)
+    sign = oracle.unpack_canonical(
+        bl.bitlinear_packed_to_canonical(packed, N, K).cpu().numpy().view(np.uint32), K)
+    dX_ref, dW_ref = oracle.backward_ste(dY, codes.cpu().numpy(), gamma.cpu().numpy(), sign,
+                                         float(beta.cpu()[0]), False)
+    close(dX.cpu().numpy(), dX_ref)
+    close(dW.cpu().numpy(), dW_ref)
+
+
+@pytest.mark.parametrize("ring", ["0", "1"])
+def test_backward_exact_when_dy_is_bf16_representable(bl, monkeypatch, ring):
     """Small integers in dY, codes and signs: every product and partial sum is exact in fp32,
     so the GPU must reproduce the integer result bit for bit (catches layout mistakes that a
     tolerance would hide)."""
+    monkeypatch.setenv("BITLINEAR_BWD_RING", ring)
     M, N, K = 96, 80, 160
     rng = np.random.default_rng(3)
     W = wl.make_weight(N, K, 0.02, 5)
@@ -100,8 +128,9 @@ def test_backward_training_shape_sampled(bl):
     codes, gamma, rowsum, _ = bl.bitlinear_quant_act(dev(X), per_tensor=True)
     del X
     dX, dW = bl.bitlinear_backward_ste(dev(dY), codes, gamma, packed, beta, True)
-    rows_dx = np.array([0, 1, 4097, 8191])
-    rows_dw = np.array([0, 255, 256, 16383])
+    rng = np.random.default_rng(11)
+    rows_dx = np.concatenate([[0, 1, 4097, 8191], rng.integers(0, M, 12)])
+    rows_dw = np.concatenate([[0, 255, 256, 16383], rng.integers(0, N, 12)])
     dX_ref, dW_ref = oracle.backward_ste(dY, codes.cpu().numpy(), gamma.cpu().numpy(), sign,
                                          float(b), True, rows_dx=rows_dx, rows_dw=rows_dw)
     close(dX.cpu().numpy()[rows_dx], dX_ref)
