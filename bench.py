@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the BitLinear hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu] [--no-decode]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu] [--no-decode] [--no-train]
 
 Workload at one GPU: the BitNet-6.7B-shaped prefill pair (4096->16384 and 16384->4096 at
 M = 2048 tokens, activations N(0,1) with 0.1 % outliers x20, weights N(0, 0.02^2)).
@@ -13,8 +13,9 @@ per weight at inference and is timed separately ("weight_prep").
 Prints ONE JSON line.  `value` is prefill TOPS (2*M*N*K summed over the step / step time);
 `roofline` describes the dominant kernel (the MFMA GEMM) from HIP-event timing of that
 kernel alone inside the timed loop; `decode` reports the packed-weight streaming rate of
-the small-M kernel on BitNet-30B-shaped layers; `cpu_baseline` times the CPU oracle on a
-bounded sample of the same workload on this machine's host cores.
+the small-M kernel on BitNet-30B-shaped layers; `training` times one forward + straight-through
+backward of the 4096->16384 layer at M = 8192; `cpu_baseline` times the CPU oracle on a bounded
+sample of the same workload on this machine's host cores.
 """
 from __future__ import annotations
 
@@ -58,6 +59,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode streaming leg")
+    ap.add_argument("--no-train", action="store_true", help="skip the training-step leg")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run plain device copies of 256 MiB (reference for the rocprofv3 "
@@ -321,6 +323,54 @@ def main():
                                   traffic=None,
                                   note="events around back-to-back launches: includes dispatch gaps")
 
+    # ---- training-step leg: forward + STE backward (Section 2.2) at M = 8192, 4096 -> 16384 ----
+    # Weights change every step, so the step starts from fp32 W: pack (Eq. 1-3), forward
+    # (Eq. 12, 4-5, 7, 11), dX^ and dW by the straight-through estimator, dx through LayerNorm.
+    train = None
+    if not args.no_train:
+        c4 = wl.CONFIGS[4]
+        L4, M4 = c4.layers[0], c4.Ms[0]
+        s4 = wl.seed_for(4, 0)
+        W4 = torch.from_numpy(wl.make_weight(L4.N, L4.K, c4.w_std, s4)).to(dev)
+        X4 = torch.from_numpy(wl.make_activation(M4, L4.K, s4)).to(dev)
+        dY4 = torch.from_numpy(wl.make_grad(M4, L4.N, s4)).to(dev)
+        Y4 = torch.empty((M4, L4.N), dtype=torch.float32, device=dev)
+        wsb = torch.empty(bl.workspace_bytes(bl.OP_BACKWARD, M4, L4.N, L4.K, True),
+                          dtype=torch.uint8, device=dev)
+        st4 = {}
+
+        def t_pack():
+            st4["packed"], _, st4["beta"] = bl.bitlinear_pack_weights(W4, workspace=pws)
+
+        def t_fwd():
+            st4["q"] = bl.bitlinear_quant_act(X4, per_tensor=True)
+            bl.bitlinear_matmul(st4["q"][0], st4["q"][1], st4["q"][2], st4["packed"], L4.N,
+                                st4["beta"], per_tensor=True, out=Y4)
+
+        def t_bwd():
+            st4["dX"], st4["dW"] = bl.bitlinear_backward_ste(
+                dY4, st4["q"][0], st4["q"][1], st4["packed"], st4["beta"], True, workspace=wsb)
+
+        def t_ln():
+            bl.bitlinear_layernorm_backward(st4["dX"], X4, out=st4["dX"])
+
+        def t_all():
+            t_pack(), t_fwd(), t_bwd(), t_ln()
+
+        t_all()
+        torch.cuda.synchronize()
+        parts = {n: event_ms(f, 5, torch) for n, f in
+                 (("pack_ms", t_pack), ("forward_ms", t_fwd), ("backward_ste_ms", t_bwd),
+                  ("ln_backward_ms", t_ln), ("step_ms", t_all))}
+        fl = 2.0 * M4 * L4.N * L4.K
+        train = dict(workload=f"train-step: M={M4}, {L4.K}->{L4.N}, per-tensor gamma, dY~N(0,1e-6)",
+                     **parts, forward_tops=fl / (parts["forward_ms"] * 1e-3) / 1e12,
+                     backward_tflops=2 * fl / (parts["backward_ste_ms"] * 1e-3) / 1e12,
+                     backward_frac_bf16_peak=2 * fl / (parts["backward_ste_ms"] * 1e-3) / 1e12 / 2500.0,
+                     note="backward_ste = one pass over dY (bf16 copies), bit expansion, code "
+                          "transpose, two bf16 MFMA GEMMs")
+        del W4, X4, dY4, Y4, wsb, st4
+
     # ---- CPU oracle on a bounded sample of the same workload ---------------------------------
     # The same step (LN, quantise, integer GEMM, dequant through both layers) on the first
     # s_rows tokens, repeated `reps` times, sized from a small calibration run to about
@@ -378,7 +428,7 @@ def main():
                                "16384->4096, M=2048, per-token gamma, fp32 in/out",
                    "step": "LN+quantise+GEMM+dequant for both layers; weights packed beforehand"},
         "mfma_frac_of_peak": tops / I8_MFMA_PEAK_TOPS,
-        "kernels": kern, "roofline": roof, "weight_prep": prep, "decode": decode,
+        "kernels": kern, "roofline": roof, "weight_prep": prep, "decode": decode, "training": train,
         "cpu_baseline": cpu, "parity": parity,
     }
     print(json.dumps(out))
