@@ -226,37 +226,6 @@ int bitlinear_layernorm_backward(const float* dXhat, const float* X, int64_t M, 
                                  float* dgain, float* dbias, void* workspace,
                                  size_t workspace_bytes, void* stream);
 
-/* ---- A chain of layers for a few tokens in one launch -----------------------------------
- * h_0 = X, h_l = BitLinear_l(the leading K_l columns of h_{l-1}), Y = h_L: every layer is
- * Eq. 12, Eq. 4-5 (per token), Eq. 7 and Eq. 11 as bitlinear_forward computes them, bit for bit
- * (whatever sits between two BitLinear layers of a model is not part of this library; a layer
- * narrower than its predecessor's output reads the leading columns).  Decoding one token runs
- * through dozens of layers of a few MB each; one persistent launch whose workgroups meet at a
- * barrier between layers replaces two launches per layer.
- *   layers          host array of n_layers entries: packed weights and beta (device pointers,
- *                   as bitlinear_pack_weights wrote them), N, K
- *   layers_device   the same array in device memory (the kernel reads it; the caller keeps
- *                   both alive and identical)
- *   M               1..16 tokens; M * (K rounded up to 512) <= 65536 for every layer
- *   X               fp32 [M, K_0];  Y  fp32 [M, N_last]
- *   workspace       bitlinear_decode_stack_workspace_bytes bytes.  Its first two uint32 are the
- *                   barrier's arrival count and an error flag: the flag is nonzero after the
- *                   work has run iff some workgroup waited about a second for the others and
- *                   gave up (Y is then invalid).  That needs the kernel's workgroups (one per
- *                   CU) to be on the GPU together: nothing else may occupy the GPU's CUs for
- *                   good while it runs.
- * Requirements: N % 4 == 0, K % 32 == 0, K_l <= N_{l-1} (else BL_ERR_SHAPE), K <= 32768, no
- * LayerNorm gain/bias, per-token gamma.  BL_ERR_UNSUPPORTED for layers the kernel cannot take. */
-typedef struct {
-    const void* packed;
-    const float* beta;
-    int64_t N, K;
-} bl_stack_layer;
-size_t bitlinear_decode_stack_workspace_bytes(const bl_stack_layer* layers, int n_layers, int64_t M);
-int bitlinear_decode_stack(const float* X, int64_t M, const bl_stack_layer* layers,
-                           const bl_stack_layer* layers_device, int n_layers, float ln_eps, float* Y,
-                           void* workspace, size_t workspace_bytes, void* stream);
-
 /* host: static description of a status code. */
 const char* bitlinear_status_string(int status);
 

@@ -12,5 +12,4 @@ from .binding import (  # noqa: F401
     workspace_bytes_grouped,
     bitlinear_forward_nonneg, bitlinear_matmul_nonneg, bitlinear_quant_act_nonneg,
     bitlinear_weight_rowsums,
-    DecodeStack, bitlinear_decode_stack,
 )

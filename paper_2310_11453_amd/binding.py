@@ -28,7 +28,7 @@ EXPORTS = (
     "bitlinear_pack_weights_grouped", "bitlinear_packed_to_canonical_grouped",
     "bitlinear_quant_act_grouped", "bitlinear_forward_grouped", "bitlinear_layernorm_backward",
     "bitlinear_weight_rowsums", "bitlinear_quant_act_nonneg", "bitlinear_matmul_nonneg",
-    "bitlinear_forward_nonneg", "bitlinear_decode_stack_workspace_bytes", "bitlinear_decode_stack",
+    "bitlinear_forward_nonneg",
 )
 
 _lib = None
@@ -90,10 +90,6 @@ def load_library() -> ctypes.CDLL:
     lib.bitlinear_forward_nonneg.restype = ci
     lib.bitlinear_forward_nonneg.argtypes = [vp, i64, i64, vp, i64, vp, vp, vp, vp, cf, ci, u32, vp,
                                              vp, sz, vp]
-    lib.bitlinear_decode_stack_workspace_bytes.restype = sz
-    lib.bitlinear_decode_stack_workspace_bytes.argtypes = [vp, ci, i64]
-    lib.bitlinear_decode_stack.restype = ci
-    lib.bitlinear_decode_stack.argtypes = [vp, i64, vp, vp, ci, cf, vp, vp, sz, vp]
     lib.bitlinear_status_string.restype = ctypes.c_char_p
     lib.bitlinear_status_string.argtypes = [ci]
     _lib = lib
@@ -382,51 +378,4 @@ def bitlinear_forward_nonneg(X: torch.Tensor, packed: torch.Tensor, N: int, beta
         _ptr(wsum, torch.int32), _ptr(ln_gain, torch.float32), _ptr(ln_bias, torch.float32), ln_eps,
         GAMMA_PER_TOKEN, flags, _ptr(out), _ptr(ws), ws.numel(), _stream()),
         "bitlinear_forward_nonneg")
-    return out
-
-
-# ---- a chain of layers in one launch ------------------------------------------------------
-class _StackLayer(ctypes.Structure):  # bl_stack_layer
-    _fields_ = [("packed", ctypes.c_void_p), ("beta", ctypes.c_void_p), ("N", ctypes.c_int64),
-                ("K", ctypes.c_int64)]
-
-
-class DecodeStack:
-    """The layer table of bitlinear_decode_stack, on the host and on the device, and the
-    workspace for M tokens.  `layers`: sequence of (packed, beta, N, K) with device tensors."""
-
-    def __init__(self, layers, M: int):
-        self.M, self.n = int(M), len(layers)
-        self._keep = [(p, b) for (p, b, _, _) in layers]  # the table holds raw pointers
-        self.host = (_StackLayer * self.n)()
-        for i, (p, b, N, K) in enumerate(layers):
-            self.host[i] = _StackLayer(_ptr(p), _ptr(b, torch.float32), int(N), int(K))
-        dev = layers[0][0].device
-        raw = torch.frombuffer(bytearray(bytes(self.host)), dtype=torch.uint8)
-        self.device = raw.to(dev)
-        self.K0, self.N_last = int(layers[0][3]), int(layers[-1][2])
-        nbytes = int(load_library().bitlinear_decode_stack_workspace_bytes(
-            ctypes.addressof(self.host), self.n, self.M))
-        if nbytes == 0:
-            raise BitLinearError("bitlinear_decode_stack cannot take these layers (see include/bitlinear.h)")
-        self.workspace = torch.zeros(nbytes, dtype=torch.uint8, device=dev)
-
-    def barrier_failed(self) -> bool:
-        """Synchronises and reads the error flag the kernel leaves in the workspace."""
-        torch.cuda.synchronize()
-        return bool(self.workspace[4:8].view(torch.int32).item())
-
-
-def bitlinear_decode_stack(X: torch.Tensor, stack: DecodeStack, ln_eps: float = 1e-5,
-                           out: torch.Tensor | None = None) -> torch.Tensor:
-    """Y = the chain of BitLinear layers applied to X [M, K_0] (per-token gamma), one launch."""
-    M, K = X.shape
-    if M != stack.M or K != stack.K0:
-        raise BitLinearError("X does not match the stack")
-    if out is None:
-        out = torch.empty((M, stack.N_last), dtype=torch.float32, device=X.device)
-    _check(load_library().bitlinear_decode_stack(
-        _ptr(X, torch.float32), M, ctypes.addressof(stack.host), _ptr(stack.device), stack.n, ln_eps,
-        _ptr(out, torch.float32), _ptr(stack.workspace), stack.workspace.numel(), _stream()),
-        "bitlinear_decode_stack")
     return out

@@ -2,7 +2,6 @@
 // Declarations and argument semantics: include/bitlinear.h.
 #include "../../include/bitlinear.h"
 #include "common.h"
-#include "decode_stack.h"
 #include "kernels.h"
 
 using namespace bl;
@@ -508,56 +507,6 @@ int bitlinear_layernorm_backward(const float* dXhat, const float* X, int64_t M, 
     a.rowstats = affine ? (double*)((char*)workspace + ws.rowstats) : nullptr;
     double* partials = affine ? (double*)((char*)workspace + ws.partials) : nullptr;
     return check_hip(launch_ln_backward(a, dgain, dbias, partials, (hipStream_t)stream));
-}
-
-// ---- a chain of layers in one launch ------------------------------------------------------
-static_assert(sizeof(bl_stack_layer) == sizeof(StackLayer), "bl_stack_layer is the kernel's table entry");
-
-static int stack_check(const bl_stack_layer* layers, int n_layers, int64_t M, int64_t* max_inner) {
-    if (n_layers < 1 || n_layers > 4096 || M < 0 || M > kStackMaxM) return BL_ERR_SHAPE;
-    if (!layers) return BL_ERR_NULL;
-    int64_t widest = 0;
-    for (int i = 0; i < n_layers; ++i) {
-        const bl_stack_layer& L = layers[i];
-        if (!shape_ok(L.N, L.K)) return BL_ERR_SHAPE;
-        if (i > 0 && L.K > layers[i - 1].N) return BL_ERR_SHAPE;
-        StackPlan pl;
-        if (!stack_plan(L.N, L.K, M > 0 ? (int)M : 1, pl)) return BL_ERR_UNSUPPORTED;
-        if (!L.packed || !L.beta) return BL_ERR_NULL;
-        if (i + 1 < n_layers && L.N > widest) widest = L.N;
-    }
-    *max_inner = widest;
-    return BL_OK;
-}
-
-size_t bitlinear_decode_stack_workspace_bytes(const bl_stack_layer* layers, int n_layers, int64_t M) {
-    int64_t widest = 0;
-    if (stack_check(layers, n_layers, M, &widest) != BL_OK) return 0;
-    return 256 + 2 * align256((size_t)M * (size_t)widest * 4);
-}
-
-int bitlinear_decode_stack(const float* X, int64_t M, const bl_stack_layer* layers,
-                           const bl_stack_layer* layers_device, int n_layers, float ln_eps, float* Y,
-                           void* workspace, size_t workspace_bytes, void* stream) {
-    int64_t widest = 0;
-    const int st = stack_check(layers, n_layers, M, &widest);
-    if (st != BL_OK) return st;
-    if (M == 0) return BL_OK;
-    if (!X || !Y || !layers_device) return BL_ERR_NULL;
-    const size_t half = align256((size_t)M * (size_t)widest * 4);
-    if (!workspace || workspace_bytes < 256 + 2 * half) return BL_ERR_WORKSPACE;
-    StackArgs a{};
-    a.layers = reinterpret_cast<const StackLayer*>(layers_device);
-    a.n_layers = n_layers;
-    a.M = (int)M;
-    a.X = X;
-    a.Y = Y;
-    a.sync = (unsigned*)workspace;
-    a.buf[0] = (float*)((char*)workspace + 256);
-    a.buf[1] = (float*)((char*)workspace + 256 + half);
-    a.eps = ln_eps;
-    a.spin_limit = 1u << 19;  // about a second of polling before a workgroup gives up
-    return check_hip(launch_decode_stack(a, (hipStream_t)stream));
 }
 
 const char* bitlinear_status_string(int status) {

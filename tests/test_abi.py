@@ -72,40 +72,6 @@ def test_argument_errors_are_found_on_the_host(lib):
     assert lib.bitlinear_status_string(-2).decode().startswith("bad shape")
 
 
-def test_decode_stack_host_checks(lib):
-    """bitlinear_decode_stack validates the chain on the host before any launch."""
-    from paper_2310_11453_amd.binding import _StackLayer
-    one = ctypes.c_void_p(256)
-
-    def table(*dims):
-        t = (_StackLayer * len(dims))()
-        for i, (K, N) in enumerate(dims):
-            t[i] = _StackLayer(256, 256, N, K)
-        return t
-
-    def run(t, n, M, ws_bytes=1 << 30, dev=one):
-        return lib.bitlinear_decode_stack(one, M, ctypes.addressof(t), dev, n, 1e-5, one, one,
-                                          ws_bytes, None)
-
-    ok = table((2048, 6144), (2048, 2048))
-    need = lib.bitlinear_decode_stack_workspace_bytes(ctypes.addressof(ok), 2, 4)
-    assert need == 256 + 2 * 4 * 6144 * 4
-    assert run(ok, 2, 0) == 0                      # no tokens: nothing to do
-    assert run(ok, 2, 4, ws_bytes=need - 1) == -4  # workspace too small
-    assert run(ok, 2, 4, dev=None) == -1           # the device copy of the table is required
-    assert run(ok, 2, 17) == -2                    # more tokens than the kernel's MFMA tile holds
-    assert run(ok, 0, 1) == -2
-    assert run(table((2048, 1024), (2048, 512)), 2, 1) == -2   # layer 1 wider than layer 0's output
-    assert run(table((2048, 1022)), 1, 1) == -3                # N % 4
-    assert run(table((2050, 64)), 1, 1) == -2                  # K % 32
-    assert run(table((40000, 64)), 1, 1) == -3                 # a row longer than the quantiser holds
-    assert run(table((16384, 64)), 1, 8) == -3                 # 8 rows of 16384 codes exceed the LDS budget
-    assert lib.bitlinear_decode_stack_workspace_bytes(ctypes.addressof(table((2048, 1022))), 1, 1) == 0
-    t = table((2048, 64))
-    t[0].beta = None
-    assert run(t, 1, 1) == -1
-
-
 def test_grouped_host_checks(lib):
     """Eq. 13-15 entry points: sizes and argument errors, all on the host."""
     import paper_2310_11453_amd as bl
