@@ -418,6 +418,16 @@ def main():
                    sample=f"{reps} x the step on the first {s_rows} of {M} tokens (LN, quantise, "
                           f"int GEMM, dequant through both layers); weights pre-binarised")
 
+    # ---- analytic arithmetic energy of the step's products (Section 3's estimate; context only) ----
+    from paper_2310_11453_amd import energy as en
+    e_bit = [en.bitlinear_energy(M, d["L"].K, d["L"].N, "7nm") for d in layers]
+    e_f16 = [en.matmul_energy(M, d["L"].K, d["L"].N, "fp16", "7nm") for d in layers]
+    energy_model = dict(node="7nm", unit="J per step", bitlinear_add=sum(e[0] for e in e_bit),
+                        bitlinear_mul=sum(e[1] for e in e_bit), fp16_add=sum(e[0] for e in e_f16),
+                        fp16_mul=sum(e[1] for e in e_f16),
+                        note="the paper's per-operation energy model applied to the two products of "
+                             "the step; not a measurement")
+
     out = {
         "metric": "BitLinear prefill TOPS (i8 MFMA %) + decode packed-weight HBM GB/s",
         "value": tops, "unit": "TOPS", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -428,7 +438,7 @@ def main():
                                "16384->4096, M=2048, per-token gamma, fp32 in/out",
                    "step": "LN+quantise+GEMM+dequant for both layers; weights packed beforehand"},
         "mfma_frac_of_peak": tops / I8_MFMA_PEAK_TOPS,
-        "kernels": kern, "roofline": roof, "weight_prep": prep, "decode": decode, "training": train,
+        "kernels": kern, "roofline": roof, "weight_prep": prep, "decode": decode, "training": train, "energy_model": energy_model,
         "cpu_baseline": cpu, "parity": parity,
     }
     print(json.dumps(out))
