@@ -1,0 +1,342 @@
+// 1-bit x 8-bit GEMM + dequantisation for a few dozen tokens (16 < M <= 64), Eq. 7 and Eq. 11
+// of arXiv 2310.11453: the batch between the weight-streaming kernel (M <= 16) and the large
+// MFMA tiles.  One 64 x 128 output tile per workgroup gives at most a few hundred workgroups,
+// each with a long serial walk over K, and a four-wave workgroup takes about 225 ns per 64-k
+// stage whatever the MFMA rate (LDS round trips, a DMA wait and a barrier per stage against
+// four MFMAs per wave).  So the walk is split INSIDE the workgroup: eight waves, four K-groups
+// of two waves (64 x 64 each), each group streaming its own quarter of K through its own LDS
+// ring exactly as the large kernel does (codes and packed bits by global_load_lds, bits
+// expanded in registers, hand-counted vmcnt; see gemm_prefill.hip), all groups meeting at the
+// same barriers: about 0.5 us for four stages.  The integer accumulators of the four groups
+// are added through LDS at the end and one epilogue dequantises: the same integers as any
+// other split of K, so the result does not depend on it.
+#include "common.h"
+#include "kernels.h"
+#include "ring.h"
+
+namespace bl {
+
+namespace mid {
+constexpr int BM = 64, BN = 128, KG = 4, WN = 2;
+constexpr int THREADS = KG * WN * kWave;  // 512
+constexpr int GT = WN * kWave;            // threads of a K-group
+constexpr int STAGE_BYTES = BM * 64;      // 64 rows x 64 k
+constexpr int P = BM * 4 / GT;            // 16-byte DMA pieces per thread and stage: 2
+constexpr int NBW = (BN / 16) / WN;       // packed tiles per wave and chunk: 4
+static_assert(P == 2 && NBW == 4, "tile shape");
+
+// operands of one half-step (rows j and 32 + j of the stage), complete on exit
+__device__ inline void read_a(v4i (&a)[2], uint32_t ad) {
+    asm volatile(
+        "ds_read_b128 %0, %2\n\t"
+        "ds_read_b128 %1, %2 offset:2048\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(a[0]), "=&v"(a[1])
+        : "v"(ad));
+}
+// packed bits of the lane's two columns (sub-tile s at +2048), two halves of a chunk (+512)
+__device__ inline void read_bits(v4i (&bw)[2][2], uint32_t ad) {
+    asm volatile(
+        "ds_read_b128 %0, %4\n\t"
+        "ds_read_b128 %1, %4 offset:512\n\t"
+        "ds_read_b128 %2, %4 offset:2048\n\t"
+        "ds_read_b128 %3, %4 offset:2560\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(bw[0][0]), "=&v"(bw[0][1]), "=&v"(bw[1][0]), "=&v"(bw[1][1])
+        : "v"(ad));
+}
+// acc[mi][s] += ac[mi] x b[s]; an = operands at `ad`, complete on exit
+__device__ inline void half_step(v16i (&acc)[2][2], const v4i (&ac)[2], const v4i (&b)[2],
+                                 v4i (&an)[2], uint32_t ad) {
+    asm volatile(
+        "ds_read_b128 %4, %10\n\t"
+        "ds_read_b128 %5, %10 offset:2048\n\t"
+        "s_nop 1\n\t"
+        "v_mfma_i32_32x32x32_i8 %0, %6, %8, %0\n\t"
+        "v_mfma_i32_32x32x32_i8 %1, %6, %9, %1\n\t"
+        "v_mfma_i32_32x32x32_i8 %2, %7, %8, %2\n\t"
+        "v_mfma_i32_32x32x32_i8 %3, %7, %9, %3\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "+v"(acc[0][0]), "+v"(acc[0][1]), "+v"(acc[1][0]), "+v"(acc[1][1]), "=&v"(an[0]),
+          "=&v"(an[1])
+        : "v"(ac[0]), "v"(ac[1]), "v"(b[0]), "v"(b[1]), "v"(ad));
+}
+}  // namespace mid
+
+// Work item = (column tile, K-slice): blockIdx.x = slice * grid_n + tile.  With a.split_k the
+// slice's partial sums 2 * sum_k q b go to a.split_ws and splitk_reduce finishes; otherwise the
+// workgroup owns all of K and writes Y.
+// NS = stages in each group's ring (six instead of four changes nothing: the pace is set by
+// each wave's own instruction chain per stage, not by the DMA latency).
+template <int NS>
+__global__ __launch_bounds__(mid::THREADS) void gemm_mid_kernel(GemmArgs a, int grid_n) {
+    using namespace mid;
+    // rings of the four K-groups; after the walk the same bytes hold two 64 x 128 int32 sums
+    __shared__ __attribute__((aligned(1024))) uint8_t smA[KG * NS * STAGE_BYTES];
+    __shared__ __attribute__((aligned(1024))) uint8_t smB[KG * (BN / 16) * 1024];
+    static_assert(KG * NS * STAGE_BYTES >= 2 * BM * BN * 4, "room for the reduction");
+
+    // wave-uniform values in scalar registers: the loop below branches on them
+    const int w = __builtin_amdgcn_readfirstlane((int)threadIdx.x / kWave), l = threadIdx.x % kWave;
+    const int kg = w / WN, wn = w % WN;
+    const int tg = threadIdx.x % GT;  // thread inside the K-group
+    const int j = l & 31, g2 = l >> 5;
+    const int64_t M = a.M, N = a.N;
+    const int64_t TN = tiles_n(N);
+    const int64_t TKp = a.tk_pitch ? a.tk_pitch : tiles_k(a.K);
+    const int sp = (int)blockIdx.x / grid_n;
+    const int64_t n0 = (int64_t)((int)blockIdx.x % grid_n) * BN;
+
+    // ---- this item's slice of K, then this group's chunks of it ----------------------------
+    int64_t ki0 = 0, Ki = a.K;
+    if (a.split_k) {
+        ki0 = (int64_t)sp * a.split_k;
+        Ki = a.K - ki0 < a.split_k ? a.K - ki0 : a.split_k;
+    }
+    const int64_t TKi = tiles_k(Ki);
+    const int64_t c0 = TKi * kg / KG, c1 = TKi * (kg + 1) / KG;
+    const int64_t k0 = ki0 + c0 * kChunkK;
+    int64_t K = Ki - c0 * kChunkK;  // this group's K
+    if (K > (c1 - c0) * kChunkK) K = (c1 - c0) * kChunkK;
+    if (c1 == c0) K = 0;
+    const int64_t TK = c1 - c0;
+    // Every group walks the same number of stages, whole chunks of the longest group; what lies
+    // past a group's own K meets zero bits (padding of its last chunk, or a zero mask past its
+    // last chunk), so it adds nothing.
+    int64_t TKmax = 0;
+#pragma unroll
+    for (int g = 0; g < KG; ++g) {
+        const int64_t d = TKi * (g + 1) / KG - TKi * g / KG;
+        TKmax = d > TKmax ? d : TKmax;
+    }
+    const int nrun = (int)TKmax * 8;
+
+    // ---- epilogue operands of this thread's outputs, requested now ---------------------------
+    // thread -> columns nq .. nq+3 of the tile, rows er + 16 h
+    constexpr int EH = BM * (BN / 4) / THREADS;  // 4
+    constexpr int ER = THREADS / (BN / 4);       // 16
+    const int er = (int)threadIdx.x >> 5;
+    const int64_t nq = n0 + (threadIdx.x & 31) * 4;
+    float e_gamma[EH], e_eta[EH];
+    int e_rs[EH];
+#pragma unroll
+    for (int h = 0; h < EH; ++h) {
+        const int64_t m = er + ER * h < M ? er + ER * h : M - 1;
+        e_gamma[h] = a.gamma[a.per_tensor ? 0 : m * a.gstride];
+        e_rs[h] = a.rowsum[m * a.gstride];
+        e_eta[h] = *(a.eta ? a.eta + m * a.gstride : a.gamma);
+    }
+    float e_beta[4];
+    int e_ws[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const int64_t n = nq + c < N ? nq + c : N - 1;
+        e_beta[c] = a.beta[((uint32_t)n / (uint32_t)a.beta_rows) * a.beta_stride];
+        e_ws[c] = *(a.eta ? a.wsum + n : a.rowsum);
+    }
+
+    // ---- DMA of this group: thread -> one 16-byte piece of a stage; wave -> two bit tiles ----
+    uint8_t* const ringA = smA + kg * (NS * STAGE_BYTES);
+    uint8_t* const ringB = smB + kg * ((BN / 16) * 1024);
+    const int8_t* gsrc[P];
+    int gseg[P];
+#pragma unroll
+    for (int q = 0; q < P; ++q) {
+        const int slot = q * GT + tg;
+        int row = slot >> 2;
+        gseg[q] = ((slot & 3) ^ ((row >> 2) & 3)) * 16;
+        if (row > M - 1) row = (int)(M - 1);
+        gsrc[q] = a.codes + (int64_t)row * a.ldq + k0 + gseg[q];
+    }
+    const uint32_t* bsrc[NBW];
+#pragma unroll
+    for (int q = 0; q < NBW; ++q) {
+        int64_t tn = (n0 >> 4) + wn + q * WN;
+        if (tn > TN - 1) tn = TN - 1;
+        bsrc[q] = a.packed + tile_dword_offset(tn, k0 / kChunkK, TKp) + l * 4;
+    }
+    const uint32_t lds_wave = (uint32_t)(wn * kWave * 16);
+    auto issue = [&](int st, bool clamp) {
+#pragma unroll
+        for (int q = 0; q < P; ++q) {
+            const int8_t* src = gsrc[q] + (int64_t)st * 64;
+            if (clamp) {
+                const int64_t k = (int64_t)st * 64 + gseg[q];
+                if (k > K - 16) src -= k - (K - 16);
+            }
+            __builtin_amdgcn_global_load_lds(
+                (const void*)src,
+                (__attribute__((address_space(3))) void*)(ringA + (st % NS) * STAGE_BYTES +
+                                                          q * GT * 16 + lds_wave),
+                16, 0, 0);
+        }
+    };
+    auto issue_bits = [&](int64_t tk) {
+#pragma unroll
+        for (int q = 0; q < NBW; ++q)
+            __builtin_amdgcn_global_load_lds(
+                (const void*)(bsrc[q] + tk * 256),
+                (__attribute__((address_space(3))) void*)(ringB + (wn + q * WN) * 1024), 16, 0, 0);
+    };
+
+    const uint32_t b_lane = (uint32_t)(uintptr_t)ringB + ((wn * 64 + j) >> 4) * 1024 +
+                            (g2 * 16 + (j & 15)) * 16;
+    const int sw = (j >> 2) & 3;
+    const uint32_t a_lane[2] = {(uint32_t)(uintptr_t)ringA + j * 64 + ((g2) ^ sw) * 16,
+                                (uint32_t)(uintptr_t)ringA + j * 64 + ((2 + g2) ^ sw) * 16};
+    auto a_addr = [&](int st, int h) { return a_lane[h] + (uint32_t)((st % NS) * STAGE_BYTES); };
+
+    v16i acc[2][2];
+#pragma unroll
+    for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mi][s2][r] = 0;
+    // plane i of half h of chunk c as {0,1} bytes; nothing past the group's last chunk
+    v4i bw[2][2];
+    auto expand = [&](v4i (&b)[2], int h, int i, int64_t c) {
+        const uint32_t m01 = c < TK ? 0x01010101u : 0u;
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+            for (int d = 0; d < 4; ++d) b[s2][d] = (int)(((uint32_t)bw[s2][h][d] >> i) & m01);
+    };
+    v4i ax[2], ay[2], bx[2], by[2];
+    const bool has_k = TK > 0;  // a group without chunks requests nothing and multiplies by zero
+
+    if (has_k) {
+        issue_bits(0);
+#pragma unroll
+        for (int s = 0; s < NS - 1; ++s) issue(s, true);
+    }
+    wait_vmcnt<(NS - 2) * P>();  // younger than stage 0: stages 1 .. NS-2
+    block_barrier();
+    read_bits(bw, b_lane);
+    read_a(ax, a_addr(0, 0));
+    expand(bx, 0, 0, 0);
+    // Stage st = 8 c + i, bit plane i of the group's chunk c.  The asm blocks run unconditionally
+    // (a branch around one would make the compiler shuffle their registers at every join); only
+    // DMA requests and the choice of wait depend on where the group is.  DMA bookkeeping as in
+    // the large kernel: at the mid-stage wait the operations younger than stage st+1 are those of
+    // stages st+2 .. st+NS-2 and, while the bits of the next chunk (requested at i == 2, read
+    // at i == 7) are among them, those too.
+    for (int64_t c = 0; c < TKmax; ++c) {
+        static_for<0, 8>([&](auto ic) {
+            constexpr int i = decltype(ic)::value;
+            const int st = (int)c * 8 + i;
+            const bool ahead = st + NS - 1 < nrun;
+            const bool bits_next = has_k && c + 1 < TK;
+            expand(by, 1, i, c);
+            half_step(acc, ax, bx, ay, a_addr(st, 1));
+            if (!ahead) wait_vmcnt<0>();
+            else if (bits_next && i >= 3 && i <= NS - 1 && i <= 6) wait_vmcnt<(NS - 3) * P + NBW>();
+            else wait_vmcnt<(NS - 3) * P>();
+            block_barrier();
+            if (i == 7) read_bits(bw, b_lane);
+            if (i == 2 && bits_next) issue_bits(c + 1);
+            if (ahead && has_k) issue(st + NS - 1, (int64_t)(st + NS) * 64 > K);  // clamp only past K
+            expand(bx, 0, (i + 1) & 7, i == 7 ? c + 1 : c);
+            half_step(acc, ay, by, ax, a_addr(st + 1, 0));
+        });
+    }
+    // the accumulators were last written inside an asm block: let the matrix pipeline retire
+    // them before ordinary instructions read them
+    asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
+    wait_vmcnt<0>();
+    __syncthreads();  // every group is done with its ring
+
+    // ---- add the four groups: lane (j, g2) of wave wn holds columns 64*wn + 32*s + j, rows
+    // 32*mi + 8*(r/4) + 4*g2 + r%4; groups 2,3 write, groups 0,1 add theirs, then all threads
+    // read both sums ------------------------------------------------------------------------
+    int* red = reinterpret_cast<int*>(smA);
+    auto red_at = [&](int region, int mi, int s2, int r) {
+        return red + region * (BM * BN) + (32 * mi + 8 * (r >> 2) + 4 * g2 + (r & 3)) * BN + wn * 64 +
+               32 * s2 + j;
+    };
+    if (kg >= 2) {
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) *red_at(kg - 2, mi, s2, r) = acc[mi][s2][r];
+    }
+    __syncthreads();
+    if (kg < 2) {
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) *red_at(kg, mi, s2, r) += acc[mi][s2][r];
+    }
+    __syncthreads();
+
+    // ---- epilogue (Eq. 11): sum_k q s = 2 sum_k q b - sum_k q ; y = that * (beta gamma / 128) ----
+#pragma unroll
+    for (int h = 0; h < EH; ++h) {
+        const int64_t m = er + ER * h;
+        if (m >= M || nq >= N) continue;
+        const int* p0 = red + (er + ER * h) * BN + (threadIdx.x & 31) * 4;
+        const v4i s4 = *reinterpret_cast<const v4i*>(p0) + *reinterpret_cast<const v4i*>(p0 + BM * BN);
+        const bool vec = (N & 3) == 0;  // then nq + 3 < N and the row starts 16-byte aligned
+        if (a.split_k) {
+            int* o = a.split_ws + ((int64_t)sp * M + m) * N + nq;
+            const v4i t = s4 * 2;
+            if (vec) *reinterpret_cast<v4i*>(o) = t;
+            else
+                for (int c = 0; c < 4; ++c)
+                    if (nq + c < N) o[c] = t[c];
+            continue;
+        }
+        const v4i pm = s4 * 2 - e_rs[h];
+        if (a.out_acc) {
+            int* o = reinterpret_cast<int*>(a.Y) + m * N + nq;
+            if (vec) *reinterpret_cast<v4i*>(o) = pm;
+            else
+                for (int c = 0; c < 4; ++c)
+                    if (nq + c < N) o[c] = pm[c];
+            continue;
+        }
+        float* o = a.Y + m * N + nq;
+        const float sc = e_gamma[h] * 0.0078125f;  // gamma / 128, exact
+        v4f y;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            // beta * (gamma / 128) has the bits of (beta * gamma) / 128
+            y[c] = (float)pm[c] * (e_beta[c] * sc);
+            if (a.eta) y[c] = y[c] + (e_beta[c] * e_eta[h]) * (float)e_ws[c];  // Eq. 6
+        }
+        if (vec) {
+            if (a.accumulate) y += *reinterpret_cast<const v4f*>(o);  // a later K-group (Eq. 13-15)
+            *reinterpret_cast<v4f*>(o) = y;
+        } else {
+            for (int c = 0; c < 4; ++c)
+                if (nq + c < N) o[c] = a.accumulate ? y[c] + o[c] : y[c];
+        }
+    }
+}
+
+// 16 < M <= 64.  K is also split over workgroups (second kernel: splitk_reduce) when N gives
+// few tiles and the caller brought the workspace for it, as prefill_split_tiles decides.
+hipError_t launch_gemm_mid(const GemmArgs& a_in, hipStream_t s) {
+    GemmArgs a = a_in;
+    a.split_k = 0;
+    if (a.M > mid::BM || a.K >= ((int64_t)1 << 22) || a.ldq >= ((int64_t)1 << 22))
+        return hipErrorInvalidValue;
+    const int grid_n = (int)((a.N + mid::BN - 1) / mid::BN);
+    int splits = 1;
+    const int64_t per = prefill_split_tiles(a.M, a.N, a.K);
+    const size_t need = gemm_split_ws_bytes(a.M, a.N, a.K);
+    if (per && a.split_ws && a.split_ws_bytes >= need && !getenv("BITLINEAR_PREFILL_NOSPLIT")) {
+        splits = (int)((tiles_k(a.K) + per - 1) / per);
+        a.tk_pitch = a.tk_pitch ? a.tk_pitch : tiles_k(a.K);
+        a.split_k = per * kChunkK;
+    }
+    gemm_mid_kernel<4><<<(unsigned)(grid_n * splits), mid::THREADS, 0, s>>>(a, grid_n);
+    if (splits > 1) launch_splitk_reduce(a, splits, s);
+    return hipGetLastError();
+}
+
+}  // namespace bl

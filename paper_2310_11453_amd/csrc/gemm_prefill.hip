@@ -74,14 +74,6 @@ __device__ inline void lds_read_bits(v4i (&bw)[2][2], uint32_t ad) {
         : "=&v"(bw[0][0]), "=&v"(bw[0][1]), "=&v"(bw[1][0]), "=&v"(bw[1][1])
         : "v"(ad));
 }
-__device__ inline void lds_read_bits(v4i (&bw)[1][2], uint32_t ad) {
-    asm volatile(
-        "ds_read_b128 %0, %2\n\t"
-        "ds_read_b128 %1, %2 offset:512\n\t"
-        "s_waitcnt lgkmcnt(0)"
-        : "=&v"(bw[0][0]), "=&v"(bw[0][1])
-        : "v"(ad));
-}
 
 // Half-step, 4 x 2 sub-tiles: prefetch an[] from LDS address `ad`, acc[mi][s] += ac[mi] x b[s].
 // The four reads ahead of the first MFMA also separate it from whatever VALU instruction
@@ -123,20 +115,6 @@ __device__ inline void half_step(v16i (&acc)[2][2], const v4i (&ac)[2], const v4
           "=&v"(an[1])
         : "v"(ac[0]), "v"(ac[1]), "v"(b[0]), "v"(b[1]), "v"(ad));
 }
-// Half-step, 2 x 1 sub-tiles.
-__device__ inline void half_step(v16i (&acc)[2][1], const v4i (&ac)[2], const v4i (&b)[1],
-                                 v4i (&an)[2], uint32_t ad) {
-    asm volatile(
-        "ds_read_b128 %2, %7\n\t"
-        "ds_read_b128 %3, %7 offset:2048\n\t"
-        "s_nop 1\n\t"
-        "v_mfma_i32_32x32x32_i8 %0, %4, %6, %0\n\t"
-        "v_mfma_i32_32x32x32_i8 %1, %5, %6, %1\n\t"
-        "s_waitcnt lgkmcnt(0)"
-        : "+v"(acc[0][0]), "+v"(acc[1][0]), "=&v"(an[0]), "=&v"(an[1])
-        : "v"(ac[0]), "v"(ac[1]), "v"(b[0]), "v"(ad));
-}
-
 // Row scale and row sum of four consecutive rows (epilogue), complete on exit.
 __device__ inline void lds_read_rows(v4f& sc, v4i& rs, uint32_t ad_sc, uint32_t ad_rs) {
     asm volatile(
@@ -171,8 +149,7 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
     constexpr int NBW = (BN / 16) / NWAVES;  // packed-weight tiles (DMA pieces) per wave per chunk
     constexpr int STAGE_BYTES = BM * kStageK;
     static_assert(BM * 4 % THREADS == 0, "tile shape");
-    static_assert((MI == 4 && NI == 2) || (MI == 2 && NI == 2) || (MI == 2 && NI == 1),
-                  "wave tiles with an asm block");
+    static_assert((MI == 4 && NI == 2) || (MI == 2 && NI == 2), "wave tiles with an asm block");
     static_assert(NS == 4 || NS == 8, "ring size");
     static_assert((BN / 16) % NWAVES == 0 && (NS - 2) * P + NBW < 64, "tile shape");
 
@@ -516,8 +493,7 @@ static void launch_tile(const GemmArgs& a, hipStream_t s, int splits = 1) {
                        !a.split_k && splits == 1;
     const int grid_m = (int)((a.M + BM - 1) / BM), grid_n = (int)((a.N + BN - 1) / BN);
     const int ntiles = grid_m * grid_n * splits;
-    // one workgroup per CU for the 8-wave tiles; the small 4-wave tile fits four per CU
-    int grid = num_cus() * (WM * WN <= 4 ? 4 : 1);
+    int grid = num_cus();  // one workgroup per CU
     if (const char* e = getenv("BITLINEAR_PREFILL_GRID")) grid = atoi(e);  // bench-only override
     if (grid > ntiles) grid = ntiles;
     if (plain)
@@ -529,11 +505,11 @@ static void launch_tile(const GemmArgs& a, hipStream_t s, int splits = 1) {
 }
 
 // Small batches (16 < M <= 64) leave most of the chip idle when N supplies few 64 x 128 tiles
-// (fewer than half the CUs): K is then split so that about two work items run per CU, as long
-// as the partial sums (M*N*4 bytes a slice) stay below the packed weights.  Measured on the
-// 28672 -> 7168 layer at M = 64: 95 us unsplit, 33 us in 8 slices; with 168 tiles or more a
-// split only adds traffic.  256 CUs are assumed (the workspace is sized from this too).
-// Returns tiles of K per slice, 0 = no split.
+// (fewer than half the CUs): K is then split over workgroups too, so that about one work item
+// runs per CU, as long as the partial sums (M*N*4 bytes a slice) stay below the packed weights.
+// Measured on the 28672 -> 7168 layer at M = 64: 70 us unsplit, 30 us in 4 slices, 38 us in 8;
+// with 168 tiles or more a split only adds traffic.  256 CUs are assumed (the workspace is sized
+// from this too).  Returns tiles of K per slice, 0 = no split.
 int64_t prefill_split_tiles(int64_t M, int64_t N, int64_t K) {
     if (M <= 16 || M > 64) return 0;
     if (const char* e = getenv("BITLINEAR_PREFILL_SPLIT_TILES")) {  // bench-only override
@@ -542,7 +518,7 @@ int64_t prefill_split_tiles(int64_t M, int64_t N, int64_t K) {
     }
     const int64_t tiles = ((M + 63) / 64) * ((N + 127) / 128), TK = tiles_k(K);
     if (tiles > 128) return 0;
-    int64_t smax = 512 / tiles;
+    int64_t smax = 256 / tiles;
     if (smax > K / (32 * M)) smax = K / (32 * M);
     if (smax > 16) smax = 16;
     if (smax < 2) return 0;
@@ -556,7 +532,7 @@ hipError_t launch_gemm_prefill(const GemmArgs& a_in, hipStream_t s) {
     GemmArgs a = a_in;
     a.split_k = 0;  // set here only
     if (a.K >= ((int64_t)1 << 22) || a.ldq >= ((int64_t)1 << 22)) return hipErrorInvalidValue;
-    const char* e = getenv("BITLINEAR_PREFILL_TILE");  // bench-only override: 0, 1, 2
+    const char* e = getenv("BITLINEAR_PREFILL_TILE");  // bench-only override: 1, 2
     int pick;
     if (e) pick = atoi(e);
     else if (a.M <= 64) pick = 0;
@@ -568,20 +544,8 @@ hipError_t launch_gemm_prefill(const GemmArgs& a_in, hipStream_t s) {
         };
         pick = cost(128, 256) < cost(256, 256) ? 1 : 2;
     }
-    if (pick == 0) {
-        const int64_t per = prefill_split_tiles(a.M, a.N, a.K);
-        const size_t need = gemm_split_ws_bytes(a.M, a.N, a.K);
-        if (per && a.split_ws && a.split_ws_bytes >= need && !getenv("BITLINEAR_PREFILL_NOSPLIT")) {
-            GemmArgs b = a;
-            const int splits = (int)((tiles_k(a.K) + per - 1) / per);
-            b.tk_pitch = a.tk_pitch ? a.tk_pitch : tiles_k(a.K);
-            b.split_k = per * kChunkK;
-            launch_tile<64, 128, 1, 4, 4>(b, s, splits);
-            launch_splitk_reduce(b, splits, s);
-        } else {
-            launch_tile<64, 128, 1, 4, 4>(a, s);
-        }
-    } else if (pick == 1) launch_tile<128, 256, 2, 4, 8>(a, s);
+    if (a.M <= 64) return launch_gemm_mid(a_in, s);  // 16 < M <= 64: gemm_mid.hip
+    if (pick == 1) launch_tile<128, 256, 2, 4, 8>(a, s);
     else launch_tile<256, 256, 2, 4, 8>(a, s);
     return hipGetLastError();
 }

@@ -78,6 +78,7 @@ int64_t prefill_split_tiles(int64_t M, int64_t N, int64_t K);
 void launch_splitk_reduce(const GemmArgs& a, int splits, hipStream_t s);
 hipError_t launch_gemm_decode(const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm_prefill(const GemmArgs& a, hipStream_t s);
+hipError_t launch_gemm_mid(const GemmArgs& a, hipStream_t s);  // 16 < M <= 64
 
 // backward.hip
 struct BackwardArgs {
