@@ -463,7 +463,7 @@ __global__ __launch_bounds__(512, 2) void gemm_tn_bf16_ring(const uint16_t* __re
 #pragma unroll
                 for (int s = 0; s < NI; ++s) {
                     const int64_t jj = j0 + wn * WTN + 32 * s + j;
-                    if (jj < J) C[i * J + jj] = scale * acc[mi][s][r];
+                    if (jj < J) __builtin_nontemporal_store(scale * acc[mi][s][r], &C[i * J + jj]);  // streaming
                 }
             }
         if (i0n < 0) break;

@@ -462,7 +462,9 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
                             }
                             if (GEN && a.accumulate) y += a.Y[m * a.N + n];  // a later K-group
                         }
-                        a.Y[m * a.N + n] = y;
+                        // streaming store: the output is not read again soon, and keeping it out
+                        // of L2 leaves the codes and bits there (3-4 % of the kernel)
+                        __builtin_nontemporal_store(y, &a.Y[m * a.N + n]);
                     }
                 }
             }
