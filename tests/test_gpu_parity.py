@@ -122,7 +122,10 @@ def test_quant_skip_ln_ties_clip_zero_row_affine(bl):
 GEMM_SHAPES = [(8, 256, 512), (1, 2048, 2048), (4, 96, 40), (16, 544, 200), (13, 1056, 72),
                (3, 8192, 64), (16, 7168, 96), (2, 16384, 48), (5, 28672, 32), (1, 2048, 6144),
                (17, 256, 512), (70, 544, 200), (64, 1056, 136), (300, 96, 260), (256, 2048, 384),
-               (513, 1024, 130)]
+               (513, 1024, 130),
+               # 16 < M <= 64 (K split four ways inside the workgroup): fewer chunks than groups,
+               # odd N, exact tiles, a long ragged K
+               (33, 32, 20), (48, 3616, 257), (64, 2048, 128), (20, 7200, 264)]
 
 
 @pytest.mark.parametrize("M,K,N", GEMM_SHAPES)
