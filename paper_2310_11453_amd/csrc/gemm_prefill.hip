@@ -137,10 +137,10 @@ __device__ inline void lds_write_b32(uint32_t ad, uint32_t v) {
 // Persistent: gridDim.x workgroups (one per CU) walk the tiles t = blockIdx.x, + gridDim.x, ...
 // GEN = false: the plain layer (one beta, Y = result): nothing of what follows costs anything.
 // GEN = true adds beta per column group (Eq. 13), accumulation over K-groups, the shift term of
-// Eq. 6 and K split over work items.
+// Eq. 6.
 template <int BM, int BN, int WM, int WN, int NS, bool GEN>
 __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs a, int grid_m,
-                                                                        int grid_n, int splits) {
+                                                                        int grid_n) {
     constexpr int THREADS = WM * WN * kWave;
     constexpr int WTM = BM / WM, WTN = BN / WN;
     constexpr int MI = WTM / 32, NI = WTN / 32;
@@ -166,30 +166,19 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
     const int j = l & 31, g2 = l >> 5;
     const int64_t TN = tiles_n(a.N);
     const int64_t M = a.M;
-    // K, and what follows from it, belong to the work item: with a.split_k an item is one
-    // K-slice of one tile (splits slices per tile), else the whole K.
-    int64_t K = a.K, TK = tiles_k(K), k0 = 0;
-    int nst = (int)((K + kStageK - 1) / kStageK);
-    int64_t kfull = K / kStageK;
+    const int64_t K = a.K, TK = tiles_k(K);
+    const int nst = (int)((K + kStageK - 1) / kStageK);
+    const int64_t kfull = K / kStageK;
     // chunks whose look-ahead stays inside K and that have a successor chunk
-    int64_t main_chunks = kfull >= NS + 7 ? (kfull - NS - 7) / 8 + 1 : 0;
+    const int64_t main_chunks = kfull >= NS + 7 ? (kfull - NS - 7) / 8 + 1 : 0;
     const int64_t TKp = a.tk_pitch ? a.tk_pitch : tiles_k(a.K);  // tiles per tile row in memory
-    auto set_split = [&](int sp) {
-        if (!GEN || !a.split_k) return;
-        k0 = (int64_t)sp * a.split_k;
-        K = a.K - k0 < a.split_k ? a.K - k0 : a.split_k;
-        TK = tiles_k(K);
-        nst = (int)((K + kStageK - 1) / kStageK);
-        kfull = K / kStageK;
-        main_chunks = kfull >= NS + 7 ? (kfull - NS - 7) / 8 + 1 : 0;
-    };
-    const int ntiles = grid_m * grid_n * splits;  // work items
+    const int ntiles = grid_m * grid_n;
 
     // Tile order.  Workgroups are dealt round-robin to the 8 XCDs, each with its own L2; give
     // each XCD one contiguous range of tiles, N fastest, so that the tiles running together
     // on an XCD read the same rows of codes (the large operand: 16 KiB per stage against 2 KiB
     // of packed weights) and those rows come out of HBM once per XCD.
-    auto tile_origin = [&](int t, int64_t& m0, int64_t& n0, int& sp) {
+    auto tile_origin = [&](int t, int64_t& m0, int64_t& n0) {
         int logical = t;
         const int G = (int)gridDim.x;
         if ((ntiles & 7) == 0 && (G & 7) == 0) {
@@ -197,12 +186,6 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
             logical = (t & 7) * (ntiles >> 3) + q;
             // the XCD's range may end before the last round does
             if (q >= (ntiles >> 3)) logical = -1;
-        }
-        // items of one K-slice are neighbours: they share that slice of the codes
-        sp = 0;
-        if (GEN && splits > 1 && logical >= 0) {  // no division on the usual path
-            sp = logical / (grid_m * grid_n);
-            logical -= sp * (grid_m * grid_n);
         }
         m0 = logical < 0 ? -1 : (int64_t)(logical / grid_n) * BM;
         n0 = logical < 0 ? -1 : (int64_t)(logical % grid_n) * BN;
@@ -225,14 +208,14 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
             if (m0 + row > M - 1) row = (int)(M - 1 - m0);
             goff[q] = (uint32_t)row * (uint32_t)a.ldq + gseg[q];
         }
-        gbase = a.codes + m0 * a.ldq + k0;
+        gbase = a.codes + m0 * a.ldq;
         // packed weights: tile t of the block goes to smB + t KiB, lane for lane as it lies in
         // memory; wave w moves tiles w, w + NWAVES, ...  Columns past N read a valid tile.
 #pragma unroll
         for (int q = 0; q < NBW; ++q) {
             int64_t tn = (n0 >> 4) + w + q * NWAVES;
             if (tn > TN - 1) tn = TN - 1;
-            bsrc[q] = a.packed + tile_dword_offset(tn, k0 / kChunkK, TKp) + l * 4;
+            bsrc[q] = a.packed + tile_dword_offset(tn, 0, TKp) + l * 4;
         }
     };
     const uint32_t lds_wave = (uint32_t)(w * kWave * 16);
@@ -310,11 +293,10 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
         }
     };
 
-    int t = (int)blockIdx.x, parity = 0, sp = 0;
+    int t = (int)blockIdx.x, parity = 0;
     int64_t m0, n0;
-    tile_origin(t, m0, n0, sp);
+    tile_origin(t, m0, n0);
     if (m0 < 0) return;  // uniform for the whole workgroup
-    set_split(sp);
     setup_dma(m0, n0);
     issue_tile_start();
 
@@ -397,11 +379,8 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
         block_barrier();
         const int t_next = t + (int)gridDim.x;
         int64_t m0n = -1, n0n = -1;
-        int spn = 0;
-        const int sp_cur = sp;  // the epilogue below still belongs to this item
-        if (t_next < ntiles) tile_origin(t_next, m0n, n0n, spn);
+        if (t_next < ntiles) tile_origin(t_next, m0n, n0n);
         if (m0n >= 0) {
-            set_split(spn);
             setup_dma(m0n, n0n);
             issue_tile_start();
         }
@@ -415,7 +394,7 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
                           : 1.f;
         const uint32_t sc_base = (uint32_t)(uintptr_t)&smScale[parity][wm * WTM + 4 * g2];
         const uint32_t rs_base = (uint32_t)(uintptr_t)&smRowsum[parity][wm * WTM + 4 * g2];
-        const bool special = a.out_acc || (GEN && (a.eta != nullptr || a.accumulate || a.split_k != 0));
+        const bool special = a.out_acc || (GEN && (a.eta != nullptr || a.accumulate));
         float wcol[NI];  // Eq. 6 only
 #pragma unroll
         for (int s = 0; s < NI; ++s)
@@ -447,10 +426,6 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
                         // (GEN: sc4 holds gamma / 128, else the whole scale)
                         float y = GEN ? (float)pm * (bcol[s] * sc4[rr]) : (float)pm * sc4[rr];
                         if (special) {  // uniform
-                            if (GEN && a.split_k) {  // K-slice: 2 * sum_k q b, folded by the reduce kernel
-                                a.split_ws[((int64_t)sp_cur * M + m) * a.N + n] = 2 * acc[mi][s][r];
-                                continue;
-                            }
                             if (a.out_acc) {
                                 reinterpret_cast<int*>(a.Y)[m * a.N + n] = pm;
                                 continue;
@@ -470,7 +445,6 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
             }
         if (m0n < 0) break;
         t = t_next;
-        sp = spn;
         m0 = m0n;
         n0 = n0n;
         parity ^= 1;
@@ -490,43 +464,19 @@ static int num_cus() {
 }
 
 template <int BM, int BN, int WM, int WN, int NS>
-static void launch_tile(const GemmArgs& a, hipStream_t s, int splits = 1) {
-    const bool plain = a.beta_rows >= a.N && a.gstride == 1 && !a.eta && !a.accumulate &&
-                       !a.split_k && splits == 1;
+static void launch_tile(const GemmArgs& a, hipStream_t s) {
+    const bool plain = a.beta_rows >= a.N && a.gstride == 1 && !a.eta && !a.accumulate;
     const int grid_m = (int)((a.M + BM - 1) / BM), grid_n = (int)((a.N + BN - 1) / BN);
-    const int ntiles = grid_m * grid_n * splits;
+    const int ntiles = grid_m * grid_n;
     int grid = num_cus();  // one workgroup per CU
     if (const char* e = getenv("BITLINEAR_PREFILL_GRID")) grid = atoi(e);  // bench-only override
     if (grid > ntiles) grid = ntiles;
     if (plain)
         gemm_prefill_kernel<BM, BN, WM, WN, NS, false>
-            <<<(unsigned)grid, WM * WN * kWave, 0, s>>>(a, grid_m, grid_n, 1);
+            <<<(unsigned)grid, WM * WN * kWave, 0, s>>>(a, grid_m, grid_n);
     else
         gemm_prefill_kernel<BM, BN, WM, WN, NS, true>
-            <<<(unsigned)grid, WM * WN * kWave, 0, s>>>(a, grid_m, grid_n, splits);
-}
-
-// Small batches (16 < M <= 64) leave most of the chip idle when N supplies few 64 x 128 tiles
-// (fewer than half the CUs): K is then split over workgroups too, so that about one work item
-// runs per CU, as long as the partial sums (M*N*4 bytes a slice) stay below the packed weights.
-// Measured on the 28672 -> 7168 layer at M = 64: 70 us unsplit, 30 us in 4 slices, 38 us in 8;
-// with 168 tiles or more a split only adds traffic.  256 CUs are assumed (the workspace is sized
-// from this too).  Returns tiles of K per slice, 0 = no split.
-int64_t prefill_split_tiles(int64_t M, int64_t N, int64_t K) {
-    if (M <= 16 || M > 64) return 0;
-    if (const char* e = getenv("BITLINEAR_PREFILL_SPLIT_TILES")) {  // bench-only override
-        const int64_t per = atoi(e);
-        return per > 0 && per < tiles_k(K) ? per : 0;
-    }
-    const int64_t tiles = ((M + 63) / 64) * ((N + 127) / 128), TK = tiles_k(K);
-    if (tiles > 128) return 0;
-    int64_t smax = 256 / tiles;
-    if (smax > K / (32 * M)) smax = K / (32 * M);
-    if (smax > 16) smax = 16;
-    if (smax < 2) return 0;
-    int64_t per = (TK + smax - 1) / smax;
-    if (per < 2) per = 2;
-    return (TK + per - 1) / per >= 2 ? per : 0;
+            <<<(unsigned)grid, WM * WN * kWave, 0, s>>>(a, grid_m, grid_n);
 }
 
 // K < 2^22 is required (the per-lane offset into a block of 256 rows is kept in 32 bits).
