@@ -150,6 +150,40 @@ def test_matmul_acc_bit_exact_and_y(bl, M, K, N):
     assert np.array_equal(host(acc), np.repeat((-128 * sign.astype(np.int64).sum(1))[None], M, 0))
 
 
+def _random_shapes(n, seed):
+    """Seeded shapes across the three GEMM kernels' ranges of M, with K a multiple of 32 and any N."""
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        M = int(rng.choice([rng.integers(1, 17), rng.integers(17, 65), rng.integers(65, 400)]))
+        K = 32 * int(rng.integers(1, 130))
+        N = int(rng.integers(1, 700))
+        out.append((M, K, N))
+    return out
+
+
+@pytest.mark.parametrize("M,K,N", _random_shapes(24, 20231011))
+def test_matmul_random_shapes(bl, M, K, N):
+    """Accumulators and outputs on seeded random shapes: whichever kernel the batch size selects
+    (streaming, mid-batch, large tiles), with and without the workspace that allows a K split."""
+    print(f"matmul random M={M} K={K} N={N}", flush=True)
+    sd = wl.seed_for(2, 7 * M + 3 * K + N)
+    W = wl.make_weight(N, K, 0.02, sd)
+    X = wl.make_activation(M, K, sd)
+    packed, alpha, beta = bl.bitlinear_pack_weights(dev(W))
+    codes, gamma, rowsum, _ = bl.bitlinear_quant_act(dev(X))
+    sign = oracle.unpack_canonical(host(bl.bitlinear_packed_to_canonical(packed, N, K)).view(np.uint32), K)
+    acc_ref = oracle.matmul_i32(host(codes), sign)
+    y_ref = oracle.dequant(acc_ref, host(gamma), host(beta))
+    ws = torch.empty(max(256, bl.workspace_bytes(bl.OP_MATMUL, M, N, K)), dtype=torch.uint8, device="cuda")
+    for workspace in (None, ws):
+        acc = bl.bitlinear_matmul(codes, gamma, rowsum, packed, N, beta, flags=bl.FLAG_OUT_ACC_I32,
+                                  workspace=workspace)
+        assert np.array_equal(host(acc), acc_ref)
+        y = bl.bitlinear_matmul(codes, gamma, rowsum, packed, N, beta, workspace=workspace)
+        assert np.array_equal(host(y), y_ref)
+
+
 @pytest.mark.parametrize("M,K,N,per_tensor", [(8, 256, 512, False), (8, 256, 512, True),
                                               (16, 2048, 2048, False), (130, 512, 272, True),
                                               (40, 1024, 1000, False)])
