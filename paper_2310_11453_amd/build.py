@@ -14,7 +14,7 @@ PKG = Path(__file__).resolve().parent
 CSRC = PKG / "csrc"
 OBJ = PKG / "_build"
 LIB = PKG / "libbitlinear.so"
-SOURCES = ["pack.hip", "quant.hip", "gemm_decode.hip", "gemm_prefill.hip", "gemm_mid.hip", "backward.hip", "ln_backward.hip", "api.hip"]
+SOURCES = ["pack.hip", "quant.hip", "gemm_decode.hip", "gemm_prefill.hip", "gemm_mid.hip", "gemm_stream.hip", "backward.hip", "ln_backward.hip", "api.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -279,8 +279,12 @@ size_t gemm_split_ws_bytes(int64_t M, int64_t N, int64_t K) {
     int64_t splits = 0;
     if (M <= 16) {
         if (TK > 32) splits = (TK + 15) / 16;
-    } else if (const int64_t per = prefill_split_tiles(M, N, K)) {
-        splits = (TK + per - 1) / per;
+    } else {  // enough for whichever of the two mid-batch kernels takes the shape
+        if (const int64_t per = prefill_split_tiles(M, N, K)) splits = (TK + per - 1) / per;
+        if (const int64_t per = stream_split_tiles(M, K)) {
+            const int64_t s2 = (TK + per - 1) / per;
+            splits = s2 > splits ? s2 : splits;
+        }
     }
     return (size_t)splits * (size_t)M * (size_t)N * 4;
 }

@@ -496,7 +496,10 @@ hipError_t launch_gemm_prefill(const GemmArgs& a_in, hipStream_t s) {
         };
         pick = cost(128, 256) < cost(256, 256) ? 1 : 2;
     }
-    if (a.M <= 64) return launch_gemm_mid(a_in, s);  // 16 < M <= 64: gemm_mid.hip
+    if (a.M <= 64) {  // up to 32 tokens: gemm_stream.hip where it takes the shape; else gemm_mid.hip
+        if (!getenv("BITLINEAR_MID_ONLY") && launch_gemm_stream(a_in, s)) return hipGetLastError();
+        return launch_gemm_mid(a_in, s);
+    }
     if (pick == 1) launch_tile<128, 256, 2, 4, 8>(a, s);
     else launch_tile<256, 256, 2, 4, 8>(a, s);
     return hipGetLastError();

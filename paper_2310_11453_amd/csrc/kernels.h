@@ -79,6 +79,8 @@ void launch_splitk_reduce(const GemmArgs& a, int splits, hipStream_t s);
 hipError_t launch_gemm_decode(const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm_prefill(const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm_mid(const GemmArgs& a, hipStream_t s);  // 16 < M <= 64
+bool launch_gemm_stream(const GemmArgs& a, hipStream_t s);      // 16 < M <= 32; false: not taken
+int64_t stream_split_tiles(int64_t M, int64_t K);
 
 // backward.hip
 struct BackwardArgs {

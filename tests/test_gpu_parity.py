@@ -184,6 +184,33 @@ def test_matmul_random_shapes(bl, M, K, N):
         assert np.array_equal(host(y), y_ref)
 
 
+# 17 to 32 tokens (weights streamed through registers): N not a multiple of 4 (element-wise
+# stores), one to four pairs of tiles per workgroup, 1 / 5 / 7 / 8 waves, chunks spread unevenly
+# over the waves, a K long enough for two slices, and a shape the kernel hands to the mid-batch one
+STREAM_SHAPES = [(17, 512, 30), (32, 1056, 37), (25, 4608, 8200), (31, 1024, 32768), (24, 7168, 1536),
+                 (32, 4096, 24000), (19, 8704, 520), (32, 16384, 1024), (18, 28672, 7168)]
+
+
+@pytest.mark.parametrize("M,K,N", STREAM_SHAPES)
+def test_matmul_17_to_32_tokens(bl, M, K, N):
+    print(f"matmul stream M={M} K={K} N={N}", flush=True)
+    sd = wl.seed_for(2, 11 * M + K + N)
+    W = wl.make_weight(N, K, 0.02, sd)
+    X = wl.make_activation(M, K, sd)
+    packed, alpha, beta = bl.bitlinear_pack_weights(dev(W))
+    codes, gamma, rowsum, _ = bl.bitlinear_quant_act(dev(X))
+    sign = oracle.unpack_canonical(host(bl.bitlinear_packed_to_canonical(packed, N, K)).view(np.uint32), K)
+    acc_ref = oracle.matmul_i32(host(codes), sign)
+    y_ref = oracle.dequant(acc_ref, host(gamma), host(beta))
+    ws = torch.empty(max(256, bl.workspace_bytes(bl.OP_MATMUL, M, N, K)), dtype=torch.uint8, device="cuda")
+    for workspace in (None, ws):
+        acc = bl.bitlinear_matmul(codes, gamma, rowsum, packed, N, beta, flags=bl.FLAG_OUT_ACC_I32,
+                                  workspace=workspace)
+        assert np.array_equal(host(acc), acc_ref)
+        y = bl.bitlinear_matmul(codes, gamma, rowsum, packed, N, beta, workspace=workspace)
+        assert np.array_equal(host(y), y_ref)
+
+
 @pytest.mark.parametrize("M,K,N,per_tensor", [(8, 256, 512, False), (8, 256, 512, True),
                                               (16, 2048, 2048, False), (130, 512, 272, True),
                                               (40, 1024, 1000, False)])
