@@ -315,8 +315,11 @@ def main():
             run_all()
             t = event_ms(run_all, 5, torch) / len(runners)
             nbytes = sum(gemm_bytes(Md, L2.K, L2.N) + 5 * Md * L2.K for (L2, _, _) in protos) * 24
-            block.append(dict(M=Md, layers=24, launches=24 * 2 * len(protos), us_per_step=t * 1e3,
-                              us_per_launch=t * 1e3 / (24 * 2 * len(protos)),
+            # one token with K <= 16384: the GEMM launch quantises the row itself (one launch a
+            # layer); otherwise quantiser + GEMM
+            n_launch = 24 * sum(1 if Md == 1 and L2.K <= 16384 else 2 for (L2, _, _) in protos)
+            block.append(dict(M=Md, layers=24, launches=n_launch, us_per_step=t * 1e3,
+                              us_per_launch=t * 1e3 / n_launch,
                               gbs=nbytes / (t * 1e-3) / 1e9, launch=mode))
         decode["block_decode_1p3b"] = block
         del sets, protos

@@ -240,11 +240,21 @@ int bitlinear_forward(const float* X, int64_t M, int64_t K, const void* packed, 
     int8_t* codes = (int8_t*)(base + ws.codes);
     float* gamma = (float*)(base + ws.gamma);
     int32_t* rowsum = (int32_t*)(base + ws.rowsum);
-    int rc = bitlinear_quant_act(X, M, K, ln_gain, ln_bias, ln_eps, granularity,
-                                 flags & BL_FLAG_SKIP_LN, codes, gamma, rowsum, nullptr,
-                                 base + ws.quant, ws.split - ws.quant, stream);
-    if (rc != BL_OK) return rc;
+    // one token: the GEMM kernel quantises the row itself and the layer is one launch (codes,
+    // gamma and rowsum still land in the workspace)
+    const bool fuse = gemm_decode_fuses_quant(M, K);
+    if (!fuse) {
+        int rc = bitlinear_quant_act(X, M, K, ln_gain, ln_bias, ln_eps, granularity,
+                                     flags & BL_FLAG_SKIP_LN, codes, gamma, rowsum, nullptr,
+                                     base + ws.quant, ws.split - ws.quant, stream);
+        if (rc != BL_OK) return rc;
+    }
     GemmArgs a{};
+    if (fuse) {
+        a.x_row = X; a.ln_gain = ln_gain; a.ln_bias = ln_bias; a.ln_eps = ln_eps;
+        a.skip_ln = (flags & BL_FLAG_SKIP_LN) != 0;
+        a.codes_out = codes; a.gamma_out = gamma; a.rowsum_out = rowsum;
+    }
     a.codes = codes; a.gamma = gamma; a.rowsum = rowsum; a.M = M; a.K = K; a.N = N;
     a.packed = (const uint32_t*)packed; a.beta = beta;
     a.per_tensor = granularity == BL_GAMMA_PER_TENSOR;

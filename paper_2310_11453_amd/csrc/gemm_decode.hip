@@ -18,16 +18,171 @@
 // operands, reusing them for every tile.  Partial sums meet in LDS.
 #include "common.h"
 #include "kernels.h"
+#include "rowops.h"
 
 namespace bl {
+
+// LayerNorm (Eq. 12) and the 8-bit absmax quantiser (Eq. 4-5) of ONE token by a whole workgroup,
+// with the arithmetic of the stand-alone quantiser: sums in fp64 about an element of the row,
+// the normalised value rounded once to fp32, then scale = 128 / gamma, rne, clamp - one fp32
+// operation per step.  The codes go to `lds_codes` (K bytes); returns gamma and sum_k codes.
+// Every thread of the workgroup must call it (it synchronises), K <= 16 * blockDim.
+// `after_loads` runs once the row's loads are issued: loads return in order, so whatever else
+// the caller wants in flight meanwhile has to queue behind the row, not ahead of it.
+struct TokenQuant {
+    float gamma;
+    int rowsum;
+};
+template <class F>
+__device__ inline TokenQuant quant_token(const GemmArgs& a, uint32_t* lds_codes, double (*smd)[16],
+                                         float (*smf)[16], int* smi, F&& after_loads) {
+    constexpr int NV = 4;
+    const int T = blockDim.x, t = threadIdx.x, W = T / kWave, wave = t / kWave;
+    const bool lead = (t & (kWave - 1)) == 0;
+    const int K4 = (int)(a.K / 4);
+    const float4* __restrict__ x4 = reinterpret_cast<const float4*>(a.x_row);
+    float4 v[NV];
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int idx = t + j * T;
+        v[j] = x4[idx < K4 ? idx : K4 - 1];
+    }
+    const float first = a.x_row[0];
+    after_loads();
+    const bool affine = a.ln_gain != nullptr || a.ln_bias != nullptr;
+    bool have_amax = false;
+    float amax = 0.f;
+    if (!a.skip_ln) {
+        const double c = (double)first;
+        double s = 0.0, q = 0.0;
+        float mn = v[0].x, mx = v[0].x;  // always an element of the row (clamped index)
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            if (t + j * T < K4) {
+                const double dx = (double)v[j].x, dy = (double)v[j].y;
+                const double dz = (double)v[j].z, dw = (double)v[j].w;
+                s += (dx + dy) + (dz + dw);
+                q = fma(dx - c, dx - c, q);
+                q = fma(dy - c, dy - c, q);
+                q = fma(dz - c, dz - c, q);
+                q = fma(dw - c, dw - c, q);
+                mn = fminf(fminf(mn, v[j].x), fminf(fminf(v[j].y, v[j].z), v[j].w));
+                mx = fmaxf(fmaxf(mx, v[j].x), fmaxf(fmaxf(v[j].y, v[j].z), v[j].w));
+            }
+        }
+        s = wave_reduce(s, OpSum{});
+        q = wave_reduce(q, OpSum{});
+        mn = wave_reduce(mn, OpMin{});
+        mx = wave_reduce(mx, OpMax{});
+        if (lead) {
+            smd[0][wave] = s;
+            smd[1][wave] = q;
+            smf[0][wave] = mn;
+            smf[1][wave] = mx;
+        }
+        __syncthreads();
+        s = smd[0][0];
+        q = smd[1][0];
+        mn = smf[0][0];
+        mx = smf[1][0];
+        for (int i = 1; i < W; ++i) {
+            s += smd[0][i];
+            q += smd[1][i];
+            mn = fminf(mn, smf[0][i]);
+            mx = fmaxf(mx, smf[1][i]);
+        }
+        const double mu = s / (double)a.K;
+        const double var = fmax(q / (double)a.K - (mu - c) * (mu - c), 0.0);
+        const double rstd = 1.0 / sqrt(var + (double)a.ln_eps);
+        if (!affine) {
+            // x -> fl32((x - mu) * rstd) is monotone: the largest magnitude sits at min or max
+            const float lo = (float)(((double)mn - mu) * rstd);
+            const float hi = (float)(((double)mx - mu) * rstd);
+            amax = fmaxf(fabsf(lo), fabsf(hi));
+            have_amax = true;
+        }
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            const int idx = t + j * T;
+            float4 o;
+            o.x = (float)(((double)v[j].x - mu) * rstd);
+            o.y = (float)(((double)v[j].y - mu) * rstd);
+            o.z = (float)(((double)v[j].z - mu) * rstd);
+            o.w = (float)(((double)v[j].w - mu) * rstd);
+            if (idx < K4) {
+                if (a.ln_gain) {
+                    const float4 g = reinterpret_cast<const float4*>(a.ln_gain)[idx];
+                    o.x = o.x * g.x; o.y = o.y * g.y; o.z = o.z * g.z; o.w = o.w * g.w;
+                }
+                if (a.ln_bias) {
+                    const float4 b = reinterpret_cast<const float4*>(a.ln_bias)[idx];
+                    o.x = o.x + b.x; o.y = o.y + b.y; o.z = o.z + b.z; o.w = o.w + b.w;
+                }
+                v[j] = o;
+            }
+        }
+    }
+    if (!have_amax) {  // uniform: no LayerNorm, or a gain / bias after it
+        float m = 0.f;
+#pragma unroll
+        for (int j = 0; j < NV; ++j) {
+            if (t + j * T < K4)
+                m = fmaxf(m, fmaxf(fmaxf(fabsf(v[j].x), fabsf(v[j].y)), fmaxf(fabsf(v[j].z), fabsf(v[j].w))));
+        }
+        m = wave_reduce(m, OpMax{});
+        if (lead) smf[2][wave] = m;
+        __syncthreads();
+        amax = smf[2][0];
+        for (int i = 1; i < W; ++i) amax = fmaxf(amax, smf[2][i]);
+    }
+    const float gamma = fmaxf(amax, 1e-5f);
+    const float scale = 128.0f / gamma;
+    int rs = 0;
+#pragma unroll
+    for (int j = 0; j < NV; ++j) {
+        const int idx = t + j * T;
+        // the integral float plus 128 lies in 0..255 and goes straight into its byte; flipping
+        // the top bit of each byte turns that offset form into two's complement
+        const float q0 = fminf(fmaxf(rintf(v[j].x * scale), -128.f), 127.f) + 128.f;
+        const float q1 = fminf(fmaxf(rintf(v[j].y * scale), -128.f), 127.f) + 128.f;
+        const float q2 = fminf(fmaxf(rintf(v[j].z * scale), -128.f), 127.f) + 128.f;
+        const float q3 = fminf(fmaxf(rintf(v[j].w * scale), -128.f), 127.f) + 128.f;
+        uint32_t wd = __builtin_amdgcn_cvt_pk_u8_f32(q0, 0, 0u);
+        wd = __builtin_amdgcn_cvt_pk_u8_f32(q1, 1, wd);
+        wd = __builtin_amdgcn_cvt_pk_u8_f32(q2, 2, wd);
+        wd = __builtin_amdgcn_cvt_pk_u8_f32(q3, 3, wd) ^ 0x80808080u;
+        if (idx < K4) {
+            rs = __builtin_amdgcn_sdot4((int)wd, 0x01010101, rs, false);  // sum of the four codes
+            lds_codes[idx] = wd;
+            if (blockIdx.x == 0 && blockIdx.y == 0 && a.codes_out)
+                reinterpret_cast<uint32_t*>(a.codes_out)[idx] = wd;
+        }
+    }
+    rs = wave_reduce(rs, OpSum{});
+    if (lead) smi[wave] = rs;
+    __syncthreads();  // also: the codes are in LDS
+    rs = smi[0];
+    for (int i = 1; i < W; ++i) rs += smi[i];
+    if (t == 0 && blockIdx.x == 0 && blockIdx.y == 0) {
+        if (a.gamma_out) a.gamma_out[0] = gamma;
+        if (a.rowsum_out) a.rowsum_out[0] = rs;
+    }
+    return {gamma, rs};
+}
 
 // C = K-chunks per wave and round, T = weight tiles per workgroup (compile-time bound; `tpb`
 // <= T of them are used), MAXT = launch bound.  ONE_ROUND: the waves of the group cover K in a
 // single round, so a tile's partial sum goes straight to LDS and no per-tile registers are
 // kept - this is what lets a wave keep eight 1 KiB weight loads in flight.
-template <int C, int T, int MAXT, bool ONE_ROUND>
+// FUSED (one round, M = 1): the codes come from quant_token, not from memory.
+template <int C, int T, int MAXT, bool ONE_ROUND, bool FUSED = false>
 __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) {
+    static_assert(!FUSED || ONE_ROUND, "the fused quantiser covers K in one round");
     __shared__ __attribute__((aligned(16))) int red[(MAXT / kWave) * T * 256];  // [W][T][64][4]
+    __shared__ __attribute__((aligned(16))) uint32_t row_codes[FUSED ? 16384 / 4 : 1];
+    __shared__ double smd[FUSED ? 2 : 1][16];
+    __shared__ float smf[FUSED ? 3 : 1][16];
+    __shared__ int smi[16];
     const int W = blockDim.x / kWave;
     const int w = threadIdx.x / kWave, l = threadIdx.x % kWave;
     const int m = l & 15, g = l >> 4;
@@ -50,10 +205,14 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
     };
     const float beta_first = beta_of(tn0 + w);
     const int mc = m < M ? m : M - 1;
-    const int rs = a.rowsum[mc * a.gstride];
-    const float gm = a.per_tensor ? a.gamma[0] : a.gamma[mc * a.gstride];
-    // Eq. 6 only; without it the load goes to gamma (always valid) and the value is not used
-    const float eta = *(a.eta ? a.eta + mc * a.gstride : a.gamma);
+    int rs = 0;
+    float gm = 0.f, eta = 0.f;
+    if constexpr (!FUSED) {
+        rs = a.rowsum[mc * a.gstride];
+        gm = a.per_tensor ? a.gamma[0] : a.gamma[mc * a.gstride];
+        // Eq. 6 only; without it the load goes to gamma (always valid) and the value is not used
+        eta = *(a.eta ? a.eta + mc * a.gstride : a.gamma);
+    }
 
     int part[ONE_ROUND ? 1 : T][4];
     if (!ONE_ROUND) {
@@ -74,16 +233,18 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
         // activation operand: lane (m, g) holds codes[m][512*tk + 64*i + 16*g .. +15].  Rows
         // m >= M read row M-1 (their outputs are never stored); columns k >= K read the last 16
         // valid bytes (the packed bits there are zero, so they contribute nothing).
-        const int8_t* arow = a.codes + (int64_t)(m < M ? m : M - 1) * a.ldq;
         v4i act[C][8];
+        auto load_act = [&](const int8_t* arow) {
 #pragma unroll
-        for (int c = 0; c < C; ++c)
+            for (int c = 0; c < C; ++c)
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                int64_t k = (tk0 + c) * kChunkK + 64 * i + 16 * g;
-                if (k > a.K - 16) k = a.K - 16;
-                act[c][i] = *reinterpret_cast<const v4i*>(arow + k);
-            }
+                for (int i = 0; i < 8; ++i) {
+                    int64_t k = (tk0 + c) * kChunkK + 64 * i + 16 * g;
+                    if (k > a.K - 16) k = a.K - 16;
+                    act[c][i] = *reinterpret_cast<const v4i*>(arow + k);
+                }
+        };
+        if constexpr (!FUSED) load_act(a.codes + (int64_t)(m < M ? m : M - 1) * a.ldq);
 
         // Weight tiles: a software pipeline of depth kDepth per wave.  Asking for everything at
         // once looks attractive for a 4-microsecond stream, but the memory system then returns
@@ -92,7 +253,9 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
         // CU, enough to cover the latency) tiles arrive in order and compute overlaps the stream.
         // Tiles past the end re-read the last tile (never stored); chunks past the end are
         // masked to zero arithmetically (no branch around a load).
-        constexpr int kDepth = T < 3 ? T : 3;
+        // FUSED: the waves spend the next microseconds on the token, not on MFMAs, so every tile
+        // is requested now and the stream runs under the quantiser.
+        constexpr int kDepth = FUSED ? T : T < 3 ? T : 3;
         v4i wt[T][C];
         // chunk c of this wave: valid index and all-ones / all-zeros mask
         int64_t tkc[C];
@@ -115,8 +278,22 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
             for (int c = 0; c < C; ++c)  // read once: streaming loads leave L2 to the codes (3-6 %)
                 wt[t][c] = __builtin_nontemporal_load(reinterpret_cast<const v4i*>(wbase[c] + off));
         };
+        if constexpr (FUSED) {
+            // the row is normalised and quantised while the tiles are on their way; every column
+            // of the MFMA then holds the one token
+            const TokenQuant tq = quant_token(a, row_codes, smd, smf, smi, [&]() {
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int t = 0; t < kDepth; ++t) load_tile(t);
+                for (int t = 0; t < kDepth; ++t) load_tile(t);
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            gm = tq.gamma;
+            rs = tq.rowsum;
+            load_act(reinterpret_cast<const int8_t*>(row_codes));
+        } else {
+#pragma unroll
+            for (int t = 0; t < kDepth; ++t) load_tile(t);
+        }
 
 #pragma unroll
         for (int t = 0; t < T; ++t) {
@@ -249,27 +426,33 @@ static int num_cus() {
     return n;
 }
 
-template <int C, int T, int MAXT, bool ONE_ROUND>
+template <int C, int T, int MAXT, bool ONE_ROUND, bool FUSED = false>
 static void launch_one(const GemmArgs& a, int W, int tpb, hipStream_t s) {
     const int64_t TN = tiles_n(a.N);
     const unsigned splits = a.split_k ? (unsigned)((a.K + a.split_k - 1) / a.split_k) : 1u;
     const dim3 grid((unsigned)((TN + tpb - 1) / tpb), splits);
-    gemm_decode_kernel<C, T, MAXT, ONE_ROUND><<<grid, W * kWave, 0, s>>>(a, tpb);
+    gemm_decode_kernel<C, T, MAXT, ONE_ROUND, FUSED><<<grid, W * kWave, 0, s>>>(a, tpb);
 }
 
 // one round, up to 8 waves, exactly tpb = 1..8 tiles per group
-template <int C>
+template <int C, bool FUSED>
 static void launch_tiles(const GemmArgs& a, int W, int tpb, hipStream_t s) {
     switch (tpb) {
-        case 1: launch_one<C, 1, 512, true>(a, W, 1, s); break;
-        case 2: launch_one<C, 2, 512, true>(a, W, 2, s); break;
-        case 3: launch_one<C, 3, 512, true>(a, W, 3, s); break;
-        case 4: launch_one<C, 4, 512, true>(a, W, 4, s); break;
-        case 5: launch_one<C, 5, 512, true>(a, W, 5, s); break;
-        case 6: launch_one<C, 6, 512, true>(a, W, 6, s); break;
-        case 7: launch_one<C, 7, 512, true>(a, W, 7, s); break;
-        default: launch_one<C, 8, 512, true>(a, W, 8, s); break;
+        case 1: launch_one<C, 1, 512, true, FUSED>(a, W, 1, s); break;
+        case 2: launch_one<C, 2, 512, true, FUSED>(a, W, 2, s); break;
+        case 3: launch_one<C, 3, 512, true, FUSED>(a, W, 3, s); break;
+        case 4: launch_one<C, 4, 512, true, FUSED>(a, W, 4, s); break;
+        case 5: launch_one<C, 5, 512, true, FUSED>(a, W, 5, s); break;
+        case 6: launch_one<C, 6, 512, true, FUSED>(a, W, 6, s); break;
+        case 7: launch_one<C, 7, 512, true, FUSED>(a, W, 7, s); break;
+        default: launch_one<C, 8, 512, true, FUSED>(a, W, 8, s); break;
     }
+}
+
+// One token and a K that one round of waves covers (quant_token holds 16 elements per thread,
+// and a wave covers two 512-chunks): the small-batch kernel can quantise the row itself.
+bool gemm_decode_fuses_quant(int64_t M, int64_t K) {
+    return M == 1 && tiles_k(K) <= 32 && !env_int("BITLINEAR_DECODE_NOFUSE", 0);
 }
 
 // K > 16384 with a workspace: split K over workgroups so that every slice takes the one-round
@@ -298,6 +481,7 @@ hipError_t launch_gemm_decode(const GemmArgs& a_in, hipStream_t s) {
     const int64_t TN = tiles_n(a.N);
     int64_t TK = tiles_k(a.K);
     int splits = 1;
+    const bool fused = a.x_row != nullptr;  // the caller asked gemm_decode_fuses_quant
     const size_t need = gemm_split_ws_bytes(a.M, a.N, a.K);
     if (need && a.split_ws && a.split_ws_bytes >= need && !env_int("BITLINEAR_DECODE_NOSPLIT", 0)) {
         splits = (int)((TK + 15) / 16);
@@ -321,19 +505,27 @@ hipError_t launch_gemm_decode(const GemmArgs& a_in, hipStream_t s) {
         // K < 4096: one K-chunk per wave, W = TK waves cover K in one round
         const int W = (int)TK;
         const int tpb = tiles_per_group(8);
-        launch_tiles<1>(a, W, tpb, s);
+        if (fused) launch_tiles<1, true>(a, W, tpb, s);
+        else launch_tiles<1, false>(a, W, tpb, s);
     } else if (TK <= 16) {
         // 4096 <= K <= 8192: two chunks per wave (the fold of the bit planes, once per tile and
         // wave, is then shared by two chunks), W = ceil(TK/2) <= 8 waves, one round
         const int W = (int)((TK + 1) / 2);
         const int tpb = tiles_per_group(8);
-        launch_tiles<2>(a, W, tpb, s);
+        if (fused) launch_tiles<2, true>(a, W, tpb, s);
+        else launch_tiles<2, false>(a, W, tpb, s);
     } else if (TK <= 32) {
         // K <= 16384: up to 16 waves of two chunks, one round; 128 registers per lane
         const int W = (int)((TK + 1) / 2);
         const int tpb = tiles_per_group(2);
-        if (tpb <= 1) launch_one<2, 1, 1024, true>(a, W, 1, s);
-        else launch_one<2, 2, 1024, true>(a, W, 2, s);
+        if (fused) {
+            if (tpb <= 1) launch_one<2, 1, 1024, true, true>(a, W, 1, s);
+            else launch_one<2, 2, 1024, true, true>(a, W, 2, s);
+        } else if (tpb <= 1) {
+            launch_one<2, 1, 1024, true>(a, W, 1, s);
+        } else {
+            launch_one<2, 2, 1024, true>(a, W, 2, s);
+        }
     } else {
         // longer K: two chunks per wave and round, up to 16 waves, several rounds
         const int64_t slots = (TK + 1) / 2;

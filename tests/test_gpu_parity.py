@@ -230,6 +230,49 @@ def test_forward_end_to_end(bl, M, K, N, per_tensor):
     assert (acc != r["acc"]).mean() <= 1e-3  # differs only where an x^ sits on a rounding tie
 
 
+# One token: the small-batch GEMM kernel normalises and quantises the row itself (one launch).
+# K below one chunk, one chunk per wave, two per wave, the 16-wave kernels, a ragged last chunk;
+# every variant of the quantiser the forward call offers.
+@pytest.mark.parametrize("K,N", [(96, 40), (2048, 6144), (3616, 257), (7168, 1000), (8192, 2048),
+                                 (12320, 520), (16384, 300)])
+@pytest.mark.parametrize("variant", ["plain", "affine", "skip_ln", "per_tensor"])
+def test_forward_single_token(bl, K, N, variant, monkeypatch):
+    print(f"forward single token K={K} N={N} {variant}", flush=True)
+    sd = wl.seed_for(0, 5 * K + N)
+    W = wl.make_weight(N, K, 0.02, sd)
+    X = wl.make_activation(1, K, sd)
+    rng = np.random.default_rng(sd)
+    gain = (1.0 + 0.1 * rng.standard_normal(K)).astype(np.float32) if variant == "affine" else None
+    bias = (0.05 * rng.standard_normal(K)).astype(np.float32) if variant == "affine" else None
+    kw = dict(per_tensor=variant == "per_tensor", flags=bl.FLAG_SKIP_LN if variant == "skip_ln" else 0,
+              ln_gain=None if gain is None else dev(gain), ln_bias=None if bias is None else dev(bias))
+    r = oracle.forward(X, W, per_tensor=variant == "per_tensor", skip_ln=variant == "skip_ln",
+                       gain=gain, bias=bias)
+    packed, alpha, beta = bl.bitlinear_pack_weights(dev(W))
+    y = host(bl.bitlinear_forward(dev(X), packed, N, beta, **kw))
+    rms = np.sqrt(np.mean(r["y"].astype(np.float64) ** 2))
+    assert np.abs(y - r["y"]).max() <= 1e-3 * rms
+    kw_acc = dict(kw, flags=kw["flags"] | bl.FLAG_OUT_ACC_I32)
+    acc = host(bl.bitlinear_forward(dev(X), packed, N, beta, **kw_acc))
+    assert (acc != r["acc"]).mean() <= 1e-3  # differs only where an x^ sits on a rounding tie
+    # the workspace holds what the stand-alone quantiser would have put there
+    ws = torch.zeros(bl.workspace_bytes(bl.OP_FORWARD, 1, N, K, variant == "per_tensor"),
+                     dtype=torch.uint8, device="cuda")
+    bl.bitlinear_forward(dev(X), packed, N, beta, workspace=ws, **kw)
+    codes, gamma, rowsum, _ = bl.bitlinear_quant_act(dev(X), per_tensor=variant == "per_tensor",
+                                                     flags=kw["flags"], ln_gain=kw["ln_gain"],
+                                                     ln_bias=kw["ln_bias"])
+    held = host(ws)
+    assert (held[:K].view(np.int8) != host(codes)[0]).mean() <= 1e-3
+    # and the two-launch path (quantiser, then GEMM) gives the same layer output
+    monkeypatch.setenv("BITLINEAR_DECODE_NOFUSE", "1")
+    y2 = host(bl.bitlinear_forward(dev(X), packed, N, beta, **kw))
+    acc2 = host(bl.bitlinear_forward(dev(X), packed, N, beta, **kw_acc))
+    monkeypatch.delenv("BITLINEAR_DECODE_NOFUSE")
+    assert (acc2 != acc).mean() <= 1e-3
+    assert np.abs(y2 - y).max() <= 1e-3 * rms
+
+
 def test_empty_batch_and_errors(bl):
     W = dev(wl.make_weight(32, 64, 0.02, 1))
     packed, alpha, beta = bl.bitlinear_pack_weights(W)
