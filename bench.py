@@ -315,14 +315,62 @@ def main():
             run_all()
             t = event_ms(run_all, 5, torch) / len(runners)
             nbytes = sum(gemm_bytes(Md, L2.K, L2.N) + 5 * Md * L2.K for (L2, _, _) in protos) * 24
-            # one token with K <= 16384: the GEMM launch quantises the row itself (one launch a
+            # one token with K <= 32768: the GEMM launch quantises the row itself (one launch a
             # layer); otherwise quantiser + GEMM
-            n_launch = 24 * sum(1 if Md == 1 and L2.K <= 16384 else 2 for (L2, _, _) in protos)
+            n_launch = 24 * sum(1 if Md == 1 and L2.K <= 32768 else 2 for (L2, _, _) in protos)
             block.append(dict(M=Md, layers=24, launches=n_launch, us_per_step=t * 1e3,
                               us_per_launch=t * 1e3 / n_launch,
                               gbs=nbytes / (t * 1e-3) / 1e9, launch=mode))
         decode["block_decode_1p3b"] = block
         del sets, protos
+
+        # The same chain at the 30B shapes (with the 7168 -> 7168 output projection added), one
+        # token: eight distinct layers (0.6 GB of packed weights) in one HIP graph, one launch per
+        # projection (the GEMM kernel quantises the row itself).
+        protos3 = []
+        for li, L3 in enumerate(list(c3.layers[:1]) + [wl.Layer("o", 7168, 7168)] + list(c3.layers[1:])):
+            W3 = wl.make_weight(L3.N, L3.K, c3.w_std, wl.seed_for(3, 10 + li))
+            p3, _, b3 = bl.bitlinear_pack_weights(torch.from_numpy(W3).to(dev))
+            protos3.append((L3, p3, b3))
+            del W3
+        layers8 = [[(L3, p3.clone(), b3) for (L3, p3, b3) in protos3] for _ in range(8)]
+        h0 = torch.from_numpy(wl.make_activation(1, 7168, wl.seed_for(3, 50))).to(dev)
+        bufs3 = {L3.name: torch.empty((1, L3.N), dtype=torch.float32, device=dev) for (L3, _, _) in protos3}
+        wss3 = {L3.name: torch.empty(bl.workspace_bytes(bl.OP_FORWARD, 1, L3.N, L3.K), dtype=torch.uint8,
+                                     device=dev) for (L3, _, _) in protos3}
+
+        def run_stack3():
+            h = h0
+            for layer in layers8:
+                for (L3, p3, b3) in layer:
+                    x_in = h if h.shape[1] == L3.K else h.view(-1)[:L3.K].view(1, L3.K)
+                    h = bl.bitlinear_forward(x_in, p3, L3.N, b3, out=bufs3[L3.name], workspace=wss3[L3.name])
+            return h
+
+        ref3 = run_stack3().clone()
+        torch.cuda.synchronize()
+        timed3, mode3 = run_stack3, "eager launches"
+        try:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                run_stack3()
+            torch.cuda.current_stream().wait_stream(side)
+            g3 = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g3):
+                run_stack3()
+            g3.replay()
+            torch.cuda.synchronize()
+            if torch.equal(ref3, bufs3["down"]):
+                timed3, mode3 = g3.replay, "one HIP graph of eight layers, replayed"
+        except Exception as exc:
+            mode3 = f"eager launches (graph capture failed: {type(exc).__name__})"
+        timed3()
+        t3 = event_ms(timed3, 5, torch) / 8
+        nbytes3 = sum(gemm_bytes(1, L3.K, L3.N) + 5 * L3.K for (L3, _, _) in protos3)
+        decode["block_decode_30b"] = dict(M=1, layers=8, us_per_layer=t3 * 1e3, gbs=nbytes3 / (t3 * 1e-3) / 1e9,
+                                          launch=mode3)
+        del layers8, protos3
         decode["value"] = best["gbs"]
         decode["unit"] = "GB/s"
         decode["roofline"] = dict(bound="hbm", kernel="gemm_decode_kernel", achieved=best["gbs"],

@@ -114,11 +114,12 @@ int bitlinear_matmul(const int8_t* codes, const float* gamma, const int32_t* row
                      void* stream);
 
 /* Eq. 11, the whole layer: bitlinear_quant_act into the workspace, then
- * bitlinear_matmul.  Arguments as above.  For one token (M = 1, K <= 16384) both
- * steps run in one launch: the GEMM kernel normalises and quantises the row
- * itself, with the quantiser's arithmetic but its own summation order, so a
- * code can differ from bitlinear_quant_act's where x^ * 128 / gamma sits on a
- * rounding tie.  The workspace is required in every case
+ * bitlinear_matmul.  Arguments as above.  For one token (M = 1, K <= 32768 and
+ * an N that one round of workgroups covers) both steps run in one launch: the
+ * GEMM kernel normalises and quantises the row itself, with the quantiser's
+ * arithmetic but its own summation order, so a code can differ from
+ * bitlinear_quant_act's where x^ * 128 / gamma sits on a rounding tie.  The
+ * workspace is required in every case
  * (bitlinear_workspace_bytes(BL_OP_FORWARD, ...)); its contents afterwards are
  * unspecified. */
 int bitlinear_forward(const float* X, int64_t M, int64_t K, const void* packed, int64_t N,

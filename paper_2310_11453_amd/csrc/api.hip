@@ -242,7 +242,7 @@ int bitlinear_forward(const float* X, int64_t M, int64_t K, const void* packed, 
     int32_t* rowsum = (int32_t*)(base + ws.rowsum);
     // one token: the GEMM kernel quantises the row itself and the layer is one launch (codes,
     // gamma and rowsum still land in the workspace)
-    const bool fuse = gemm_decode_fuses_quant(M, K);
+    const bool fuse = gemm_decode_fuses_quant(M, K, N);
     if (!fuse) {
         int rc = bitlinear_quant_act(X, M, K, ln_gain, ln_bias, ln_eps, granularity,
                                      flags & BL_FLAG_SKIP_LN, codes, gamma, rowsum, nullptr,

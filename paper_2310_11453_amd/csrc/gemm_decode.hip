@@ -26,17 +26,16 @@ namespace bl {
 // with the arithmetic of the stand-alone quantiser: sums in fp64 about an element of the row,
 // the normalised value rounded once to fp32, then scale = 128 / gamma, rne, clamp - one fp32
 // operation per step.  The codes go to `lds_codes` (K bytes); returns gamma and sum_k codes.
-// Every thread of the workgroup must call it (it synchronises), K <= 16 * blockDim.
+// Every thread of the workgroup must call it (it synchronises), K <= 4 * NV * blockDim.
 // `after_loads` runs once the row's loads are issued: loads return in order, so whatever else
 // the caller wants in flight meanwhile has to queue behind the row, not ahead of it.
 struct TokenQuant {
     float gamma;
     int rowsum;
 };
-template <class F>
+template <int NV, class F>
 __device__ inline TokenQuant quant_token(const GemmArgs& a, uint32_t* lds_codes, double (*smd)[16],
                                          float (*smf)[16], int* smi, F&& after_loads) {
-    constexpr int NV = 4;
     const int T = blockDim.x, t = threadIdx.x, W = T / kWave, wave = t / kWave;
     const bool lead = (t & (kWave - 1)) == 0;
     const int K4 = (int)(a.K / 4);
@@ -174,12 +173,16 @@ __device__ inline TokenQuant quant_token(const GemmArgs& a, uint32_t* lds_codes,
 // <= T of them are used), MAXT = launch bound.  ONE_ROUND: the waves of the group cover K in a
 // single round, so a tile's partial sum goes straight to LDS and no per-tile registers are
 // kept - this is what lets a wave keep eight 1 KiB weight loads in flight.
-// FUSED (one round, M = 1): the codes come from quant_token, not from memory.
-template <int C, int T, int MAXT, bool ONE_ROUND, bool FUSED = false>
+// FUSED (one round, M = 1): the codes come from quant_token, not from memory.  1: a wave keeps
+// its slice of them in registers like codes read from memory; 2 (long K, many chunks per wave):
+// every MFMA takes its operand from LDS.
+template <int C, int T, int MAXT, bool ONE_ROUND, int FUSED = 0>
 __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) {
     static_assert(!FUSED || ONE_ROUND, "the fused quantiser covers K in one round");
+    constexpr bool kActLds = FUSED == 2;
+    constexpr int kRowBytes = FUSED == 2 ? 32768 : 16384;  // longest row the fused kernels take
     __shared__ __attribute__((aligned(16))) int red[(MAXT / kWave) * T * 256];  // [W][T][64][4]
-    __shared__ __attribute__((aligned(16))) uint32_t row_codes[FUSED ? 16384 / 4 : 1];
+    __shared__ __attribute__((aligned(16))) uint32_t row_codes[FUSED ? kRowBytes / 4 : 1];
     __shared__ double smd[FUSED ? 2 : 1][16];
     __shared__ float smf[FUSED ? 3 : 1][16];
     __shared__ int smi[16];
@@ -233,8 +236,9 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
         // activation operand: lane (m, g) holds codes[m][512*tk + 64*i + 16*g .. +15].  Rows
         // m >= M read row M-1 (their outputs are never stored); columns k >= K read the last 16
         // valid bytes (the packed bits there are zero, so they contribute nothing).
-        v4i act[C][8];
+        v4i act[kActLds ? 1 : C][8];
         auto load_act = [&](const int8_t* arow) {
+            if constexpr (kActLds) return;
 #pragma unroll
             for (int c = 0; c < C; ++c)
 #pragma unroll
@@ -281,7 +285,7 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
         if constexpr (FUSED) {
             // the row is normalised and quantised while the tiles are on their way; every column
             // of the MFMA then holds the one token
-            const TokenQuant tq = quant_token(a, row_codes, smd, smf, smi, [&]() {
+            const TokenQuant tq = quant_token<kActLds ? 16 : 4>(a, row_codes, smd, smf, smi, [&]() {
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int t = 0; t < kDepth; ++t) load_tile(t);
@@ -308,14 +312,26 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
 #pragma unroll
             for (int c = 0; c < C; ++c)
                 wv[c] = (C == 1 && ONE_ROUND) ? wt[t][c] : (wt[t][c] & livem[c]);
+            // kActLds: an offset of zero the compiler cannot see through, so that each tile reads
+            // its operands again instead of all C * 8 of them being kept in registers
+            int again = 0;
+            if constexpr (kActLds) asm volatile("" : "+v"(again));
 #pragma unroll
             for (int c = 0; c < C; ++c)
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     const int mask = (int)(0x01010101u << i);
                     const v4i plane = wv[c] & mask;
+                    v4i cols;
+                    if constexpr (kActLds) {
+                        int k = (int)(tk0 + c) * kChunkK + 64 * i + 16 * g;
+                        if (k > (int)a.K - 16) k = (int)a.K - 16;
+                        cols = *reinterpret_cast<const v4i*>(reinterpret_cast<const int8_t*>(row_codes) + k + again);
+                    } else {
+                        cols = act[c][i];
+                    }
                     // rows of the MFMA = weights (n), columns = tokens (m)
-                    acc[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(plane, act[c][i], acc[i], 0, 0, 0);
+                    acc[i] = __builtin_amdgcn_mfma_i32_16x16x64_i8(plane, cols, acc[i], 0, 0, 0);
                 }
             // fold the planes, scaled by 128 so that one shift-add per plane does it:
             //   128 * sum_k q b = sum_{i<7} acc_i * 2^(7-i) - acc_7      (|.| < 2^24 per chunk)
@@ -426,7 +442,7 @@ static int num_cus() {
     return n;
 }
 
-template <int C, int T, int MAXT, bool ONE_ROUND, bool FUSED = false>
+template <int C, int T, int MAXT, bool ONE_ROUND, int FUSED = 0>
 static void launch_one(const GemmArgs& a, int W, int tpb, hipStream_t s) {
     const int64_t TN = tiles_n(a.N);
     const unsigned splits = a.split_k ? (unsigned)((a.K + a.split_k - 1) / a.split_k) : 1u;
@@ -435,7 +451,7 @@ static void launch_one(const GemmArgs& a, int W, int tpb, hipStream_t s) {
 }
 
 // one round, up to 8 waves, exactly tpb = 1..8 tiles per group
-template <int C, bool FUSED>
+template <int C, int FUSED>
 static void launch_tiles(const GemmArgs& a, int W, int tpb, hipStream_t s) {
     switch (tpb) {
         case 1: launch_one<C, 1, 512, true, FUSED>(a, W, 1, s); break;
@@ -449,10 +465,16 @@ static void launch_tiles(const GemmArgs& a, int W, int tpb, hipStream_t s) {
     }
 }
 
-// One token and a K that one round of waves covers (quant_token holds 16 elements per thread,
-// and a wave covers two 512-chunks): the small-batch kernel can quantise the row itself.
-bool gemm_decode_fuses_quant(int64_t M, int64_t K) {
-    return M == 1 && tiles_k(K) <= 32 && !env_int("BITLINEAR_DECODE_NOFUSE", 0);
+// One token and a K that one round of waves covers: the small-batch kernel can quantise the row
+// itself.  Up to 32 chunks a wave holds one or two of them as register operands; up to 64 it
+// walks eight, with the operands read from LDS.  Every workgroup repeats the quantiser, so it
+// pays only while one round of workgroups covers N (8, 2 or 3 tiles a group at most, as the
+// launcher below chooses): K = N = 28672 measured 58 us fused against 44 us in two launches.
+bool gemm_decode_fuses_quant(int64_t M, int64_t K, int64_t N) {
+    const int64_t TK = tiles_k(K);
+    if (M != 1 || TK > 64 || env_int("BITLINEAR_DECODE_NOFUSE", 0)) return false;
+    const int64_t cap = TK <= 16 ? 8 : TK <= 32 ? 2 : 3;
+    return tiles_n(N) <= cap * num_cus();
 }
 
 // K > 16384 with a workspace: split K over workgroups so that every slice takes the one-round
@@ -483,7 +505,7 @@ hipError_t launch_gemm_decode(const GemmArgs& a_in, hipStream_t s) {
     int splits = 1;
     const bool fused = a.x_row != nullptr;  // the caller asked gemm_decode_fuses_quant
     const size_t need = gemm_split_ws_bytes(a.M, a.N, a.K);
-    if (need && a.split_ws && a.split_ws_bytes >= need && !env_int("BITLINEAR_DECODE_NOSPLIT", 0)) {
+    if (need && !fused && a.split_ws && a.split_ws_bytes >= need && !env_int("BITLINEAR_DECODE_NOSPLIT", 0)) {
         splits = (int)((TK + 15) / 16);
         const int64_t per = (TK + splits - 1) / splits;  // tiles per slice, evenly
         splits = (int)((TK + per - 1) / per);            // slices that actually hold tiles
@@ -505,26 +527,35 @@ hipError_t launch_gemm_decode(const GemmArgs& a_in, hipStream_t s) {
         // K < 4096: one K-chunk per wave, W = TK waves cover K in one round
         const int W = (int)TK;
         const int tpb = tiles_per_group(8);
-        if (fused) launch_tiles<1, true>(a, W, tpb, s);
-        else launch_tiles<1, false>(a, W, tpb, s);
+        if (fused) launch_tiles<1, 1>(a, W, tpb, s);
+        else launch_tiles<1, 0>(a, W, tpb, s);
     } else if (TK <= 16) {
         // 4096 <= K <= 8192: two chunks per wave (the fold of the bit planes, once per tile and
         // wave, is then shared by two chunks), W = ceil(TK/2) <= 8 waves, one round
         const int W = (int)((TK + 1) / 2);
         const int tpb = tiles_per_group(8);
-        if (fused) launch_tiles<2, true>(a, W, tpb, s);
-        else launch_tiles<2, false>(a, W, tpb, s);
+        if (fused) launch_tiles<2, 1>(a, W, tpb, s);
+        else launch_tiles<2, 0>(a, W, tpb, s);
     } else if (TK <= 32) {
         // K <= 16384: up to 16 waves of two chunks, one round; 128 registers per lane
         const int W = (int)((TK + 1) / 2);
         const int tpb = tiles_per_group(2);
         if (fused) {
-            if (tpb <= 1) launch_one<2, 1, 1024, true, true>(a, W, 1, s);
-            else launch_one<2, 2, 1024, true, true>(a, W, 2, s);
+            if (tpb <= 1) launch_one<2, 1, 1024, true, 1>(a, W, 1, s);
+            else launch_one<2, 2, 1024, true, 1>(a, W, 2, s);
         } else if (tpb <= 1) {
             launch_one<2, 1, 1024, true>(a, W, 1, s);
         } else {
             launch_one<2, 2, 1024, true>(a, W, 2, s);
+        }
+    } else if (fused) {
+        // one token, K <= 32768: eight chunks per wave (the last ones masked), up to 8 waves, one
+        // round, up to three tiles per group in registers (96 of them)
+        const int W = (int)((TK + 7) / 8);
+        switch (tiles_per_group(3)) {
+            case 1: launch_one<8, 1, 512, true, 2>(a, W, 1, s); break;
+            case 2: launch_one<8, 2, 512, true, 2>(a, W, 2, s); break;
+            default: launch_one<8, 3, 512, true, 2>(a, W, 3, s); break;
         }
     } else {
         // longer K: two chunks per wave and round, up to 16 waves, several rounds

@@ -72,7 +72,7 @@ struct GemmArgs {
     int64_t split_k;
     int32_t* split_ws;
     size_t split_ws_bytes;  // what the caller offers; too small or nullptr: no split
-    // One token (M = 1, K <= 16384) straight from fp32, small-batch kernel only: every workgroup
+    // One token (M = 1, K <= 32768) straight from fp32, small-batch kernel only: every workgroup
     // normalises and quantises the row for itself (Eq. 12, Eq. 4-5) while its first weight tiles
     // are on their way, instead of reading codes / gamma / rowsum, so the layer is one launch.
     // Workgroup 0 also writes the three to codes_out / gamma_out / rowsum_out.  nullptr: codes
@@ -86,7 +86,7 @@ struct GemmArgs {
     float* gamma_out;
     int32_t* rowsum_out;
 };
-bool gemm_decode_fuses_quant(int64_t M, int64_t K);
+bool gemm_decode_fuses_quant(int64_t M, int64_t K, int64_t N);
 size_t gemm_split_ws_bytes(int64_t M, int64_t N, int64_t K);
 int64_t prefill_split_tiles(int64_t M, int64_t N, int64_t K);
 void launch_splitk_reduce(const GemmArgs& a, int splits, hipStream_t s);

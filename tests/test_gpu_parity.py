@@ -231,10 +231,12 @@ def test_forward_end_to_end(bl, M, K, N, per_tensor):
 
 
 # One token: the small-batch GEMM kernel normalises and quantises the row itself (one launch).
-# K below one chunk, one chunk per wave, two per wave, the 16-wave kernels, a ragged last chunk;
+# K below one chunk, one chunk per wave, two per wave, the 16-wave kernels, a ragged last chunk,
+# eight chunks per wave with operands from LDS (K > 16384; one to three tiles per workgroup);
 # every variant of the quantiser the forward call offers.
 @pytest.mark.parametrize("K,N", [(96, 40), (2048, 6144), (3616, 257), (7168, 1000), (8192, 2048),
-                                 (12320, 520), (16384, 300)])
+                                 (12320, 520), (16384, 300), (16896, 200), (28672, 7168), (32768, 1100),
+                                 (20512, 12288)])
 @pytest.mark.parametrize("variant", ["plain", "affine", "skip_ln", "per_tensor"])
 def test_forward_single_token(bl, K, N, variant, monkeypatch):
     print(f"forward single token K={K} N={N} {variant}", flush=True)
