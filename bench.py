@@ -173,7 +173,8 @@ def main():
     # ---- decode leg: packed-weight streaming on 30B-shaped layers, M = 16 and M = 1 ----------
     decode = None
     if not args.no_decode:
-        decode = {"workload": "bitnet-30b layers, GEMM+dequant kernel per launch", "shapes": []}
+        decode = {"workload": "bitnet-30b layers, GEMM+dequant kernel per launch (prefill_30b: the same "
+                              "layers at M = 4096, this leg holds their weights)", "shapes": []}
         c3 = wl.CONFIGS[3]
         best = None
         for li, L3 in enumerate(c3.layers):
@@ -205,7 +206,26 @@ def main():
                 decode["shapes"].append(rec)
                 if Md <= 16 and (best is None or gbs > best["gbs"]):
                     best = rec
-            del copies, p3
+            del copies
+            # the same layer at the configuration's prefill batch (M = 4096): GEMM + dequant launch
+            # alone, after enough launches for the clock to settle
+            Mp = 4096
+            Xp = torch.from_numpy(wl.make_activation(Mp, L3.K, wl.seed_for(3, 20 + li))).to(dev)
+            cp, gp, rp, _ = bl.bitlinear_quant_act(Xp)
+            del Xp
+            Yp = torch.empty((Mp, L3.N), dtype=torch.float32, device=dev)
+
+            def run_p():
+                bl.bitlinear_matmul(cp, gp, rp, p3, L3.N, b3, out=Yp)
+
+            for _ in range(100):
+                run_p()
+            tp = event_ms(run_p, 30, torch)
+            tops_p = 2 * Mp * L3.K * L3.N / (tp * 1e-3) / 1e12
+            decode.setdefault("prefill_30b", []).append(
+                dict(layer=L3.name, K=L3.K, N=L3.N, M=Mp, us=tp * 1e3, tops=tops_p,
+                     frac_i8_mfma_peak=tops_p / I8_MFMA_PEAK_TOPS))
+            del cp, Yp, p3
 
         # Layer stream at the 1.3B shapes: the four projections of 24 layers, four distinct sets of
         # them (604 MB of packed weights, more than L2 + Infinity Cache), enqueued back to back as

@@ -339,7 +339,9 @@ def test_full_size_prefill_6p7b(bl, li):
 
 # M = 64: mid-batch kernel; 16: small-batch; 32 and 24: the 17-32 token kernel (layer 2, K = 28672,
 # goes on to the mid-batch one); 1: the quantiser inside the GEMM launch
-@pytest.mark.parametrize("li,M", [(0, 64), (2, 64), (1, 16), (1, 32), (0, 24), (2, 32), (1, 1), (0, 1)])
+# 4096: the configuration's prefill batch (large-tile kernel, seven rounds of tiles per workgroup)
+@pytest.mark.parametrize("li,M", [(0, 64), (2, 64), (1, 16), (1, 32), (0, 24), (2, 32), (1, 1), (0, 1),
+                                  (1, 4096)])
 def test_full_size_30b_batched_decode(bl, li, M):
     L = wl.CONFIGS[3].layers[li]
     print(f"full 30b {L} M={M}", flush=True)
