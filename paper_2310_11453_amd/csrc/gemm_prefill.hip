@@ -489,10 +489,14 @@ hipError_t launch_gemm_prefill(const GemmArgs& a_in, hipStream_t s) {
     if (e) pick = atoi(e);
     else if (a.M <= 64) pick = 0;
     else {
-        // 256x256 unless the 128-row tile needs fewer block-rounds of work on the 256 CUs
+        // 256x256 unless the 128-row tile needs fewer block-rounds of work on the CUs.  A 128-row
+        // tile expands every weight bit for half as many MFMAs: per unit of work it measured
+        // 1.12-1.17 times the 256-row tile's time (4096 x 7168 x 21504: 530 us in 11 rounds of
+        // 128-row tiles, 514 us in 6 rounds of 256-row tiles), hence the 8/7.
+        const int64_t cus = num_cus();
         auto cost = [&](int64_t bm, int64_t bn) {
             const int64_t blocks = ((a.M + bm - 1) / bm) * ((a.N + bn - 1) / bn);
-            return ((blocks + 255) / 256) * bm * bn;
+            return ((blocks + cus - 1) / cus) * bm * bn * (bm == 128 ? 8 : 7);
         };
         pick = cost(128, 256) < cost(256, 256) ? 1 : 2;
     }
