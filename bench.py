@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the BitLinear hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu] [--no-decode] [--no-train]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu] [--no-decode] [--no-train] [--no-prefill-30b]
 
 Workload at one GPU: the BitNet-6.7B-shaped prefill pair (4096->16384 and 16384->4096 at
 M = 2048 tokens, activations N(0,1) with 0.1 % outliers x20, weights N(0, 0.02^2)).
@@ -60,6 +60,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode streaming leg")
     ap.add_argument("--no-train", action="store_true", help="skip the training-step leg")
+    ap.add_argument("--no-prefill-30b", action="store_true",
+                    help="skip the 30B layers at M = 4096 (they run the 6.7B step's GEMM kernel at another "
+                         "size: a per-kernel profile of the step wants them out)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run plain device copies of 256 MiB (reference for the rocprofv3 "
@@ -209,6 +212,9 @@ def main():
             del copies
             # the same layer at the configuration's prefill batch (M = 4096): GEMM + dequant launch
             # alone, after enough launches for the clock to settle
+            if args.no_prefill_30b:
+                del p3
+                continue
             Mp = 4096
             Xp = torch.from_numpy(wl.make_activation(Mp, L3.K, wl.seed_for(3, 20 + li))).to(dev)
             cp, gp, rp, _ = bl.bitlinear_quant_act(Xp)
