@@ -316,7 +316,8 @@ __global__ __launch_bounds__(512, 2) void gemm_tn_bf16_ring(const uint16_t* __re
                                                             int64_t ld,
                                                             const float* __restrict__ scale_ptr,
                                                             float scale_mul, float* __restrict__ C,
-                                                            int grid_i, int grid_j) {
+                                                            int grid_i, int grid_j, int blk_i,
+                                                            int blk_j) {
     constexpr int BM = 256, BN = 256, WN = 4, THREADS = 512, WTM = 128, WTN = 64, MI = 4, NI = 2;
     constexpr int PA = BM * 4 / THREADS, PB = BN * 4 / THREADS, P = PA + PB;
     constexpr int A_BYTES = BM * 64, STAGE_BYTES = (BM + BN) * 64;
@@ -331,15 +332,27 @@ __global__ __launch_bounds__(512, 2) void gemm_tn_bf16_ring(const uint16_t* __re
     // groups of NS stages whose look-ahead stage st+NS-1 exists for every stage of the group
     const int main_groups = nst >= 2 * NS - 1 ? (nst - (2 * NS - 1)) / NS + 1 : 0;
 
-    // Workgroups are dealt round-robin to the 8 XCDs (one L2 each): an XCD gets one contiguous
-    // range of tiles, J fastest, so that the tiles it runs together share rows of A.
+    // Workgroups are dealt round-robin to the 8 XCDs (one L2 each).  An XCD gets grid_i / 8 whole
+    // rows of tiles, and the gridDim / 8 tiles it runs together form a blk_i x blk_j block of
+    // them: both operands are equally wide here, so what the XCD streams from memory per step of
+    // the contraction is blk_i + blk_j operand blocks, least for a square.  blk_i = 0 (the host
+    // found no such blocks for this grid): one contiguous range of tiles per XCD, J fastest.
     auto tile_origin = [&](int t, int64_t& i0, int64_t& j0) {
         int logical = t;
         const int G = (int)gridDim.x;
         if ((ntiles & 7) == 0 && (G & 7) == 0) {
             const int q = ((t % G) >> 3) + (t / G) * (G >> 3);
-            logical = (t & 7) * (ntiles >> 3) + q;
-            if (q >= (ntiles >> 3)) logical = -1;
+            const int per = ntiles >> 3;
+            if (q >= per) {
+                logical = -1;
+            } else if (blk_i > 0) {
+                const int cpx = G >> 3, b = q / cpx, within = q % cpx, bpr = grid_j / blk_j;
+                const int row = (t & 7) * (grid_i >> 3) + (b / bpr) * blk_i + within / blk_j;
+                const int col = (b % bpr) * blk_j + within % blk_j;
+                logical = row * grid_j + col;
+            } else {
+                logical = (t & 7) * per + q;
+            }
         }
         i0 = logical < 0 ? -1 : (int64_t)(logical / grid_j) * BM;
         j0 = logical < 0 ? -1 : (int64_t)(logical % grid_j) * BN;
@@ -498,8 +511,26 @@ static void launch_gemm_tn(const uint16_t* A, const uint16_t* B, int64_t I, int6
         int grid = bwd_num_cus();
         if (const char* e = getenv("BITLINEAR_BWD_GRID")) grid = atoi(e) > 0 ? atoi(e) : grid;  // tests
         if (grid > gi * gj) grid = (int)(gi * gj);
+        // the block of tiles an XCD runs together (see tile_origin): blk_i x blk_j = grid / 8 tiles
+        // out of its grid_i / 8 rows, as square as the divisors allow; 0 = no such tiling
+        int blk_i = 0, blk_j = 0;
+        const int64_t ntiles = gi * gj;
+        if (ntiles % 8 == 0 && grid % 8 == 0 && gi % 8 == 0 && (ntiles / 8) % (grid / 8) == 0 &&
+            !getenv("BITLINEAR_BWD_ROWMAJOR")) {
+            const int cpx = grid / 8;
+            const int64_t rx = gi / 8;
+            for (int br = 1; br <= cpx; ++br) {
+                if (cpx % br) continue;
+                const int bc = cpx / br;
+                if (br <= rx && bc <= gj && rx % br == 0 && gj % bc == 0 &&
+                    (blk_i == 0 || br + bc < blk_i + blk_j)) {
+                    blk_i = br;
+                    blk_j = bc;
+                }
+            }
+        }
         gemm_tn_bf16_ring<4><<<(unsigned)grid, 512, 0, s>>>(A, B, I, J, Rp, ld, scale_ptr, scale_mul,
-                                                             C, (int)gi, (int)gj);
+                                                             C, (int)gi, (int)gj, blk_i, blk_j);
     } else {
         const unsigned blocks = (unsigned)(((I + 255) / 256) * ((J + 127) / 128));
         gemm_tn_bf16<256, 128><<<blocks, 256, 0, s>>>(A, B, I, J, Rp, ld, scale_ptr, scale_mul, C);
