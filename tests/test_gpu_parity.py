@@ -275,6 +275,44 @@ def test_forward_single_token(bl, K, N, variant, monkeypatch):
     assert np.abs(y2 - y).max() <= 1e-3 * rms
 
 
+# Two to four tokens: the batch sizes next to the one-launch single-token path (they take the
+# quantiser and the small-batch GEMM as two launches), in every variant of the quantiser.
+@pytest.mark.parametrize("M,K,N", [(4, 2048, 6144), (2, 2048, 2048), (3, 8192, 2048), (4, 8192, 520),
+                                   (2, 7168, 1000), (3, 7168, 21504), (4, 7168, 300), (2, 12320, 264),
+                                   (2, 16384, 1000), (4, 512, 40), (3, 3616, 257)])
+@pytest.mark.parametrize("variant", ["plain", "affine", "skip_ln", "per_tensor"])
+def test_forward_few_tokens(bl, M, K, N, variant):
+    print(f"forward few tokens M={M} K={K} N={N} {variant}", flush=True)
+    sd = wl.seed_for(0, 9 * K + N + M)
+    W = wl.make_weight(N, K, 0.02, sd)
+    X = wl.make_activation(M, K, sd)
+    X[M - 1] *= 3.0  # rows of different scale: a mixed-up gamma or row sum would show
+    rng = np.random.default_rng(sd)
+    gain = (1.0 + 0.1 * rng.standard_normal(K)).astype(np.float32) if variant == "affine" else None
+    bias = (0.05 * rng.standard_normal(K)).astype(np.float32) if variant == "affine" else None
+    pt = variant == "per_tensor"
+    kw = dict(per_tensor=pt, flags=bl.FLAG_SKIP_LN if variant == "skip_ln" else 0,
+              ln_gain=None if gain is None else dev(gain), ln_bias=None if bias is None else dev(bias))
+    r = oracle.forward(X, W, per_tensor=pt, skip_ln=variant == "skip_ln", gain=gain, bias=bias)
+    packed, alpha, beta = bl.bitlinear_pack_weights(dev(W))
+    y = host(bl.bitlinear_forward(dev(X), packed, N, beta, **kw))
+    rms = np.sqrt(np.mean(r["y"].astype(np.float64) ** 2))
+    assert np.abs(y - r["y"]).max() <= 1e-3 * rms
+    kw_acc = dict(kw, flags=kw["flags"] | bl.FLAG_OUT_ACC_I32)
+    acc = host(bl.bitlinear_forward(dev(X), packed, N, beta, **kw_acc))
+    assert (acc != r["acc"]).mean() <= 1e-3  # differs only where an x^ sits on a rounding tie
+    # the workspace holds what the stand-alone quantiser would have put there
+    ws = torch.zeros(bl.workspace_bytes(bl.OP_FORWARD, M, N, K, pt), dtype=torch.uint8, device="cuda")
+    bl.bitlinear_forward(dev(X), packed, N, beta, workspace=ws, **kw)
+    codes, gamma, rowsum, _ = bl.bitlinear_quant_act(dev(X), per_tensor=pt, flags=kw["flags"],
+                                                     ln_gain=kw["ln_gain"], ln_bias=kw["ln_bias"])
+    held = host(ws)
+    assert np.array_equal(held[:M * K].view(np.int8).reshape(M, K), host(codes))
+    # here the codes are the stand-alone quantiser's own, so the layer output follows from them
+    y_ref = oracle.dequant(oracle.matmul_i32(host(codes), r["sign"]), host(gamma), host(beta), pt)
+    assert np.array_equal(y, y_ref)
+
+
 def test_empty_batch_and_errors(bl):
     W = dev(wl.make_weight(32, 64, 0.02, 1))
     packed, alpha, beta = bl.bitlinear_pack_weights(W)
