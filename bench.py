@@ -246,7 +246,7 @@ def main():
         n_sets = 4 * 24
         sets = [[(L2, p2.clone(), b2) for (L2, p2, b2) in protos] for _ in range(n_sets)]
         stream = []
-        for Md in (1, 16):
+        for Md in (1, 4, 16):
             acts = {}
             for K2 in sorted({L2.K for (L2, _, _) in protos}):
                 X2 = torch.from_numpy(wl.make_activation(Md, K2, wl.seed_for(1, K2 % 97))).to(dev)
@@ -294,7 +294,7 @@ def main():
         # non-linearity between them are left out: only their place in the chain matters here).
         # Four stacks of distinct weights, one HIP graph each, replayed in turn.
         block = []
-        for Md in (1, 16):
+        for Md in (1, 4, 16):
             h0 = torch.from_numpy(wl.make_activation(Md, 2048, wl.seed_for(1, 50))).to(dev)
             bufs = {L2.name: torch.empty((Md, L2.N), dtype=torch.float32, device=dev)
                     for (L2, _, _) in protos}
