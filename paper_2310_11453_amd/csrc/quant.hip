@@ -207,7 +207,14 @@ __global__ __launch_bounds__((WPR < 4 ? 4 : WPR) * kWave, 4) void ln_quant_rows(
         }
         if constexpr (MODE == kStats) {
             // non-negative floats order like their bit patterns: integer max is exact
-            if (t == 0 && live) atomicMax(a.gmax_bits + grp, __float_as_uint(amax));
+            // The running maximum only grows, so a row that does not exceed what is there already
+            // has nothing to add: the look first keeps thousands of rows from queueing on one
+            // address (a stale, lower value only costs the atomic it would have saved).
+            if (t == 0 && live) {
+                const uint32_t bits = __float_as_uint(amax);
+                if (bits > __hip_atomic_load(a.gmax_bits + grp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+                    atomicMax(a.gmax_bits + grp, bits);
+            }
             return;
         }
         gamma = fmaxf(amax, 1e-5f);
