@@ -40,7 +40,7 @@ __global__ __launch_bounds__((WPR < 4 ? 4 : WPR) * kWave, 4) void ln_quant_rows(
     const int t = wr * kWave + (threadIdx.x & (kWave - 1));
     int64_t row = (int64_t)blockIdx.x * RPW + rw;
     const bool live = row < a.M;
-    if constexpr (WPR == 1) {
+    if constexpr (WPR == 1 && MODE != kStats) {
         if (!live) return;  // no barriers on this path
     } else {
         if (!live) row = a.M - 1;
@@ -207,13 +207,27 @@ __global__ __launch_bounds__((WPR < 4 ? 4 : WPR) * kWave, 4) void ln_quant_rows(
         }
         if constexpr (MODE == kStats) {
             // non-negative floats order like their bit patterns: integer max is exact
-            // The running maximum only grows, so a row that does not exceed what is there already
+            // The running maximum only grows, so whoever does not exceed what is there already
             // has nothing to add: the look first keeps thousands of rows from queueing on one
-            // address (a stale, lower value only costs the atomic it would have saved).
-            if (t == 0 && live) {
-                const uint32_t bits = __float_as_uint(amax);
-                if (bits > __hip_atomic_load(a.gmax_bits + grp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
-                    atomicMax(a.gmax_bits + grp, bits);
+            // address (a stale, lower value only costs the atomic it would have saved).  With one
+            // K-group the rows of a workgroup share a maximum and send one candidate.
+            __shared__ float wg_amax[NW];
+            auto offer = [&](float v, int g) {
+                const uint32_t bits = __float_as_uint(v);
+                if (bits > __hip_atomic_load(a.gmax_bits + g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+                    atomicMax(a.gmax_bits + g, bits);
+            };
+            if (RPW > 1 && a.groups <= 1) {  // uniform
+                if (t == 0) wg_amax[rw] = live ? amax : 0.f;
+                __syncthreads();
+                if (threadIdx.x == 0) {
+                    float m = wg_amax[0];
+#pragma unroll
+                    for (int i = 1; i < RPW; ++i) m = fmaxf(m, wg_amax[i]);
+                    offer(m, 0);
+                }
+            } else if (t == 0 && live) {
+                offer(amax, grp);
             }
             return;
         }
