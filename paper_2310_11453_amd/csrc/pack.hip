@@ -22,12 +22,23 @@ __global__ __launch_bounds__(256) void weight_partial_sums(const float4* __restr
     double s = 0.0, a = 0.0;
     const int64_t stride = (int64_t)gridDim.x * 256;
     const bool strided = ld4 != cols4;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count4; i += stride) {
-        const float4 w = W4[strided ? (i / cols4) * ld4 + i % cols4 : i];
+    auto at = [&](int64_t i) { return W4[strided ? (i / cols4) * ld4 + i % cols4 : i]; };
+    auto add = [&](const float4& w) {
         const double x = (double)w.x, y = (double)w.y, z = (double)w.z, u = (double)w.w;
         s += (x + y) + (z + u);
         a += (fabs(x - centre) + fabs(y - centre)) + (fabs(z - centre) + fabs(u - centre));
+    };
+    // four loads in flight per thread (one at a time, the pass is bound by their latency); the
+    // order of the sums stays that of the plain loop
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 3 * stride < count4; i += 4 * stride) {
+        const float4 w0 = at(i), w1 = at(i + stride), w2 = at(i + 2 * stride), w3 = at(i + 3 * stride);
+        add(w0);
+        add(w1);
+        add(w2);
+        add(w3);
     }
+    for (; i < count4; i += stride) add(at(i));
     s = block_sum<4>(s, sm);
     a = block_sum<4>(a, sm);
     if (threadIdx.x == 0) {
