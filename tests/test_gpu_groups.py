@@ -100,9 +100,10 @@ def _check_forward(bl, M, K, N, gn, gk, per_tensor, seed):
 
 
 @pytest.mark.parametrize("gn,gk", GROUPS)
-@pytest.mark.parametrize("M", [8, 100])
+@pytest.mark.parametrize("M", [8, 24, 48, 100])
 def test_grouped_forward(bl, M, gn, gk):
-    """Small batch (streaming kernel) and larger batch (MFMA-tile kernel), per-token gamma."""
+    """One batch size for each of the four GEMM kernels (up to 16, 17-32, 33-64 tokens, large
+    tiles), per-token gamma."""
     K, N = 2048, 512
     print(f"grouped forward M={M} K={K} N={N} gn={gn} gk={gk}", flush=True)
     _check_forward(bl, M, K, N, gn, gk, False, 300 + gn * 10 + gk)
@@ -119,6 +120,8 @@ def test_grouped_forward_ragged(bl):
     print("grouped forward ragged", flush=True)
     _check_forward(bl, 70, 384, 240, 3, 4, False, 500)
     _check_forward(bl, 5, 384, 240, 3, 4, False, 501)
+    _check_forward(bl, 19, 384, 240, 3, 4, False, 502)
+    _check_forward(bl, 33, 384, 240, 3, 4, False, 503)
 
 
 def test_groups_of_one_match_the_plain_entry_points(bl):

@@ -65,7 +65,8 @@ def test_weight_rowsums(bl, N, K):
 
 
 @pytest.mark.parametrize("M,K,N", [(1, 256, 512), (8, 2048, 512), (16, 1056, 200), (40, 512, 384),
-                                   (100, 2048, 512), (300, 4096, 1024), (70, 96, 240)])
+                                   (100, 2048, 512), (300, 4096, 1024), (70, 96, 240),
+                                   (24, 2048, 512), (32, 1056, 201), (17, 8704, 384)])
 def test_forward_nonneg(bl, M, K, N):
     print(f"forward nonneg M={M} K={K} N={N}", flush=True)
     X = wl.make_activation(M, K, seed=wl.seed_for(5, M + K + N), outlier_p=0.005, outlier_mul=8.0)
