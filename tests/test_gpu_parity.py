@@ -213,6 +213,7 @@ def test_matmul_17_to_32_tokens(bl, M, K, N):
 
 @pytest.mark.parametrize("M,K,N,per_tensor", [(8, 256, 512, False), (8, 256, 512, True),
                                               (16, 2048, 2048, False), (130, 512, 272, True),
+                                              (24, 1056, 300, True), (48, 1056, 300, True),
                                               (40, 1024, 1000, False)])
 def test_forward_end_to_end(bl, M, K, N, per_tensor):
     print(f"forward M={M} K={K} N={N} per_tensor={per_tensor}", flush=True)
