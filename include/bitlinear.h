@@ -18,7 +18,11 @@
  *     hipStream_t passed as void*; NULL = the default stream) and the call
  *     returns at once.
  *   - W is fp32 [N,K] row-major (K = fan-in, contiguous), X is fp32 [M,K],
- *     Y is fp32 [M,N].  K must be a multiple of 32.
+ *     Y is fp32 [M,N].  K must be a multiple of 32.  M, N, K <= 2^30 and
+ *     N * K <= 2^40 (else BL_ERR_SHAPE); the matmul and forward calls (plain,
+ *     grouped, non-negative) take K <= 65536 (per K-group for the grouped
+ *     calls), else BL_ERR_UNSUPPORTED: their int32 partial sums carry a factor
+ *     of up to 2^14 per element of K.
  *   - Return value: BL_OK or a negative bl_status.  Argument errors are found
  *     on the host before any launch, in the order shape, flags, pointers,
  *     workspace.  M == 0 is a successful no-op (pointers are not looked at).
@@ -68,7 +72,9 @@ typedef enum { BL_OP_PACK = 0, BL_OP_QUANT = 1, BL_OP_FORWARD = 2, BL_OP_BACKWAR
  * N padded to 16 and K to 512). */
 size_t bitlinear_packed_bytes(int64_t N, int64_t K, unsigned flags);
 
-/* host: scratch bytes the given operation needs (never 0 for valid shapes). */
+/* host: scratch bytes the given operation needs; 0 for an invalid argument.  BL_OP_MATMUL
+ * is the one operation whose need may be 0 for a valid shape (its workspace is optional and
+ * only some shapes have a use for it). */
 size_t bitlinear_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int granularity,
                                  unsigned flags);
 
@@ -106,8 +112,9 @@ int bitlinear_quant_act(const float* X, int64_t M, int64_t K, const float* ln_ga
  *   rowsum  in  int32 [M] as produced by bitlinear_quant_act (required)
  *   Y       out fp32 [M,N] (int32 accumulators with BL_FLAG_OUT_ACC_I32)
  *   workspace   optional (may be NULL): with bitlinear_workspace_bytes(BL_OP_MATMUL, ...) bytes
- *               the library may split a long K (> 16384 at M <= 16) over more workgroups and
- *               fold the slices in a second kernel; the result is the same bit for bit */
+ *               the library may split K over more workgroups (M <= 16: K > 16384; 16 < M <= 64:
+ *               whenever N alone supplies too few workgroups for the chip) and fold the int32
+ *               slices afterwards; the result is the same bit for bit */
 int bitlinear_matmul(const int8_t* codes, const float* gamma, const int32_t* rowsum, int64_t M,
                      int64_t K, const void* packed, int64_t N, const float* beta, int granularity,
                      unsigned flags, float* Y, void* workspace, size_t workspace_bytes,
@@ -120,12 +127,21 @@ int bitlinear_matmul(const int8_t* codes, const float* gamma, const int32_t* row
  * arithmetic but its own summation order, so a code can differ from
  * bitlinear_quant_act's where x^ * 128 / gamma sits on a rounding tie.  The
  * workspace is required in every case
- * (bitlinear_workspace_bytes(BL_OP_FORWARD, ...)); its contents afterwards are
- * unspecified. */
+ * (bitlinear_workspace_bytes(BL_OP_FORWARD, ...)).  Afterwards it holds the codes,
+ * gamma and row sums the matmul step read and, for M = 1, the normalised row x^ the
+ * codes were rounded from (bitlinear_forward_workspace_layout says where); the rest
+ * is unspecified. */
 int bitlinear_forward(const float* X, int64_t M, int64_t K, const void* packed, int64_t N,
                       const float* beta, const float* ln_gain, const float* ln_bias, float ln_eps,
                       int granularity, unsigned flags, float* Y, void* workspace,
                       size_t workspace_bytes, void* stream);
+
+/* host: where bitlinear_forward leaves its intermediates in the workspace, for inspection.
+ * offsets[0..3] = byte offsets of codes (int8 [M,K]), gamma (fp32 [M] or [1]), rowsum
+ * (int32 [M]) and x^ (fp32 [K], M = 1 only; (size_t)-1 otherwise).  BL_ERR_SHAPE /
+ * BL_ERR_UNSUPPORTED / BL_ERR_NULL as for bitlinear_forward. */
+int bitlinear_forward_workspace_layout(int64_t M, int64_t N, int64_t K, int granularity,
+                                       size_t offsets[4]);
 
 /* ---- Group Quantization and Normalization (Eq. 13-15) -------------------------------
  * The paper splits weights and activations into G groups "along the partition dimension"
@@ -232,6 +248,26 @@ int bitlinear_layernorm_backward(const float* dXhat, const float* X, int64_t M, 
                                  int groups_k, const float* ln_gain, float ln_eps, float* dX,
                                  float* dgain, float* dbias, void* workspace,
                                  size_t workspace_bytes, void* stream);
+
+/* host: launch-time switches for tests and benchmarks; results never depend on them.
+ * spec = "name=value,name=value" (integers); every switch not named returns to 0 = the
+ * library decides; NULL or "" resets all.  Process-wide, not thread-safe, takes effect on the
+ * next call.  Unless this function has been called, the environment variable
+ * BITLINEAR_TUNING (same syntax) is read once, at the first call that launches.
+ *   decode_nofuse=1     bitlinear_forward at M = 1: quantiser and GEMM as two launches
+ *   decode_nosplit=1    M <= 16: never split K over workgroups
+ *   decode_tiles=t      M <= 16: weight tiles per workgroup
+ *   mid_nosplit=1       16 < M <= 64: never split K over workgroups
+ *   mid_split_tiles=c   16 < M <= 64: 512-element chunks of K per slice
+ *   mid_only=1          16 < M <= 32: skip the register-streaming kernel
+ *   mid_kernel=1        32 < M <= 64: the LDS-tiled kernel with the K split inside the workgroup
+ *   prefill_tile=1|2    M > 64: 128 x 256 or 256 x 256 output tiles
+ *   prefill_grid=g      M > 64: workgroups of the persistent kernel
+ *   quant_wpr=w         quantiser: waves per row (1, 2, 4, 8)
+ *   bwd_ring=1|2        backward GEMMs: the ring kernel / the small kernel
+ *   bwd_grid=g, bwd_rowmajor=1   backward ring kernel: workgroups, plain tile order
+ * Returns BL_OK, or BL_ERR_UNSUPPORTED (unknown name or bad syntax; nothing changes). */
+int bitlinear_set_tuning(const char* spec);
 
 /* host: static description of a status code. */
 const char* bitlinear_status_string(int status);

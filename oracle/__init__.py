@@ -270,12 +270,14 @@ def binarize_grouped(W, alpha):
 
 
 def forward_grouped(X, W, groups_n: int = 1, groups_k: int = 1, eps=1e-5, per_tensor=False,
-                    skip_ln=False, beta_centered=False, gain=None, bias=None):
+                    skip_ln=False, beta_centered=False, gain=None, bias=None, xhat=None):
     """BitLinear forward with the group parameters of Eq. 13-15.  The weights are split into
     groups_n row groups and groups_k column groups (alpha, beta per block); the activations into
     groups_k slices of each token (group LayerNorm, Eq. 15; gamma per slice, Eq. 14).  Each
     K-slice is contracted on its own and dequantised with its own beta_g * gamma_g / 128
-    (fp32 product as in Eq. 11); the slices are added in fp64."""
+    (fp32 product as in Eq. 11); the slices are added in fp64.  `xhat`, if given, replaces the
+    group LayerNorm's output (a test passes the normalised input another implementation produced,
+    to compare everything after it "given the same normalised input")."""
     X = _f32(X)
     W = _f32(W)
     M, K = X.shape
@@ -283,7 +285,9 @@ def forward_grouped(X, W, groups_n: int = 1, groups_k: int = 1, eps=1e-5, per_te
     Ng, Kg = N // groups_n, K // groups_k
     alpha, beta = weight_stats_grouped(W, groups_n, groups_k, beta_centered)
     sign = binarize_grouped(W, alpha)
-    xhat = X if skip_ln else layernorm(X, eps, gain, bias, groups=groups_k)
+    if xhat is None:
+        xhat = X if skip_ln else layernorm(X, eps, gain, bias, groups=groups_k)
+    xhat = _f32(xhat)
     gamma = absmax(xhat, per_tensor, groups=groups_k)       # [M*groups_k] or [groups_k]
     codes = quantize(xhat, gamma, per_tensor, groups=groups_k)
     gam = gamma.reshape(-1, groups_k)                       # [M, groups_k] or [1, groups_k]

@@ -298,17 +298,6 @@ void oracle_dequant(const int32_t *acc, int64_t M, int64_t N, const float *gamma
         }
 }
 
-/* accumulate variant for K-groups: Y += acc_g * (beta * gamma_g / 128) */
-void oracle_dequant_accumulate(const int32_t *acc, int64_t M, int64_t N, const float *gamma,
-                               int64_t gamma_stride, float beta, double *Ysum)
-{
-    for (int64_t m = 0; m < M; ++m)
-        for (int64_t n = 0; n < N; ++n) {
-            const float s = (beta * gamma[m * gamma_stride]) / QB;
-            Ysum[m * N + n] += (double)((float)acc[m * N + n] * s);
-        }
-}
-
 /* ---- Section 2.2, straight-through estimator ----------------------------- */
 /* bf16 round-to-nearest-even of an fp32 value, returned as fp32. */
 static float bf16_rne(float v)

@@ -28,7 +28,7 @@ EXPORTS = (
     "bitlinear_pack_weights_grouped", "bitlinear_packed_to_canonical_grouped",
     "bitlinear_quant_act_grouped", "bitlinear_forward_grouped", "bitlinear_layernorm_backward",
     "bitlinear_weight_rowsums", "bitlinear_quant_act_nonneg", "bitlinear_matmul_nonneg",
-    "bitlinear_forward_nonneg",
+    "bitlinear_forward_nonneg", "bitlinear_forward_workspace_layout", "bitlinear_set_tuning",
 )
 
 _lib = None
@@ -90,6 +90,10 @@ def load_library() -> ctypes.CDLL:
     lib.bitlinear_forward_nonneg.restype = ci
     lib.bitlinear_forward_nonneg.argtypes = [vp, i64, i64, vp, i64, vp, vp, vp, vp, cf, ci, u32, vp,
                                              vp, sz, vp]
+    lib.bitlinear_forward_workspace_layout.restype = ci
+    lib.bitlinear_forward_workspace_layout.argtypes = [i64, i64, i64, ci, ctypes.POINTER(sz)]
+    lib.bitlinear_set_tuning.restype = ci
+    lib.bitlinear_set_tuning.argtypes = [ctypes.c_char_p]
     lib.bitlinear_status_string.restype = ctypes.c_char_p
     lib.bitlinear_status_string.argtypes = [ci]
     _lib = lib
@@ -131,6 +135,21 @@ def packed_bytes(N: int, K: int, flags: int = 0) -> int:
 
 def workspace_bytes(op: int, M: int, N: int, K: int, per_tensor: bool = False, flags: int = 0) -> int:
     return int(load_library().bitlinear_workspace_bytes(op, M, N, K, _gran(per_tensor), flags))
+
+
+def set_tuning(spec: str | None = None) -> None:
+    """Launch-time switches for tests and benchmarks ("name=value,..."; None resets)."""
+    _check(load_library().bitlinear_set_tuning(None if spec is None else spec.encode()),
+           "bitlinear_set_tuning")
+
+
+def forward_workspace_layout(M: int, N: int, K: int, per_tensor: bool = False) -> dict:
+    """Byte offsets of what bitlinear_forward leaves in its workspace (xhat: M = 1 only)."""
+    off = (ctypes.c_size_t * 4)()
+    _check(load_library().bitlinear_forward_workspace_layout(M, N, K, _gran(per_tensor), off),
+           "bitlinear_forward_workspace_layout")
+    return dict(codes=off[0], gamma=off[1], rowsum=off[2],
+                xhat=None if off[3] == ctypes.c_size_t(-1).value else off[3])
 
 
 def _workspace(nbytes: int, device) -> torch.Tensor:

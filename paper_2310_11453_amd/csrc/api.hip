@@ -1,5 +1,8 @@
 // C ABI of the BitLinear library: argument checks on the host, then launches.
 // Declarations and argument semantics: include/bitlinear.h.
+#include <stdlib.h>
+#include <string.h>
+
 #include "../../include/bitlinear.h"
 #include "common.h"
 #include "kernels.h"
@@ -8,7 +11,49 @@ using namespace bl;
 
 namespace {
 
+// ---- launch-time switches (bitlinear_set_tuning) ----------------------------------------
+struct TuningField {
+    const char* name;
+    int Tuning::*field;
+};
+const TuningField kTuningFields[] = {
+    {"decode_nofuse", &Tuning::decode_nofuse},   {"decode_nosplit", &Tuning::decode_nosplit},
+    {"decode_tiles", &Tuning::decode_tiles},     {"mid_nosplit", &Tuning::mid_nosplit},
+    {"mid_split_tiles", &Tuning::mid_split_tiles}, {"mid_only", &Tuning::mid_only},
+    {"prefill_tile", &Tuning::prefill_tile},     {"prefill_grid", &Tuning::prefill_grid},
+    {"quant_wpr", &Tuning::quant_wpr},           {"bwd_ring", &Tuning::bwd_ring},
+    {"bwd_grid", &Tuning::bwd_grid},             {"bwd_rowmajor", &Tuning::bwd_rowmajor},
+    {"mid_kernel", &Tuning::mid_kernel},
+};
+Tuning g_tuning{};
+bool g_tuning_init = false;
+
+// "name=value,name=value": all fields not named become 0.  false: unknown name or bad syntax
+// (then nothing changes).
+bool parse_tuning(const char* spec, Tuning& out) {
+    Tuning t{};
+    const char* p = spec ? spec : "";
+    while (*p) {
+        const char* eq = strchr(p, '=');
+        if (!eq) return false;
+        const TuningField* f = nullptr;
+        for (const TuningField& c : kTuningFields)
+            if (strlen(c.name) == (size_t)(eq - p) && strncmp(c.name, p, eq - p) == 0) f = &c;
+        if (!f) return false;
+        char* end = nullptr;
+        const long v = strtol(eq + 1, &end, 10);
+        if (end == eq + 1 || (*end && *end != ',')) return false;
+        t.*(f->field) = (int)v;
+        p = *end ? end + 1 : end;
+    }
+    out = t;
+    return true;
+}
+
 constexpr int64_t kMaxDim = (int64_t)1 << 30;
+// The GEMM kernels keep partial sums scaled by up to 2^14 per element of K in int32 and byte
+// offsets into a block of rows in 32 bits: both hold up to this K.
+constexpr int64_t kMaxGemmK = 65536;
 constexpr unsigned kKnownFlags = BL_FLAG_SKIP_LN | BL_FLAG_OUT_ACC_I32 | BL_FLAG_BETA_CENTERED;
 
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -36,7 +81,7 @@ QuantWs quant_ws(int64_t M, int granularity) {
     return w;
 }
 struct ForwardWs {
-    size_t codes, gamma, rowsum, quant, split, split_bytes, total;
+    size_t codes, gamma, rowsum, quant, split, split_bytes, xhat, total;
 };
 ForwardWs forward_ws(int64_t M, int64_t N, int64_t K, int granularity) {
     ForwardWs w{};
@@ -52,6 +97,8 @@ ForwardWs forward_ws(int64_t M, int64_t N, int64_t K, int granularity) {
     w.split = off;  // partial sums of a K split (small M, long K), else empty
     w.split_bytes = gemm_split_ws_bytes(M, N, K);
     off += align256(w.split_bytes);
+    w.xhat = off;  // one token: the normalised row, fp32 [K] (what the codes were rounded from)
+    off += M == 1 ? align256((size_t)K * 4) : 0;
     w.total = off;
     return w;
 }
@@ -123,7 +170,23 @@ void plain_fields(GemmArgs& a) {
 
 }  // namespace
 
+namespace bl {
+// The environment variable is looked at once, at the first launch decision of the process.
+const Tuning& tuning() {
+    if (!g_tuning_init) {
+        g_tuning_init = true;
+        parse_tuning(getenv("BITLINEAR_TUNING"), g_tuning);
+    }
+    return g_tuning;
+}
+}  // namespace bl
+
 extern "C" {
+
+int bitlinear_set_tuning(const char* spec) {
+    g_tuning_init = true;
+    return parse_tuning(spec, g_tuning) ? BL_OK : BL_ERR_UNSUPPORTED;
+}
 
 size_t bitlinear_packed_bytes(int64_t N, int64_t K, unsigned flags) {
     if (!shape_ok(N, K) || (flags & ~kKnownFlags)) return 0;
@@ -210,6 +273,7 @@ int bitlinear_matmul(const int8_t* codes, const float* gamma, const int32_t* row
                      void* stream) {
     if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return BL_ERR_SHAPE;
     if (!gran_ok(granularity) || (flags & ~BL_FLAG_OUT_ACC_I32)) return BL_ERR_UNSUPPORTED;
+    if (K > kMaxGemmK) return BL_ERR_UNSUPPORTED;
     if (M == 0) return BL_OK;
     if (!codes || !gamma || !rowsum || !packed || !beta || !Y) return BL_ERR_NULL;
     GemmArgs a{};
@@ -232,6 +296,7 @@ int bitlinear_forward(const float* X, int64_t M, int64_t K, const void* packed, 
     if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return BL_ERR_SHAPE;
     if (!gran_ok(granularity) || (flags & ~(BL_FLAG_SKIP_LN | BL_FLAG_OUT_ACC_I32)))
         return BL_ERR_UNSUPPORTED;
+    if (K > kMaxGemmK) return BL_ERR_UNSUPPORTED;
     if (M == 0) return BL_OK;
     if (!X || !packed || !beta || !Y) return BL_ERR_NULL;
     const ForwardWs ws = forward_ws(M, N, K, granularity);
@@ -245,7 +310,8 @@ int bitlinear_forward(const float* X, int64_t M, int64_t K, const void* packed, 
     const bool fuse = gemm_decode_fuses_quant(M, K, N);
     if (!fuse) {
         int rc = bitlinear_quant_act(X, M, K, ln_gain, ln_bias, ln_eps, granularity,
-                                     flags & BL_FLAG_SKIP_LN, codes, gamma, rowsum, nullptr,
+                                     flags & BL_FLAG_SKIP_LN, codes, gamma, rowsum,
+                                     M == 1 ? (float*)(base + ws.xhat) : nullptr,
                                      base + ws.quant, ws.split - ws.quant, stream);
         if (rc != BL_OK) return rc;
     }
@@ -254,6 +320,7 @@ int bitlinear_forward(const float* X, int64_t M, int64_t K, const void* packed, 
         a.x_row = X; a.ln_gain = ln_gain; a.ln_bias = ln_bias; a.ln_eps = ln_eps;
         a.skip_ln = (flags & BL_FLAG_SKIP_LN) != 0;
         a.codes_out = codes; a.gamma_out = gamma; a.rowsum_out = rowsum;
+        a.xhat_out = (float*)(base + ws.xhat);
     }
     a.codes = codes; a.gamma = gamma; a.rowsum = rowsum; a.M = M; a.K = K; a.N = N;
     a.packed = (const uint32_t*)packed; a.beta = beta;
@@ -265,6 +332,19 @@ int bitlinear_forward(const float* X, int64_t M, int64_t K, const void* packed, 
     a.split_ws_bytes = ws.split_bytes;
     if (M <= 16) return check_hip(launch_gemm_decode(a, (hipStream_t)stream));
     return check_hip(launch_gemm_prefill(a, (hipStream_t)stream));
+}
+
+int bitlinear_forward_workspace_layout(int64_t M, int64_t N, int64_t K, int granularity,
+                                       size_t offsets[4]) {
+    if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return BL_ERR_SHAPE;
+    if (!gran_ok(granularity) || K > kMaxGemmK) return BL_ERR_UNSUPPORTED;
+    if (!offsets) return BL_ERR_NULL;
+    const ForwardWs ws = forward_ws(M, N, K, granularity);
+    offsets[0] = ws.codes;
+    offsets[1] = ws.gamma;
+    offsets[2] = ws.rowsum;
+    offsets[3] = M == 1 ? ws.xhat : (size_t)-1;
+    return BL_OK;
 }
 
 // ---- Group Quantization and Normalization (Eq. 13-15) ----------------------------------
@@ -368,6 +448,7 @@ int bitlinear_forward_grouped(const float* X, int64_t M, int64_t K, const void* 
     if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return BL_ERR_SHAPE;
     if (int st = groups_status(N, K, groups_n, groups_k)) return st;
     if (!gran_ok(granularity) || (flags & ~BL_FLAG_SKIP_LN)) return BL_ERR_UNSUPPORTED;
+    if (K / groups_k > kMaxGemmK) return BL_ERR_UNSUPPORTED;
     if (M == 0) return BL_OK;
     if (!X || !packed || !beta || !Y) return BL_ERR_NULL;
     const ForwardWs ws = forward_ws_grouped(M, K, groups_k, granularity);
@@ -458,7 +539,7 @@ int bitlinear_matmul_nonneg(const int8_t* codes, const float* gamma, const float
                             int64_t N, const float* beta, const int32_t* wsum, int granularity,
                             unsigned flags, float* Y, void* stream) {
     if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return BL_ERR_SHAPE;
-    if (granularity != BL_GAMMA_PER_TOKEN || flags) return BL_ERR_UNSUPPORTED;
+    if (granularity != BL_GAMMA_PER_TOKEN || flags || K > kMaxGemmK) return BL_ERR_UNSUPPORTED;
     if (M == 0) return BL_OK;
     if (!codes || !gamma || !eta || !rowsum || !packed || !beta || !wsum || !Y) return BL_ERR_NULL;
     GemmArgs a{};
@@ -480,6 +561,7 @@ int bitlinear_forward_nonneg(const float* X, int64_t M, int64_t K, const void* p
                              float* Y, void* workspace, size_t workspace_bytes, void* stream) {
     if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return BL_ERR_SHAPE;
     if (granularity != BL_GAMMA_PER_TOKEN || (flags & ~BL_FLAG_SKIP_LN)) return BL_ERR_UNSUPPORTED;
+    if (K > kMaxGemmK) return BL_ERR_UNSUPPORTED;
     if (M == 0) return BL_OK;
     if (!X || !packed || !beta || !wsum || !Y) return BL_ERR_NULL;
     const ForwardWs ws = forward_ws_nonneg(M, K);

@@ -17,7 +17,6 @@
 // serves both: a persistent 256 x 256 kernel fed by DMA for large operands, a plain 256 x 128
 // kernel otherwise.  The preparation passes are HBM-bound and small next to the 2*M*N*K flops
 // of each product.
-#include <stdlib.h>
 
 #include "common.h"
 #include "kernels.h"
@@ -506,17 +505,17 @@ static void launch_gemm_tn(const uint16_t* A, const uint16_t* B, int64_t I, int6
     const int64_t gi = (I + 255) / 256, gj = (J + 255) / 256;
     // the ring kernel keeps a lane's byte offset into a block of 256 rows in 32 bits
     int ring = gi * gj * 2 >= bwd_num_cus() && ld < ((int64_t)1 << 22);
-    if (const char* e = getenv("BITLINEAR_BWD_RING")) ring = atoi(e) != 0 && ld < ((int64_t)1 << 22);
+    if (tuning().bwd_ring) ring = tuning().bwd_ring == 1 && ld < ((int64_t)1 << 22);
     if (ring) {
         int grid = bwd_num_cus();
-        if (const char* e = getenv("BITLINEAR_BWD_GRID")) grid = atoi(e) > 0 ? atoi(e) : grid;  // tests
+        if (tuning().bwd_grid > 0) grid = tuning().bwd_grid;
         if (grid > gi * gj) grid = (int)(gi * gj);
         // the block of tiles an XCD runs together (see tile_origin): blk_i x blk_j = grid / 8 tiles
         // out of its grid_i / 8 rows, as square as the divisors allow; 0 = no such tiling
         int blk_i = 0, blk_j = 0;
         const int64_t ntiles = gi * gj;
         if (ntiles % 8 == 0 && grid % 8 == 0 && gi % 8 == 0 && (ntiles / 8) % (grid / 8) == 0 &&
-            !getenv("BITLINEAR_BWD_ROWMAJOR")) {
+            !tuning().bwd_rowmajor) {
             const int cpx = grid / 8;
             const int64_t rx = gi / 8;
             for (int br = 1; br <= cpx; ++br) {

@@ -136,6 +136,12 @@ __device__ inline TokenQuant quant_token(const GemmArgs& a, uint32_t* lds_codes,
     }
     const float gamma = fmaxf(amax, 1e-5f);
     const float scale = 128.0f / gamma;
+    if (blockIdx.x == 0 && blockIdx.y == 0 && a.xhat_out) {  // uniform
+        float4* __restrict__ d4 = reinterpret_cast<float4*>(a.xhat_out);
+#pragma unroll
+        for (int j = 0; j < NV; ++j)
+            if (t + j * T < K4) d4[t + j * T] = v[j];
+    }
     int rs = 0;
 #pragma unroll
     for (int j = 0; j < NV; ++j) {
@@ -425,11 +431,6 @@ __global__ __launch_bounds__(256) void splitk_reduce(GemmArgs a, int splits) {
     a.Y[idx] = y;
 }
 
-static int env_int(const char* name, int dflt) {
-    const char* e = getenv(name);
-    return e ? atoi(e) : dflt;
-}
-
 static int num_cus() {
     static int n = 0;
     if (n == 0) {
@@ -472,7 +473,7 @@ static void launch_tiles(const GemmArgs& a, int W, int tpb, hipStream_t s) {
 // launcher below chooses): K = N = 28672 measured 58 us fused against 44 us in two launches.
 bool gemm_decode_fuses_quant(int64_t M, int64_t K, int64_t N) {
     const int64_t TK = tiles_k(K);
-    if (M != 1 || TK > 64 || env_int("BITLINEAR_DECODE_NOFUSE", 0)) return false;
+    if (M != 1 || TK > 64 || tuning().decode_nofuse) return false;
     const int64_t cap = TK <= 16 ? 8 : TK <= 32 ? 2 : 3;
     return tiles_n(N) <= cap * num_cus();
 }
@@ -505,7 +506,7 @@ hipError_t launch_gemm_decode(const GemmArgs& a_in, hipStream_t s) {
     int splits = 1;
     const bool fused = a.x_row != nullptr;  // the caller asked gemm_decode_fuses_quant
     const size_t need = gemm_split_ws_bytes(a.M, a.N, a.K);
-    if (need && !fused && a.split_ws && a.split_ws_bytes >= need && !env_int("BITLINEAR_DECODE_NOSPLIT", 0)) {
+    if (need && !fused && a.split_ws && a.split_ws_bytes >= need && !tuning().decode_nosplit) {
         splits = (int)((TK + 15) / 16);
         const int64_t per = (TK + splits - 1) / splits;  // tiles per slice, evenly
         splits = (int)((TK + per - 1) / per);            // slices that actually hold tiles
@@ -521,7 +522,8 @@ hipError_t launch_gemm_decode(const GemmArgs& a_in, hipStream_t s) {
     auto tiles_per_group = [&](int cap) {
         int tpb = (int)((TN * splits + num_cus() - 1) / num_cus());
         tpb = tpb > cap ? cap : tpb < 1 ? 1 : tpb;
-        return env_int("BITLINEAR_DECODE_T", tpb);
+        const int t = tuning().decode_tiles;
+        return t >= 1 && t <= cap ? t : tpb;
     };
     if (TK < 8) {
         // K < 4096: one K-chunk per wave, W = TK waves cover K in one round

@@ -10,8 +10,6 @@
 // same barriers: about 0.5 us for four stages.  The integer accumulators of the four groups
 // are added through LDS at the end and one epilogue dequantises: the same integers as any
 // other split of K, so the result does not depend on it.
-#include <stdlib.h>
-
 #include "common.h"
 #include "kernels.h"
 #include "ring.h"
@@ -328,10 +326,7 @@ __global__ __launch_bounds__(mid::THREADS) void gemm_mid_kernel(GemmArgs a, int 
 // from this too).  Returns tiles of K per slice, 0 = no split.
 int64_t prefill_split_tiles(int64_t M, int64_t N, int64_t K) {
     if (M <= 16 || M > 64) return 0;
-    if (const char* e = getenv("BITLINEAR_PREFILL_SPLIT_TILES")) {  // bench-only override
-        const int64_t per = atoi(e);
-        return per > 0 && per < tiles_k(K) ? per : 0;
-    }
+    if (const int64_t per = tuning().mid_split_tiles) return per > 0 && per < tiles_k(K) ? per : 0;
     const int64_t tiles = ((M + 63) / 64) * ((N + 127) / 128), TK = tiles_k(K);
     if (tiles > 128) return 0;
     int64_t smax = 256 / tiles;
@@ -354,7 +349,7 @@ hipError_t launch_gemm_mid(const GemmArgs& a_in, hipStream_t s) {
     int splits = 1;
     const int64_t per = prefill_split_tiles(a.M, a.N, a.K);
     const size_t need = gemm_split_ws_bytes(a.M, a.N, a.K);
-    if (per && a.split_ws && a.split_ws_bytes >= need && !getenv("BITLINEAR_PREFILL_NOSPLIT")) {
+    if (per && a.split_ws && a.split_ws_bytes >= need && !tuning().mid_nosplit) {
         splits = (int)((tiles_k(a.K) + per - 1) / per);
         a.tk_pitch = a.tk_pitch ? a.tk_pitch : tiles_k(a.K);
         a.split_k = per * kChunkK;

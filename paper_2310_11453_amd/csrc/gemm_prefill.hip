@@ -469,7 +469,7 @@ static void launch_tile(const GemmArgs& a, hipStream_t s) {
     const int grid_m = (int)((a.M + BM - 1) / BM), grid_n = (int)((a.N + BN - 1) / BN);
     const int ntiles = grid_m * grid_n;
     int grid = num_cus();  // one workgroup per CU
-    if (const char* e = getenv("BITLINEAR_PREFILL_GRID")) grid = atoi(e);  // bench-only override
+    if (tuning().prefill_grid > 0) grid = tuning().prefill_grid;
     if (grid > ntiles) grid = ntiles;
     if (plain)
         gemm_prefill_kernel<BM, BN, WM, WN, NS, false>
@@ -484,9 +484,8 @@ hipError_t launch_gemm_prefill(const GemmArgs& a_in, hipStream_t s) {
     GemmArgs a = a_in;
     a.split_k = 0;  // set here only
     if (a.K >= ((int64_t)1 << 22) || a.ldq >= ((int64_t)1 << 22)) return hipErrorInvalidValue;
-    const char* e = getenv("BITLINEAR_PREFILL_TILE");  // bench-only override: 1, 2
     int pick;
-    if (e) pick = atoi(e);
+    if (tuning().prefill_tile) pick = tuning().prefill_tile;
     else if (a.M <= 64) pick = 0;
     else {
         // 256x256 unless the 128-row tile needs fewer block-rounds of work on the CUs.  A 128-row
@@ -501,7 +500,7 @@ hipError_t launch_gemm_prefill(const GemmArgs& a_in, hipStream_t s) {
         pick = cost(128, 256) < cost(256, 256) ? 1 : 2;
     }
     if (a.M <= 64) {  // up to 32 tokens: gemm_stream.hip where it takes the shape; else gemm_mid.hip
-        if (!getenv("BITLINEAR_MID_ONLY") && launch_gemm_stream(a_in, s)) return hipGetLastError();
+        if (!tuning().mid_only && launch_gemm_stream(a_in, s)) return hipGetLastError();
         return launch_gemm_mid(a_in, s);
     }
     if (pick == 1) launch_tile<128, 256, 2, 4, 8>(a, s);

@@ -18,7 +18,6 @@
 // more tokens that traffic, not the weight stream, sets the time, and the LDS-tiled mid-batch
 // kernel is as fast.  Long K is split over workgroups (second kernel: splitk_reduce) when the
 // caller brought the workspace.
-#include <stdlib.h>
 
 #include <type_traits>
 
@@ -281,7 +280,7 @@ bool launch_gemm_stream(const GemmArgs& a_in, hipStream_t s) {
     const int64_t per = stream_split_tiles(a.M, a.K);
     const int64_t nsl = per ? (tiles_k(a.K) + per - 1) / per : 1;
     const size_t need = (size_t)nsl * (size_t)a.M * (size_t)a.N * 4;
-    if (per && a.split_ws && a.split_ws_bytes >= need && !getenv("BITLINEAR_PREFILL_NOSPLIT")) {
+    if (per && a.split_ws && a.split_ws_bytes >= need && !tuning().mid_nosplit) {
         splits = (int)nsl;
         a.tk_pitch = a.tk_pitch ? a.tk_pitch : tiles_k(a.K);
         a.split_k = per * kChunkK;

@@ -5,6 +5,25 @@
 
 namespace bl {
 
+// Launch-time switches for tests and benchmarks (bitlinear_set_tuning in the C ABI; defaults:
+// everything 0 = the launchers decide).  One process-wide instance, defined in api.hip.
+struct Tuning {
+    int decode_nofuse;     // forward at one token: quantiser and GEMM as two launches
+    int decode_nosplit;    // M <= 16: never split K over workgroups
+    int decode_tiles;      // M <= 16: weight tiles per workgroup (1..8)
+    int mid_nosplit;       // 16 < M <= 64: never split K over workgroups
+    int mid_split_tiles;   // 16 < M <= 64: 512-chunks of K per slice
+    int mid_only;          // 16 < M <= 32: skip the register-streaming kernel
+    int prefill_tile;      // M > 64: 1 = 128 x 256 tiles, 2 = 256 x 256
+    int prefill_grid;      // M > 64: workgroups of the persistent kernel
+    int quant_wpr;         // quantiser: waves per row (1, 2, 4, 8)
+    int bwd_ring;          // backward GEMM: 1 = ring kernel, 2 = small kernel
+    int bwd_grid;          // backward ring kernel: workgroups
+    int bwd_rowmajor;      // backward ring kernel: plain row-major tile order
+    int mid_kernel;        // 32 < M <= 64: 1 = LDS-tiled kernel with the in-workgroup K split
+};
+const Tuning& tuning();
+
 // pack.hip
 // A block of `rows` x `cols` weights inside a matrix whose rows are `ldw` floats apart
 // (ldw == cols: the whole matrix).  `packed` receives tiles_n(rows) x tiles_k(cols) tiles.
@@ -75,7 +94,8 @@ struct GemmArgs {
     // One token (M = 1, K <= 32768) straight from fp32, small-batch kernel only: every workgroup
     // normalises and quantises the row for itself (Eq. 12, Eq. 4-5) while its first weight tiles
     // are on their way, instead of reading codes / gamma / rowsum, so the layer is one launch.
-    // Workgroup 0 also writes the three to codes_out / gamma_out / rowsum_out.  nullptr: codes
+    // Workgroup 0 also writes the three to codes_out / gamma_out / rowsum_out and the normalised
+    // row to xhat_out.  nullptr: codes
     // are read.
     const float* x_row;
     const float* ln_gain;  // [K] or nullptr
@@ -85,6 +105,7 @@ struct GemmArgs {
     int8_t* codes_out;
     float* gamma_out;
     int32_t* rowsum_out;
+    float* xhat_out;  // [K]: the normalised row the codes were rounded from
 };
 bool gemm_decode_fuses_quant(int64_t M, int64_t K, int64_t N);
 size_t gemm_split_ws_bytes(int64_t M, int64_t N, int64_t K);

@@ -9,8 +9,6 @@
 // value handed to the rounding step is the correctly rounded normalised
 // input; the steps that decide a code are single fp32 operations:
 //   scale = 128 / gamma,  t = x^ * scale,  code = clamp(rne(t), -128, 127).
-#include <stdlib.h>
-
 #include "common.h"
 #include "kernels.h"
 #include "rowops.h"
@@ -309,10 +307,8 @@ hipError_t launch_quant(const QuantArgs& a, hipStream_t s) {
     int wpr = 1;
     while (wpr < 8 && K4 > (int64_t)wpr * kWave * 16) wpr *= 2;             // capacity
     while (wpr < 8 && a.M * wpr < 4096 && K4 >= (int64_t)wpr * 2 * kWave * 4) wpr *= 2;  // occupancy
-    if (const char* e = getenv("BITLINEAR_QUANT_WPR")) {  // bench-only override
-        const int v = atoi(e);
+    if (const int v = tuning().quant_wpr)
         if ((v == 1 || v == 2 || v == 4 || v == 8) && K4 <= (int64_t)v * kWave * 16) wpr = v;
-    }
     const int64_t per_lane = (K4 + wpr * kWave - 1) / (wpr * kWave);
     int nv = 1;
     while (nv < per_lane) nv *= 2;

@@ -29,3 +29,12 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture
+def tuning():
+    """Sets the library's launch-time switches for one test and resets them afterwards:
+    tuning("decode_nofuse=1")."""
+    import paper_2310_11453_amd as bl
+    yield bl.set_tuning
+    bl.set_tuning(None)

@@ -99,3 +99,37 @@ def test_grouped_host_checks(lib):
                                          0, one, one, 8, None) == -4
     assert lib.bitlinear_forward_grouped(one, 0, 2048, one, 512, 2, 4, one, None, None, 1e-5, 0,
                                          0, one, one, 1 << 20, None) == 0
+
+
+def test_tuning_switches_parse_on_the_host(lib):
+    assert lib.bitlinear_set_tuning(b"decode_nofuse=1,bwd_grid=8") == 0
+    assert lib.bitlinear_set_tuning(b"no_such_switch=1") == -3
+    assert lib.bitlinear_set_tuning(b"decode_nofuse") == -3
+    assert lib.bitlinear_set_tuning(b"decode_nofuse=x") == -3
+    assert lib.bitlinear_set_tuning(b"") == 0
+    assert lib.bitlinear_set_tuning(None) == 0
+
+
+def test_size_limits_are_host_errors(lib):
+    """K beyond what the GEMM kernels' int32 partial sums hold: refused before any launch."""
+    one = ctypes.c_void_p(256)
+    big = 65536 + 32
+    assert lib.bitlinear_matmul(one, one, one, 4, big, one, 16, one, 0, 0, one, None, 0, None) == -3
+    assert lib.bitlinear_forward(one, 4, big, one, 16, one, None, None, 1e-5, 0, 0, one, one,
+                                 1 << 30, None) == -3
+    assert lib.bitlinear_matmul_nonneg(one, one, one, one, 4, big, one, 16, one, one, 0, 0, one,
+                                       None) == -3
+    # a grouped layer is bounded per K-group
+    assert lib.bitlinear_forward_grouped(one, 4, 2 * 65536, one, 16, 1, 2, one, None, None, 1e-5, 0,
+                                         0, one, one, 8, None) == -4
+
+
+def test_forward_workspace_layout(lib):
+    import paper_2310_11453_amd as bl
+    lay = bl.forward_workspace_layout(1, 512, 2048)
+    assert lay["codes"] == 0 and lay["gamma"] >= 2048 and lay["rowsum"] > lay["gamma"]
+    assert lay["xhat"] is not None and lay["xhat"] + 4 * 2048 <= bl.workspace_bytes(bl.OP_FORWARD, 1, 512, 2048)
+    assert bl.forward_workspace_layout(4, 512, 2048)["xhat"] is None
+    off = (ctypes.c_size_t * 4)()
+    assert lib.bitlinear_forward_workspace_layout(1, 512, 48, 0, off) == -2
+    assert lib.bitlinear_forward_workspace_layout(1, 512, 64, 0, None) == -1

@@ -38,13 +38,13 @@ SHAPES = [(8, 512, 256), (12, 20, 64), (300, 200, 96), (64, 136, 1056), (257, 51
 
 
 # The library picks the GEMM kernel from the shape (the persistent 256 x 256 ring kernel needs
-# many tiles); BITLINEAR_BWD_RING forces either one so that both see the ragged shapes.
+# many tiles); the bwd_ring switch forces either one so that both see the ragged shapes.
 @pytest.mark.parametrize("M,N,K", SHAPES)
 @pytest.mark.parametrize("per_tensor", [True, False])
-@pytest.mark.parametrize("ring", ["0", "1"])
-def test_backward_ste_matches_oracle(bl, monkeypatch, M, N, K, per_tensor, ring):
+@pytest.mark.parametrize("ring", ["2", "1"])
+def test_backward_ste_matches_oracle(bl, tuning, M, N, K, per_tensor, ring):
     print(f"backward M={M} N={N} K={K} per_tensor={per_tensor} ring={ring}", flush=True)
-    monkeypatch.setenv("BITLINEAR_BWD_RING", ring)
+    tuning(f"bwd_ring={ring}")
     sd = wl.seed_for(4, M + N + K)
     W = wl.make_weight(N, K, 0.02, sd)
     X = wl.make_activation(M, K, sd)
@@ -67,11 +67,10 @@ def test_backward_ste_matches_oracle(bl, monkeypatch, M, N, K, per_tensor, ring)
     assert none is None and torch.equal(dW2, dW)
 
 
-def test_backward_ring_kernel_walks_several_tiles(bl, monkeypatch):
-    """The persistent kernel with fewer workgroups than tiles (BITLINEAR_BWD_GRID): dX has 16
+def test_backward_ring_kernel_walks_several_tiles(bl, tuning):
+    """The persistent kernel with fewer workgroups than tiles (the bwd_grid switch): dX has 16
     tiles on 8 workgroups (the tile order that groups tiles by L2 applies), dW 12 on 8."""
-    monkeypatch.setenv("BITLINEAR_BWD_RING", "1")
-    monkeypatch.setenv("BITLINEAR_BWD_GRID", "8")
+    tuning("bwd_ring=1,bwd_grid=8")
     M, N, K = 1024, 520, 1024
     sd = wl.seed_for(4, 77)
     print(f"backward ring grid=8 M={M} N={N} K={K}", flush=True)
@@ -89,12 +88,12 @@ def test_backward_ring_kernel_walks_several_tiles(bl, monkeypatch):
     close(dW.cpu().numpy(), dW_ref)
 
 
-@pytest.mark.parametrize("ring", ["0", "1"])
-def test_backward_exact_when_dy_is_bf16_representable(bl, monkeypatch, ring):
+@pytest.mark.parametrize("ring", ["2", "1"])
+def test_backward_exact_when_dy_is_bf16_representable(bl, tuning, ring):
     """Small integers in dY, codes and signs: every product and partial sum is exact in fp32,
     so the GPU must reproduce the integer result bit for bit (catches layout mistakes that a
     tolerance would hide)."""
-    monkeypatch.setenv("BITLINEAR_BWD_RING", ring)
+    tuning(f"bwd_ring={ring}")
     M, N, K = 96, 80, 160
     rng = np.random.default_rng(3)
     W = wl.make_weight(N, K, 0.02, 5)

@@ -234,12 +234,14 @@ def test_forward_end_to_end(bl, M, K, N, per_tensor):
 # One token: the small-batch GEMM kernel normalises and quantises the row itself (one launch).
 # K below one chunk, one chunk per wave, two per wave, the 16-wave kernels, a ragged last chunk,
 # eight chunks per wave with operands from LDS (K > 16384; one to three tiles per workgroup);
-# every variant of the quantiser the forward call offers.
+# every variant of the quantiser the forward call offers.  The kernel leaves the normalised row
+# it rounded in the workspace, so codes, row sum and accumulators are compared exactly "given
+# the same normalised input", as for the stand-alone quantiser.
 @pytest.mark.parametrize("K,N", [(96, 40), (2048, 6144), (3616, 257), (7168, 1000), (8192, 2048),
                                  (12320, 520), (16384, 300), (16896, 200), (28672, 7168), (32768, 1100),
                                  (20512, 12288)])
 @pytest.mark.parametrize("variant", ["plain", "affine", "skip_ln", "per_tensor"])
-def test_forward_single_token(bl, K, N, variant, monkeypatch):
+def test_forward_single_token(bl, K, N, variant, tuning):
     print(f"forward single token K={K} N={N} {variant}", flush=True)
     sd = wl.seed_for(0, 5 * K + N)
     W = wl.make_weight(N, K, 0.02, sd)
@@ -247,33 +249,36 @@ def test_forward_single_token(bl, K, N, variant, monkeypatch):
     rng = np.random.default_rng(sd)
     gain = (1.0 + 0.1 * rng.standard_normal(K)).astype(np.float32) if variant == "affine" else None
     bias = (0.05 * rng.standard_normal(K)).astype(np.float32) if variant == "affine" else None
-    kw = dict(per_tensor=variant == "per_tensor", flags=bl.FLAG_SKIP_LN if variant == "skip_ln" else 0,
+    pt = variant == "per_tensor"
+    kw = dict(per_tensor=pt, flags=bl.FLAG_SKIP_LN if variant == "skip_ln" else 0,
               ln_gain=None if gain is None else dev(gain), ln_bias=None if bias is None else dev(bias))
-    r = oracle.forward(X, W, per_tensor=variant == "per_tensor", skip_ln=variant == "skip_ln",
-                       gain=gain, bias=bias)
-    packed, alpha, beta = bl.bitlinear_pack_weights(dev(W))
-    y = host(bl.bitlinear_forward(dev(X), packed, N, beta, **kw))
-    rms = np.sqrt(np.mean(r["y"].astype(np.float64) ** 2))
-    assert np.abs(y - r["y"]).max() <= 1e-3 * rms
     kw_acc = dict(kw, flags=kw["flags"] | bl.FLAG_OUT_ACC_I32)
-    acc = host(bl.bitlinear_forward(dev(X), packed, N, beta, **kw_acc))
-    assert (acc != r["acc"]).mean() <= 1e-3  # differs only where an x^ sits on a rounding tie
-    # the workspace holds what the stand-alone quantiser would have put there
-    ws = torch.zeros(bl.workspace_bytes(bl.OP_FORWARD, 1, N, K, variant == "per_tensor"),
-                     dtype=torch.uint8, device="cuda")
-    bl.bitlinear_forward(dev(X), packed, N, beta, workspace=ws, **kw)
-    codes, gamma, rowsum, _ = bl.bitlinear_quant_act(dev(X), per_tensor=variant == "per_tensor",
-                                                     flags=kw["flags"], ln_gain=kw["ln_gain"],
-                                                     ln_bias=kw["ln_bias"])
-    held = host(ws)
-    assert (held[:K].view(np.int8) != host(codes)[0]).mean() <= 1e-3
-    # and the two-launch path (quantiser, then GEMM) gives the same layer output
-    monkeypatch.setenv("BITLINEAR_DECODE_NOFUSE", "1")
-    y2 = host(bl.bitlinear_forward(dev(X), packed, N, beta, **kw))
-    acc2 = host(bl.bitlinear_forward(dev(X), packed, N, beta, **kw_acc))
-    monkeypatch.delenv("BITLINEAR_DECODE_NOFUSE")
-    assert (acc2 != acc).mean() <= 1e-3
-    assert np.abs(y2 - y).max() <= 1e-3 * rms
+    r = oracle.forward(X, W, per_tensor=pt, skip_ln=variant == "skip_ln", gain=gain, bias=bias)
+    packed, alpha, beta = bl.bitlinear_pack_weights(dev(W))
+    lay = bl.forward_workspace_layout(1, N, K, pt)
+    rms = np.sqrt(np.mean(r["y"].astype(np.float64) ** 2))
+    for mode in ("one launch", "decode_nofuse=1"):
+        tuning(None if mode == "one launch" else mode)
+        ws = torch.zeros(bl.workspace_bytes(bl.OP_FORWARD, 1, N, K, pt), dtype=torch.uint8, device="cuda")
+        y = host(bl.bitlinear_forward(dev(X), packed, N, beta, workspace=ws, **kw))
+        held = host(ws)
+        xh = held[lay["xhat"]:lay["xhat"] + 4 * K].view(f32).reshape(1, K)
+        codes = held[:K].view(np.int8).reshape(1, K)
+        gamma = held[lay["gamma"]:lay["gamma"] + 4].view(f32)
+        rowsum = held[lay["rowsum"]:lay["rowsum"] + 4].view(np.int32)
+        # integers, exactly, from the normalised row the kernel itself rounded
+        g_ref = oracle.absmax(xh, pt)
+        assert np.array_equal(gamma, g_ref), mode
+        q_ref = oracle.quantize(xh, g_ref, pt)
+        assert np.array_equal(codes, q_ref), mode
+        assert rowsum[0] == int(q_ref.astype(np.int64).sum()), mode
+        acc_ref = oracle.matmul_i32(q_ref, r["sign"])
+        acc = host(bl.bitlinear_forward(dev(X), packed, N, beta, **kw_acc))
+        assert np.array_equal(acc, acc_ref), mode
+        assert np.array_equal(y, oracle.dequant(acc_ref, g_ref, r["beta"], pt)), mode
+        # the normalised row itself, and the layer end to end from raw X
+        assert np.abs(xh - r["xhat"]).max() <= 4e-6 * max(1.0, np.abs(r["xhat"]).max()), mode
+        assert np.abs(y - r["y"]).max() <= 1e-3 * rms, mode
 
 
 # Two to four tokens: the batch sizes next to the one-launch single-token path (they take the
@@ -327,41 +332,95 @@ def test_empty_batch_and_errors(bl):
 
 
 # ------------------------------------------------------------------ full benchmark sizes
-def _sampled_check(bl, M, K, N, w_std, outlier_p, outlier_mul, seed, n_samples=4096):
-    """Full-size run in the launch configuration the bench uses; all bits and codes are
-    checked, accumulators and outputs on a seeded sample the oracle computes one by one."""
-    W = wl.make_weight(N, K, w_std, seed)
+def _stratified_samples(M, N, seed, bm=64, bn=64, lines=3):
+    """(rows, cols) of the outputs to check: one seeded position inside every bm x bn block of the
+    output (every tile of every GEMM kernel is a union of such blocks: 16 weight rows x all tokens,
+    64 x 128, 128 x 256, 256 x 256), the four corners, and `lines` whole rows and whole columns
+    (first, last and seeded ones)."""
+    rng = np.random.default_rng(seed)
+    gm, gn = (M + bm - 1) // bm, (N + bn - 1) // bn
+    r0 = (np.arange(gm) * bm)[:, None] + rng.integers(0, bm, (gm, gn))
+    c0 = (np.arange(gn) * bn)[None, :] + rng.integers(0, bn, (gm, gn))
+    rows = [np.minimum(r0, M - 1).ravel(), np.array([0, M - 1, 0, M - 1])]
+    cols = [np.minimum(c0, N - 1).ravel(), np.array([0, N - 1, N - 1, 0])]
+    for m in sorted({0, M - 1, *rng.integers(0, M, lines).tolist()}):
+        rows.append(np.full(N, m))
+        cols.append(np.arange(N))
+    for n in sorted({0, N - 1, *rng.integers(0, N, lines).tolist()}):
+        rows.append(np.arange(M))
+        cols.append(np.full(M, n))
+    return np.concatenate(rows).astype(np.int64), np.concatenate(cols).astype(np.int64)
+
+
+_weight_cache = {}
+
+
+def _weight(N, K, w_std, seed):
+    """The seeded weight with the oracle's alpha, beta, signs and canonical words (kept for the
+    next test of the same layer: a 30B-shaped matrix takes seconds to draw and binarise)."""
+    key = (N, K, w_std, seed)
+    if key not in _weight_cache:
+        _weight_cache.clear()
+        W = wl.make_weight(N, K, w_std, seed)
+        a, b = oracle.weight_stats(W)
+        sign = oracle.binarize(W, a)
+        _weight_cache[key] = (W, a, b, sign, oracle.pack_canonical(sign))
+    return _weight_cache[key]
+
+
+def _sampled_check(bl, M, K, N, w_std, outlier_p, outlier_mul, seed, per_tensor=False):
+    """Full-size run in the launch configuration the bench uses.  All bits, alpha, beta, gamma and
+    codes are checked (codes given the normalised input the GPU dumped); accumulators and outputs
+    on a stratified sample the oracle computes one by one: every 64 x 64 block of the output, the
+    corners, and whole rows and columns."""
+    W, a, b, sign, words = _weight(N, K, w_std, seed)
     X = wl.make_activation(M, K, seed, outlier_p, outlier_mul)
     packed, alpha, beta = bl.bitlinear_pack_weights(dev(W))
-    a, b = oracle.weight_stats(W)
     assert host(alpha)[0] == a and host(beta)[0] == b
     canon = host(bl.bitlinear_packed_to_canonical(packed, N, K)).view(np.uint32)
-    sign = oracle.binarize(W, a)
-    assert np.array_equal(canon, oracle.pack_canonical(sign))
-    del W
+    assert np.array_equal(canon, words)
+    del canon
     Xd = dev(X)
-    codes, gamma, rowsum, xhat = bl.bitlinear_quant_act(Xd, want_xhat=True)
+    codes, gamma, rowsum, xhat = bl.bitlinear_quant_act(Xd, per_tensor=per_tensor, want_xhat=True)
     xh = host(xhat)
     del xhat
-    g_ref = oracle.absmax(xh)
+    g_ref = oracle.absmax(xh, per_tensor)
     assert np.array_equal(host(gamma), g_ref)
-    assert np.array_equal(host(codes), oracle.quantize(xh, g_ref))
+    q_ref = oracle.quantize(xh, g_ref, per_tensor)
+    assert np.array_equal(host(codes), q_ref)
+    assert np.array_equal(host(rowsum)[:M], q_ref.astype(np.int32).sum(1, dtype=np.int64))
+    xh_ref = oracle.layernorm(X[:64])
+    assert np.abs(xh[:64] - xh_ref).max() <= 2e-6 * max(1.0, np.abs(xh_ref).max())
     del xh
-    y = host(bl.bitlinear_forward(Xd, packed, N, beta))
-    rng = np.random.default_rng(seed)
-    rows = rng.integers(0, M, n_samples)
-    cols = rng.integers(0, N, n_samples)
-    rows[:4] = [0, M - 1, 0, M - 1]
-    cols[:4] = [0, N - 1, N - 1, 0]
-    acc = oracle.matmul_i32_sampled(host(codes), sign, rows, cols)
-    sc = (b * g_ref[rows]) / f32(128.0)
-    y_ref = acc.astype(f32) * sc
+    ws = torch.zeros(bl.workspace_bytes(bl.OP_FORWARD, M, N, K, per_tensor), dtype=torch.uint8,
+                     device="cuda")
+    y = host(bl.bitlinear_forward(Xd, packed, N, beta, per_tensor=per_tensor, workspace=ws))
+    if M == 1:
+        # one launch: the GEMM kernel quantises the row itself, with its own summation order; the
+        # integers that follow are checked from the normalised row IT rounded (left in the workspace)
+        lay = bl.forward_workspace_layout(1, N, K, per_tensor)
+        held = host(ws)
+        xh1 = held[lay["xhat"]:lay["xhat"] + 4 * K].view(f32).reshape(1, K)
+        g_ref = oracle.absmax(xh1, per_tensor)
+        q_ref = oracle.quantize(xh1, g_ref, per_tensor)
+        assert np.array_equal(held[lay["gamma"]:lay["gamma"] + 4].view(f32), g_ref)
+        assert np.array_equal(held[:K].view(np.int8).reshape(1, K), q_ref)
+        assert np.abs(xh1 - xh_ref[:1]).max() <= 2e-6 * max(1.0, np.abs(xh_ref).max())
+    del ws
+    rows, cols = _stratified_samples(M, N, seed, bm=min(64, M), bn=64 if M > 16 else 16)
+    acc_ref = oracle.matmul_i32_sampled(q_ref, sign, rows, cols)
+    sc = (b * (g_ref[0] if per_tensor else g_ref[rows])) / f32(128.0)
+    y_ref = acc_ref.astype(f32) * sc
     assert np.array_equal(y[rows, cols], y_ref)
-    # property that holds at any size: Var(y) ~ K beta^2 E[x~^2] (Eq. 8-10)
+    acc = host(bl.bitlinear_forward(Xd, packed, N, beta, per_tensor=per_tensor,
+                                    flags=bl.FLAG_OUT_ACC_I32))
+    assert np.array_equal(acc[rows, cols], acc_ref)
     return y
 
 
-@pytest.mark.parametrize("li,M", [(0, 1), (1, 4), (2, 16), (3, 16)])
+# every (layer, batch) cell of the 1.3B decode configuration
+@pytest.mark.parametrize("M", [1, 4, 16])
+@pytest.mark.parametrize("li", [0, 1, 2, 3])
 def test_full_size_decode_1p3b(bl, li, M):
     L = wl.CONFIGS[1].layers[li]
     print(f"full decode {L} M={M}", flush=True)
@@ -376,15 +435,60 @@ def test_full_size_prefill_6p7b(bl, li):
     assert np.isfinite(y).all()
 
 
-# M = 64: mid-batch kernel; 16: small-batch; 32 and 24: the 17-32 token kernel (layer 2, K = 28672,
-# goes on to the mid-batch one); 1: the quantiser inside the GEMM launch
-# 4096: the configuration's prefill batch (large-tile kernel, seven rounds of tiles per workgroup)
-@pytest.mark.parametrize("li,M", [(0, 64), (2, 64), (1, 16), (1, 32), (0, 24), (2, 32), (1, 1), (0, 1),
-                                  (1, 4096)])
-def test_full_size_30b_batched_decode(bl, li, M):
+# Every (layer, batch) cell of the 30B configuration (M = 64: batched decode; 4096: prefill,
+# the large-tile kernel, 5.25 to seven rounds of tiles per workgroup), and the batch sizes in
+# between that select the other kernels: 16 small-batch; 32 and 24 the 17-32 token kernel (layer
+# 2, K = 28672, goes on to the mid-batch one); 1 the quantiser inside the GEMM launch.
+@pytest.mark.parametrize("li,M", [(0, 1), (0, 24), (0, 64), (0, 4096),
+                                  (1, 1), (1, 16), (1, 32), (1, 64), (1, 4096),
+                                  (2, 32), (2, 64), (2, 4096)])
+def test_full_size_30b(bl, li, M):
     L = wl.CONFIGS[3].layers[li]
     print(f"full 30b {L} M={M}", flush=True)
-    _sampled_check(bl, M, L.K, L.N, 0.01, 0, 1, wl.seed_for(3, li), n_samples=2048)
+    _sampled_check(bl, M, L.K, L.N, 0.01, 0, 1, wl.seed_for(3, li))
+
+
+def test_full_size_training_forward_per_tensor(bl):
+    """The training configuration's forward: M = 8192, 4096 -> 16384, one gamma for the tensor
+    (the statistics pass with its grid-wide maximum, then the rounding pass)."""
+    c = wl.CONFIGS[4]
+    L, M = c.layers[0], c.Ms[0]
+    print(f"full training forward {L} M={M} per-tensor", flush=True)
+    _weight_cache.clear()
+    y = _sampled_check(bl, M, L.K, L.N, c.w_std, 0, 1, wl.seed_for(4, 0), per_tensor=True)
+    assert np.isfinite(y).all()
+    _weight_cache.clear()
+
+
+# ------------------------------------------------------------------ a chain of layers
+def _glue(h, K):
+    """What stands between two projections here: the next layer's input is the first K features of
+    the previous output (the attention and the non-linearity are not part of the layer)."""
+    return np.ascontiguousarray(h[:, :K])
+
+
+@pytest.mark.parametrize("stack", ["1.3b", "6.7b"])
+@pytest.mark.parametrize("M", [1, 4])
+def test_decode_chain_of_layers(bl, stack, M):
+    """One decoding step through QKV, O, up and down of two layers, each projection fed by the
+    previous one's output, through bitlinear_forward (one launch per projection at one token),
+    against the oracle chained the same way.  Outputs within 1e-3 of the oracle's rms at every
+    link (a code may move by one where a normalised value sits on a rounding tie)."""
+    d = 2048 if stack == "1.3b" else 4096
+    shapes = [("qkv", d, 3 * d), ("o", d, d), ("up", d, 4 * d), ("down", 4 * d, d)] * 2
+    print(f"chain {stack} M={M}", flush=True)
+    h_ref = wl.make_activation(M, d, wl.seed_for(1, 500 + M))
+    h_gpu = dev(h_ref)
+    for i, (name, K, N) in enumerate(shapes):
+        W = wl.make_weight(N, K, 0.02, wl.seed_for(1, 600 + i))
+        packed, alpha, beta = bl.bitlinear_pack_weights(dev(W))
+        x_ref = _glue(h_ref, K)
+        x_gpu = h_gpu[:, :K].contiguous()
+        h_ref = oracle.forward(x_ref, W)["y"]
+        h_gpu = bl.bitlinear_forward(x_gpu, packed, N, beta)
+        rms = np.sqrt(np.mean(h_ref.astype(np.float64) ** 2))
+        err = np.abs(host(h_gpu) - h_ref).max()
+        assert err <= 1e-3 * rms, (i, name, err, rms)
 
 
 # ------------------------------------------------------------------ K split across workgroups

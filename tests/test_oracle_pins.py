@@ -576,3 +576,47 @@ def test_eq6_forward_matches_float_matmul_of_dequantised_activations():
     # and the quantised layer stays close to the unquantised one (8-bit activations)
     yf = float(r["beta"]) * r["xhat"].astype(np.float64) @ r["sign"].astype(np.float64).T
     assert np.linalg.norm(r["y"] - yf) / np.linalg.norm(yf) < 0.05
+
+
+def test_eq6_per_tensor_branches():
+    """The paragraph after Eq. 6 makes per tensor the training-time granularity: one eta and one
+    gamma for the whole tensor.  Pinned against numpy's min / max over the tensor, against the
+    per-token functions applied to the tensor laid out as one long row (and on a one-row input,
+    where the two granularities coincide), against hand values, and through the same fp64
+    reconstruction as the per-token forward."""
+    rng = np.random.default_rng(35)
+    x = (rng.standard_normal((7, 160)) * 1.3 - 0.2).astype(f32)
+    eta, gamma = oracle.minmax_nonneg(x, per_tensor=True)
+    assert eta.shape == (1,) and gamma.shape == (1,)
+    assert eta[0] == x.min() and gamma[0] == f32(x.max() - x.min())
+    q = oracle.quantize_nonneg(x, eta, gamma, per_tensor=True)
+    # one long row, per token: the same minimum, range and codes
+    row = x.reshape(1, -1)
+    e1, g1 = oracle.minmax_nonneg(row)
+    assert e1[0] == eta[0] and g1[0] == gamma[0]
+    assert np.array_equal(oracle.quantize_nonneg(row, e1, g1).reshape(x.shape), q)
+    assert q.min() == 0 and q.max() == 127
+    assert q.reshape(-1)[x.argmin()] == 0 and q.reshape(-1)[x.argmax()] == 127
+    # a one-row tensor: both granularities are the same thing
+    et, gt = oracle.minmax_nonneg(x[:1], per_tensor=True)
+    ek, gk = oracle.minmax_nonneg(x[:1])
+    assert et[0] == ek[0] and gt[0] == gk[0]
+    assert np.array_equal(oracle.quantize_nonneg(x[:1], et, gt, per_tensor=True),
+                          oracle.quantize_nonneg(x[:1], ek, gk))
+    # hand values: rows [0, 1, 2, 4] and [-4, 0, 1, 3]: eta = -4, gamma = 8, scale 16
+    h = np.array([[0, 1, 2, 4], [-4, 0, 1, 3]], f32)
+    eh, gh = oracle.minmax_nonneg(h, per_tensor=True)
+    assert eh[0] == -4 and gh[0] == 8
+    assert oracle.quantize_nonneg(h, eh, gh, per_tensor=True).tolist() == [[64, 80, 96, 127], [0, 64, 80, 112]]
+    # the per-tensor dequantisation is the per-token one with the two scalars repeated per row
+    acc = rng.integers(-5000, 5000, (7, 12)).astype(np.int32)
+    wsum = rng.integers(-160, 160, 12).astype(np.int32)
+    y_t = oracle.dequant_nonneg(acc, gamma, eta, 0.017, wsum, per_tensor=True)
+    y_k = oracle.dequant_nonneg(acc, np.repeat(gamma, 7), np.repeat(eta, 7), 0.017, wsum)
+    assert np.array_equal(y_t, y_k)
+    # end to end: y = beta * W~ (x~ gamma / Q_b + eta) with the tensor-wide scalars
+    W = (rng.standard_normal((24, 160)) * 0.02).astype(f32)
+    r = oracle.forward_nonneg(x, W, per_tensor=True)
+    rec = r["codes"].astype(np.float64) * float(r["gamma"][0]) / 128.0 + float(r["eta"][0])
+    y = float(r["beta"]) * rec @ r["sign"].astype(np.float64).T
+    assert np.abs(r["y"] - y).max() <= 1e-5 * np.abs(y).max()
