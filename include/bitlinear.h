@@ -136,6 +136,21 @@ int bitlinear_forward(const float* X, int64_t M, int64_t K, const void* packed, 
                       int granularity, unsigned flags, float* Y, void* workspace,
                       size_t workspace_bytes, void* stream);
 
+/* bitlinear_forward for callers that cannot allocate or pass scratch memory (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the workspace is a
+ * 16 MiB array the library itself holds in device memory (one copy per GPU, kept until the
+ * process ends).  The call allocates nothing and runs the same kernels as bitlinear_forward:
+ * same arguments, same result bit for bit.  Shapes whose workspace
+ * (bitlinear_workspace_bytes(BL_OP_FORWARD, ...)) exceeds 16 MiB = 16777216 bytes return
+ * BL_ERR_UNSUPPORTED: roughly M * K <= 16 MiB less the K-split partial sums, i.e. every
+ * decode batch (M <= 64 at K <= 65536), not the prefill batches.  All calls on one GPU share
+ * the array: calls that overlap in time (different streams, or threads) race; calls ordered
+ * on one stream do not.  The array's contents after a call are unspecified. */
+int bitlinear_forward_static(const float* X, int64_t M, int64_t K, const void* packed, int64_t N,
+                             const float* beta, const float* ln_gain, const float* ln_bias,
+                             float ln_eps, int granularity, unsigned flags, float* Y,
+                             void* stream);
+
 /* host: where bitlinear_forward leaves its intermediates in the workspace, for inspection.
  * offsets[0..3] = byte offsets of codes (int8 [M,K]), gamma (fp32 [M] or [1]), rowsum
  * (int32 [M]) and x^ (fp32 [K], M = 1 only; (size_t)-1 otherwise).  BL_ERR_SHAPE /

@@ -29,6 +29,7 @@ EXPORTS = (
     "bitlinear_quant_act_grouped", "bitlinear_forward_grouped", "bitlinear_layernorm_backward",
     "bitlinear_weight_rowsums", "bitlinear_quant_act_nonneg", "bitlinear_matmul_nonneg",
     "bitlinear_forward_nonneg", "bitlinear_forward_workspace_layout", "bitlinear_set_tuning",
+    "bitlinear_forward_static",
 )
 
 _lib = None
@@ -90,6 +91,8 @@ def load_library() -> ctypes.CDLL:
     lib.bitlinear_forward_nonneg.restype = ci
     lib.bitlinear_forward_nonneg.argtypes = [vp, i64, i64, vp, i64, vp, vp, vp, vp, cf, ci, u32, vp,
                                              vp, sz, vp]
+    lib.bitlinear_forward_static.restype = ci
+    lib.bitlinear_forward_static.argtypes = [vp, i64, i64, vp, i64, vp, vp, vp, cf, ci, u32, vp, vp]
     lib.bitlinear_forward_workspace_layout.restype = ci
     lib.bitlinear_forward_workspace_layout.argtypes = [i64, i64, i64, ci, ctypes.POINTER(sz)]
     lib.bitlinear_set_tuning.restype = ci
@@ -234,6 +237,19 @@ def bitlinear_forward(X: torch.Tensor, packed: torch.Tensor, N: int, beta: torch
         _ptr(X, torch.float32), M, K, _ptr(packed), N, _ptr(beta, torch.float32),
         _ptr(ln_gain, torch.float32), _ptr(ln_bias, torch.float32), ln_eps, _gran(per_tensor),
         flags, _ptr(out), _ptr(ws), ws.numel(), _stream()), "bitlinear_forward")
+    return out
+
+
+def bitlinear_forward_static(X: torch.Tensor, packed: torch.Tensor, N: int, beta: torch.Tensor,
+                             out: torch.Tensor, ln_eps: float = 1e-5, per_tensor: bool = False,
+                             flags: int = 0, ln_gain=None, ln_bias=None) -> torch.Tensor:
+    """bitlinear_forward with the library's own scratch array: nothing is allocated, here or in
+    the library (the caller brings the output)."""
+    M, K = X.shape
+    _check(load_library().bitlinear_forward_static(
+        _ptr(X, torch.float32), M, K, _ptr(packed), N, _ptr(beta, torch.float32),
+        _ptr(ln_gain, torch.float32), _ptr(ln_bias, torch.float32), ln_eps, _gran(per_tensor),
+        flags, _ptr(out), _stream()), "bitlinear_forward_static")
     return out
 
 

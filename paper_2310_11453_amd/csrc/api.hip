@@ -3,6 +3,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "../../include/bitlinear.h"
 #include "common.h"
 #include "kernels.h"
@@ -166,6 +168,29 @@ void plain_fields(GemmArgs& a) {
     a.beta_rows = a.N;
     a.beta_stride = 0;
     a.accumulate = false;
+}
+
+// ---- scratch memory the library owns (bitlinear_forward_static) ------------------------
+// Every GPU the library runs on holds its own copy of this array, at its own address, until
+// the process ends.  Its name is only a host-side stand-in: host code uses the device address
+// that hipGetSymbolAddress returns, looked up once per device with that device current.
+constexpr size_t kScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+// device address of `scratch` on the current device; nullptr on failure
+void* scratch_address() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
 }
 
 }  // namespace
@@ -332,6 +357,26 @@ int bitlinear_forward(const float* X, int64_t M, int64_t K, const void* packed, 
     a.split_ws_bytes = ws.split_bytes;
     if (M <= 16) return check_hip(launch_gemm_decode(a, (hipStream_t)stream));
     return check_hip(launch_gemm_prefill(a, (hipStream_t)stream));
+}
+
+int bitlinear_forward_static(const float* X, int64_t M, int64_t K, const void* packed, int64_t N,
+                             const float* beta, const float* ln_gain, const float* ln_bias,
+                             float ln_eps, int granularity, unsigned flags, float* Y,
+                             void* stream) {
+    if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return BL_ERR_SHAPE;
+    if (!gran_ok(granularity) || (flags & ~(BL_FLAG_SKIP_LN | BL_FLAG_OUT_ACC_I32)))
+        return BL_ERR_UNSUPPORTED;
+    if (K > kMaxGemmK) return BL_ERR_UNSUPPORTED;
+    // the same workspace as bitlinear_forward's, inside the library's own array or not at all
+    if (forward_ws(M, N, K, granularity).total > kScratchBytes) return BL_ERR_UNSUPPORTED;
+    if (M == 0) return BL_OK;
+    if (!X || !packed || !beta || !Y) return BL_ERR_NULL;
+    void* ws = scratch_address();
+    if (!ws) return BL_ERR_HIP;
+    // nothing in the workspace has to start at zero: the kernels write every byte they later
+    // read (the running maximum of a per-tensor gamma is cleared by a fill kernel of its own)
+    return bitlinear_forward(X, M, K, packed, N, beta, ln_gain, ln_bias, ln_eps, granularity, flags,
+                             Y, ws, kScratchBytes, stream);
 }
 
 int bitlinear_forward_workspace_layout(int64_t M, int64_t N, int64_t K, int granularity,
