@@ -52,6 +52,209 @@ def event_ms(fn, iters, torch):
     return start.elapsed_time(end) / iters
 
 
+def graph_ms(fn, launches, replays, torch):
+    """Per-call milliseconds of `fn` from `launches` calls captured once into a HIP graph and
+    replayed: the kernels run back to back on the device, so kernels of a few microseconds are
+    timed at the rate the device runs them, not at the rate Python can enqueue them.  `fn` takes
+    the index of the call (callers rotate buffers with it).  Falls back to eager launches."""
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for i in range(launches):
+                fn(i)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for i in range(launches):
+                fn(i)
+        g.replay()
+        torch.cuda.synchronize()
+        return event_ms(g.replay, replays, torch) / launches, "HIP graph replay"
+    except Exception as exc:  # capture unavailable
+        state = {"i": 0}
+
+        def eager():
+            fn(state["i"])
+            state["i"] += 1
+
+        return event_ms(eager, launches * replays, torch), f"eager ({type(exc).__name__})"
+
+
+def decode_stacks(bl, torch, dev, decode):
+    """The stream / whole-block legs of the decode measurement (added to `decode`)."""
+    c3 = wl.CONFIGS[3]
+    # Layer stream at the 1.3B shapes: the four projections of 24 layers, four distinct sets of
+    # them (604 MB of packed weights, more than L2 + Infinity Cache), enqueued back to back as
+    # one HIP graph per batch size; GB/s = algorithmic bytes of all launches / time.
+    c2 = wl.CONFIGS[1]
+    protos = []
+    for li, L2 in enumerate(c2.layers):
+        W2 = wl.make_weight(L2.N, L2.K, c2.w_std, wl.seed_for(1, li))
+        p2, _, b2 = bl.bitlinear_pack_weights(torch.from_numpy(W2).to(dev))
+        protos.append((L2, p2, b2))
+        del W2
+    n_sets = 4 * 24
+    sets = [[(L2, p2.clone(), b2) for (L2, p2, b2) in protos] for _ in range(n_sets)]
+    stream = []
+    for Md in (1, 4, 16):
+        acts = {}
+        for K2 in sorted({L2.K for (L2, _, _) in protos}):
+            X2 = torch.from_numpy(wl.make_activation(Md, K2, wl.seed_for(1, K2 % 97))).to(dev)
+            acts[K2] = bl.bitlinear_quant_act(X2)[:3]
+        outs = {L2.name: torch.empty((Md, L2.N), dtype=torch.float32, device=dev)
+                for (L2, _, _) in protos}
+
+        def run_stream():
+            for layer in sets:
+                for (L2, p2, b2) in layer:
+                    c_, g_, r_ = acts[L2.K]
+                    bl.bitlinear_matmul(c_, g_, r_, p2, L2.N, b2, out=outs[L2.name])
+
+        run_stream()
+        torch.cuda.synchronize()
+        mode = "eager launches"
+        timed = run_stream
+        try:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                run_stream()
+            torch.cuda.current_stream().wait_stream(side)
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                run_stream()
+            ref = {k: v.clone() for k, v in outs.items()}
+            graph.replay()
+            torch.cuda.synchronize()
+            if all(torch.equal(ref[k], outs[k]) for k in outs):
+                timed, mode = graph.replay, "one HIP graph of all launches, replayed"
+        except Exception as exc:  # capture unavailable: time the eager launches
+            mode = f"eager launches (graph capture failed: {type(exc).__name__})"
+        timed()
+        t = event_ms(timed, 5, torch)
+        nbytes = sum(gemm_bytes(Md, L2.K, L2.N) for layer in sets for (L2, _, _) in layer)
+        stream.append(dict(M=Md, launches=len(sets) * len(protos), us=t * 1e3,
+                           us_per_launch=t * 1e3 / (len(sets) * len(protos)),
+                           gbs=nbytes / (t * 1e-3) / 1e9,
+                           frac_hbm=nbytes / (t * 1e-3) / 1e9 / HBM_PEAK_GBS, launch=mode))
+    decode["layer_stream_1p3b"] = stream
+
+    # One decoding step of the 24-layer stack: LN + quantise + GEMM + dequant through QKV, O,
+    # up and down of every layer, each input being the previous output (the attention and the
+    # non-linearity between them are left out: only their place in the chain matters here).
+    # Four stacks of distinct weights, one HIP graph each, replayed in turn.
+    block = []
+    for Md in (1, 4, 16):
+        h0 = torch.from_numpy(wl.make_activation(Md, 2048, wl.seed_for(1, 50))).to(dev)
+        bufs = {L2.name: torch.empty((Md, L2.N), dtype=torch.float32, device=dev)
+                for (L2, _, _) in protos}
+        wss = {L2.name: torch.empty(bl.workspace_bytes(bl.OP_FORWARD, Md, L2.N, L2.K),
+                                    dtype=torch.uint8, device=dev) for (L2, _, _) in protos}
+
+        def run_stack(layers24):
+            h = h0
+            for layer in layers24:
+                for (L2, p2, b2) in layer:
+                    x_in = h if h.shape[1] == L2.K else h.view(-1)[:Md * L2.K].view(Md, L2.K)
+                    h = bl.bitlinear_forward(x_in, p2, L2.N, b2, out=bufs[L2.name],
+                                             workspace=wss[L2.name])
+            return h
+
+        stacks = [sets[i * 24:(i + 1) * 24] for i in range(4)]
+        ref = run_stack(stacks[0]).clone()
+        torch.cuda.synchronize()
+        mode = "eager launches"
+        runners = [lambda st=st: run_stack(st) for st in stacks]
+        try:
+            graphs = []
+            for st in stacks:
+                side = torch.cuda.Stream()
+                side.wait_stream(torch.cuda.current_stream())
+                with torch.cuda.stream(side):
+                    run_stack(st)
+                torch.cuda.current_stream().wait_stream(side)
+                g2 = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g2):
+                    run_stack(st)
+                graphs.append(g2)
+            graphs[0].replay()
+            torch.cuda.synchronize()
+            if torch.equal(ref, bufs["down"]):
+                runners, mode = [g2.replay for g2 in graphs], "one HIP graph per stack, replayed"
+        except Exception as exc:
+            mode = f"eager launches (graph capture failed: {type(exc).__name__})"
+
+        def run_all():
+            for r in runners:
+                r()
+
+        run_all()
+        t = event_ms(run_all, 5, torch) / len(runners)
+        nbytes = sum(gemm_bytes(Md, L2.K, L2.N) + 5 * Md * L2.K for (L2, _, _) in protos) * 24
+        # one token with K <= 32768: the GEMM launch quantises the row itself (one launch a
+        # layer); otherwise quantiser + GEMM
+        n_launch = 24 * sum(1 if Md == 1 and L2.K <= 32768 else 2 for (L2, _, _) in protos)
+        block.append(dict(M=Md, layers=24, launches=n_launch, us_per_step=t * 1e3,
+                          us_per_launch=t * 1e3 / n_launch,
+                          gbs=nbytes / (t * 1e-3) / 1e9, launch=mode))
+    decode["block_decode_1p3b"] = block
+    del sets, protos
+
+    # The same chain at the 6.7B shapes (d = 4096; the whole 32-layer stack, 0.8 GB of packed
+    # weights) and the 30B shapes (d = 7168; eight distinct layers, 0.6 GB), one token: one HIP
+    # graph, one launch per projection (the GEMM kernel quantises the row itself).
+    for tag, d, n_layers, w_std, sd in (("6p7b", 4096, 32, 0.02, 2), ("30b", 7168, 8, c3.w_std, 3)):
+        shapes = [wl.Layer("qkv", d, 3 * d), wl.Layer("o", d, d), wl.Layer("up", d, 4 * d),
+                  wl.Layer("down", 4 * d, d)]
+        protos3 = []
+        for li, L3 in enumerate(shapes):
+            W3 = wl.make_weight(L3.N, L3.K, w_std, wl.seed_for(sd, 10 + li))
+            p3, _, b3 = bl.bitlinear_pack_weights(torch.from_numpy(W3).to(dev))
+            protos3.append((L3, p3, b3))
+            del W3
+        stack = [[(L3, p3.clone(), b3) for (L3, p3, b3) in protos3] for _ in range(n_layers)]
+        h0 = torch.from_numpy(wl.make_activation(1, d, wl.seed_for(sd, 50))).to(dev)
+        bufs3 = {L3.name: torch.empty((1, L3.N), dtype=torch.float32, device=dev) for (L3, _, _) in protos3}
+        wss3 = {L3.name: torch.empty(bl.workspace_bytes(bl.OP_FORWARD, 1, L3.N, L3.K), dtype=torch.uint8,
+                                     device=dev) for (L3, _, _) in protos3}
+
+        def run_stack3():
+            h = h0
+            for layer in stack:
+                for (L3, p3, b3) in layer:
+                    x_in = h if h.shape[1] == L3.K else h.view(-1)[:L3.K].view(1, L3.K)
+                    h = bl.bitlinear_forward(x_in, p3, L3.N, b3, out=bufs3[L3.name], workspace=wss3[L3.name])
+            return h
+
+        ref3 = run_stack3().clone()
+        torch.cuda.synchronize()
+        timed3, mode3 = run_stack3, "eager launches"
+        try:
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                run_stack3()
+            torch.cuda.current_stream().wait_stream(side)
+            g3 = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g3):
+                run_stack3()
+            g3.replay()
+            torch.cuda.synchronize()
+            if torch.equal(ref3, bufs3["down"]):
+                timed3, mode3 = g3.replay, f"one HIP graph of {n_layers} layers, replayed"
+        except Exception as exc:
+            mode3 = f"eager launches (graph capture failed: {type(exc).__name__})"
+        timed3()
+        t3 = event_ms(timed3, 5, torch) / n_layers
+        nbytes3 = sum(gemm_bytes(1, L3.K, L3.N) + 5 * L3.K for (L3, _, _) in protos3)
+        decode[f"block_decode_{tag}"] = dict(M=1, layers=n_layers, us_per_layer=t3 * 1e3,
+                                             us_per_token=t3 * 1e3 * n_layers,
+                                             gbs=nbytes3 / (t3 * 1e-3) / 1e9, launch=mode3)
+        del stack, protos3, bufs3, wss3
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -63,6 +266,9 @@ def main():
     ap.add_argument("--no-prefill-30b", action="store_true",
                     help="skip the 30B layers at M = 4096 (they run the 6.7B step's GEMM kernel at another "
                          "size: a per-kernel profile of the step wants them out)")
+    ap.add_argument("--no-decode-stacks", action="store_true",
+                    help="decode leg: only the 30B-shaped launches (no 1.3B layer stream, no whole-block "
+                         "steps): what a counter profile of those kernels wants")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run plain device copies of 256 MiB (reference for the rocprofv3 "
@@ -131,10 +337,23 @@ def main():
         L = d["L"]
         codes, gamma, rowsum, _ = bl.bitlinear_quant_act(d["Xd"])
         torch.cuda.synchronize()
-        t_q = event_ms(lambda: bl.bitlinear_quant_act(d["Xd"]), args.steps, torch)
+        # the quantiser takes 10-35 us: timed from a graph of 20 launches (codes, gamma, row sums
+        # into the layer's workspace, as bitlinear_forward does); the GEMM with events around
+        # eager back-to-back launches (100+ us each: the queue never runs dry)
+        qws = torch.empty(bl.workspace_bytes(bl.OP_QUANT, M, 1, L.K), dtype=torch.uint8, device=dev)
+        lib = bl.load_library()
+
+        def quant_once(i, d=d, L=L, codes=codes, gamma=gamma, rowsum=rowsum, qws=qws):
+            rc = lib.bitlinear_quant_act(d["Xd"].data_ptr(), M, L.K, None, None, 1e-5, 0, 0,
+                                         codes.data_ptr(), gamma.data_ptr(), rowsum.data_ptr(), None,
+                                         qws.data_ptr(), qws.numel(),
+                                         torch.cuda.current_stream().cuda_stream)
+            assert rc == 0
+
+        t_q, q_mode = graph_ms(quant_once, 20, max(2, args.steps // 10), torch)
         t_g = event_ms(lambda: bl.bitlinear_matmul(codes, gamma, rowsum, d["packed"], L.N, d["beta"],
                                                    out=d["Y"]), args.steps, torch)
-        kern[L.name] = dict(quant_ms=t_q, gemm_ms=t_g,
+        kern[L.name] = dict(quant_ms=t_q, quant_timing=q_mode, gemm_ms=t_g,
                             gemm_tops=2 * M * L.N * L.K / (t_g * 1e-3) / 1e12,
                             quant_gbs=5 * M * L.K / (t_q * 1e-3) / 1e9)
     up = layers[0]["L"]
@@ -152,25 +371,31 @@ def main():
                 note="two passes over fp32 W (stats, then compare+pack)")
 
     # ---- parity guard: a fast-but-wrong kernel must not report a number ----------------------
+    # Both layers of the step: sampled rows of codes (given the normalised input the GPU dumped)
+    # and sampled outputs of the timed launches against the oracle.
     import oracle
-    parity = "skipped"
-    d = layers[0]
-    L = d["L"]
-    codes, gamma, rowsum, xhat = bl.bitlinear_quant_act(d["Xd"], want_xhat=True)
-    rows = np.arange(0, M, 257)
-    xh = xhat[torch.from_numpy(rows).to(dev)].cpu().numpy()
-    g_ref = oracle.absmax(xh)
-    q_ref = oracle.quantize(xh, g_ref)
-    ok = np.array_equal(codes.cpu().numpy()[rows], q_ref)
-    a, b = oracle.weight_stats(d["W"])
-    sign = oracle.binarize(d["W"], a)
-    rng = np.random.default_rng(1)
-    cols = rng.integers(0, L.N, rows.size * 16)
-    rr = np.repeat(np.arange(rows.size), 16)
-    acc = oracle.matmul_i32_sampled(q_ref, sign, rr, cols)
-    y_ref = acc.astype(np.float32) * ((b * g_ref[rr]) / np.float32(128.0))
-    y_gpu = d["Y"].cpu().numpy()[rows[rr], cols]
-    ok = ok and np.array_equal(y_gpu, y_ref) and float(d["beta"].cpu()[0]) == float(b)
+    ok = True
+    signs, betas = [], []
+    for d in layers:
+        L = d["L"]
+        codes, gamma, rowsum, xhat = bl.bitlinear_quant_act(d["Xd"], want_xhat=True)
+        rows = np.arange(0, M, 257)
+        xh = xhat[torch.from_numpy(rows).to(dev)].cpu().numpy()
+        del xhat
+        g_ref = oracle.absmax(xh)
+        q_ref = oracle.quantize(xh, g_ref)
+        ok = ok and np.array_equal(codes.cpu().numpy()[rows], q_ref)
+        a, b = oracle.weight_stats(d["W"])
+        sign = oracle.binarize(d["W"], a)
+        signs.append(sign)
+        betas.append(b)
+        rng = np.random.default_rng(1)
+        cols = rng.integers(0, L.N, rows.size * 16)
+        rr = np.repeat(np.arange(rows.size), 16)
+        acc = oracle.matmul_i32_sampled(q_ref, sign, rr, cols)
+        y_ref = acc.astype(np.float32) * ((b * g_ref[rr]) / np.float32(128.0))
+        y_gpu = d["Y"].cpu().numpy()[rows[rr], cols]
+        ok = ok and np.array_equal(y_gpu, y_ref) and float(d["beta"].cpu()[0]) == float(b)
     parity = "ok" if ok else "FAILED"
 
     # ---- decode leg: packed-weight streaming on 30B-shaped layers, M = 16 and M = 1 ----------
@@ -183,29 +408,50 @@ def main():
         for li, L3 in enumerate(c3.layers):
             W3 = wl.make_weight(L3.N, L3.K, c3.w_std, wl.seed_for(3, li))
             p3, a3, b3 = bl.bitlinear_pack_weights(torch.from_numpy(W3).to(dev))
+            # parity guard of this leg: 64 seeded output columns of every timed launch against the
+            # oracle (from the GPU's own codes), all rows at M <= 64, 64 seeded rows at M = 4096
+            a_ref, b_ref = oracle.weight_stats(W3)
+            ns = np.sort(np.random.default_rng(li).choice(L3.N, 64, replace=False))
+            sign_s = oracle.binarize(W3[ns], a_ref)
             del W3
+
+            def sampled_ok(codes_t, gamma_t, Y_t, ms):
+                q = codes_t[torch.from_numpy(ms).to(dev)].cpu().numpy()
+                g = gamma_t.cpu().numpy()[ms]
+                acc = oracle.matmul_i32(q, sign_s)
+                y_ref = acc.astype(np.float32) * ((b_ref * g) / np.float32(128.0))[:, None]
+                y = Y_t[torch.from_numpy(ms).to(dev)][:, torch.from_numpy(ns).to(dev)].cpu().numpy()
+                return bool(np.array_equal(y, y_ref)) and float(b3.cpu()[0]) == float(b_ref)
             # rotate through copies so the working set (>= 512 MB) exceeds L2 + Infinity Cache
             ncopy = max(2, int(np.ceil(512e6 / p3.numel())))
             copies = [p3.clone() for _ in range(ncopy)]
+            # The floor: a launch that only reads the same packed weights, with the small-batch
+            # kernel's grid and loads (bitlinear_probe_read), over the same rotating copies.
+            t_floor, _ = graph_ms(lambda i: bl.probe_read(copies[i % ncopy], 256, 448), 2 * ncopy, 5, torch)
+            decode.setdefault("read_floor", []).append(
+                dict(layer=L3.name, bytes=p3.numel(), us=t_floor * 1e3,
+                     gbs=p3.numel() / (t_floor * 1e-3) / 1e9,
+                     note="16-byte streaming loads of the packed weights only, 256 workgroups x 7 waves"))
             for Md in (1, 16, 64):  # M = 64 takes the MFMA-tile kernel: the ridge of the two rooflines
                 X3 = torch.from_numpy(wl.make_activation(Md, L3.K, wl.seed_for(3, li))).to(dev)
                 codes3, gamma3, rowsum3, _ = bl.bitlinear_quant_act(X3)
                 Y3 = torch.empty((Md, L3.N), dtype=torch.float32, device=dev)
                 ws3 = torch.empty(max(256, bl.workspace_bytes(bl.OP_MATMUL, Md, L3.N, L3.K)),
                                   dtype=torch.uint8, device=dev)
-                state = {"i": 0}
 
-                def run():
-                    bl.bitlinear_matmul(codes3, gamma3, rowsum3, copies[state["i"] % ncopy], L3.N,
+                def run(i):
+                    bl.bitlinear_matmul(codes3, gamma3, rowsum3, copies[i % ncopy], L3.N,
                                         b3, out=Y3, workspace=ws3)
-                    state["i"] += 1
 
-                for _ in range(ncopy):
-                    run()
-                t = event_ms(run, 4 * ncopy, torch)
+                t, t_mode = graph_ms(run, 2 * ncopy, 5, torch)
+                if not sampled_ok(codes3, gamma3, Y3, np.arange(Md)):
+                    parity = "FAILED"
                 gbs = gemm_bytes(Md, L3.K, L3.N) / (t * 1e-3) / 1e9
+                tops3 = 2 * Md * L3.K * L3.N / (t * 1e-3) / 1e12
                 rec = dict(layer=L3.name, K=L3.K, N=L3.N, M=Md, us=t * 1e3, gbs=gbs,
-                           frac_hbm=gbs / HBM_PEAK_GBS)
+                           frac_hbm=gbs / HBM_PEAK_GBS, tops=tops3,
+                           frac_i8_mfma_peak=tops3 / I8_MFMA_PEAK_TOPS,
+                           x_read_floor=t / t_floor, timing=t_mode)
                 decode["shapes"].append(rec)
                 if Md <= 16 and (best is None or gbs > best["gbs"]):
                     best = rec
@@ -227,182 +473,23 @@ def main():
             for _ in range(100):
                 run_p()
             tp = event_ms(run_p, 30, torch)
+            if not sampled_ok(cp, gp, Yp, np.sort(np.random.default_rng(7 + li).choice(Mp, 64, replace=False))):
+                parity = "FAILED"
             tops_p = 2 * Mp * L3.K * L3.N / (tp * 1e-3) / 1e12
             decode.setdefault("prefill_30b", []).append(
                 dict(layer=L3.name, K=L3.K, N=L3.N, M=Mp, us=tp * 1e3, tops=tops_p,
                      frac_i8_mfma_peak=tops_p / I8_MFMA_PEAK_TOPS))
             del cp, Yp, p3
 
-        # Layer stream at the 1.3B shapes: the four projections of 24 layers, four distinct sets of
-        # them (604 MB of packed weights, more than L2 + Infinity Cache), enqueued back to back as
-        # one HIP graph per batch size; GB/s = algorithmic bytes of all launches / time.
-        c2 = wl.CONFIGS[1]
-        protos = []
-        for li, L2 in enumerate(c2.layers):
-            W2 = wl.make_weight(L2.N, L2.K, c2.w_std, wl.seed_for(1, li))
-            p2, _, b2 = bl.bitlinear_pack_weights(torch.from_numpy(W2).to(dev))
-            protos.append((L2, p2, b2))
-            del W2
-        n_sets = 4 * 24
-        sets = [[(L2, p2.clone(), b2) for (L2, p2, b2) in protos] for _ in range(n_sets)]
-        stream = []
-        for Md in (1, 4, 16):
-            acts = {}
-            for K2 in sorted({L2.K for (L2, _, _) in protos}):
-                X2 = torch.from_numpy(wl.make_activation(Md, K2, wl.seed_for(1, K2 % 97))).to(dev)
-                acts[K2] = bl.bitlinear_quant_act(X2)[:3]
-            outs = {L2.name: torch.empty((Md, L2.N), dtype=torch.float32, device=dev)
-                    for (L2, _, _) in protos}
-
-            def run_stream():
-                for layer in sets:
-                    for (L2, p2, b2) in layer:
-                        c_, g_, r_ = acts[L2.K]
-                        bl.bitlinear_matmul(c_, g_, r_, p2, L2.N, b2, out=outs[L2.name])
-
-            run_stream()
-            torch.cuda.synchronize()
-            mode = "eager launches"
-            timed = run_stream
-            try:
-                side = torch.cuda.Stream()
-                side.wait_stream(torch.cuda.current_stream())
-                with torch.cuda.stream(side):
-                    run_stream()
-                torch.cuda.current_stream().wait_stream(side)
-                graph = torch.cuda.CUDAGraph()
-                with torch.cuda.graph(graph):
-                    run_stream()
-                ref = {k: v.clone() for k, v in outs.items()}
-                graph.replay()
-                torch.cuda.synchronize()
-                if all(torch.equal(ref[k], outs[k]) for k in outs):
-                    timed, mode = graph.replay, "one HIP graph of all launches, replayed"
-            except Exception as exc:  # capture unavailable: time the eager launches
-                mode = f"eager launches (graph capture failed: {type(exc).__name__})"
-            timed()
-            t = event_ms(timed, 5, torch)
-            nbytes = sum(gemm_bytes(Md, L2.K, L2.N) for layer in sets for (L2, _, _) in layer)
-            stream.append(dict(M=Md, launches=len(sets) * len(protos), us=t * 1e3,
-                               us_per_launch=t * 1e3 / (len(sets) * len(protos)),
-                               gbs=nbytes / (t * 1e-3) / 1e9,
-                               frac_hbm=nbytes / (t * 1e-3) / 1e9 / HBM_PEAK_GBS, launch=mode))
-        decode["layer_stream_1p3b"] = stream
-
-        # One decoding step of the 24-layer stack: LN + quantise + GEMM + dequant through QKV, O,
-        # up and down of every layer, each input being the previous output (the attention and the
-        # non-linearity between them are left out: only their place in the chain matters here).
-        # Four stacks of distinct weights, one HIP graph each, replayed in turn.
-        block = []
-        for Md in (1, 4, 16):
-            h0 = torch.from_numpy(wl.make_activation(Md, 2048, wl.seed_for(1, 50))).to(dev)
-            bufs = {L2.name: torch.empty((Md, L2.N), dtype=torch.float32, device=dev)
-                    for (L2, _, _) in protos}
-            wss = {L2.name: torch.empty(bl.workspace_bytes(bl.OP_FORWARD, Md, L2.N, L2.K),
-                                        dtype=torch.uint8, device=dev) for (L2, _, _) in protos}
-
-            def run_stack(layers24):
-                h = h0
-                for layer in layers24:
-                    for (L2, p2, b2) in layer:
-                        x_in = h if h.shape[1] == L2.K else h.view(-1)[:Md * L2.K].view(Md, L2.K)
-                        h = bl.bitlinear_forward(x_in, p2, L2.N, b2, out=bufs[L2.name],
-                                                 workspace=wss[L2.name])
-                return h
-
-            stacks = [sets[i * 24:(i + 1) * 24] for i in range(4)]
-            ref = run_stack(stacks[0]).clone()
-            torch.cuda.synchronize()
-            mode = "eager launches"
-            runners = [lambda st=st: run_stack(st) for st in stacks]
-            try:
-                graphs = []
-                for st in stacks:
-                    side = torch.cuda.Stream()
-                    side.wait_stream(torch.cuda.current_stream())
-                    with torch.cuda.stream(side):
-                        run_stack(st)
-                    torch.cuda.current_stream().wait_stream(side)
-                    g2 = torch.cuda.CUDAGraph()
-                    with torch.cuda.graph(g2):
-                        run_stack(st)
-                    graphs.append(g2)
-                graphs[0].replay()
-                torch.cuda.synchronize()
-                if torch.equal(ref, bufs["down"]):
-                    runners, mode = [g2.replay for g2 in graphs], "one HIP graph per stack, replayed"
-            except Exception as exc:
-                mode = f"eager launches (graph capture failed: {type(exc).__name__})"
-
-            def run_all():
-                for r in runners:
-                    r()
-
-            run_all()
-            t = event_ms(run_all, 5, torch) / len(runners)
-            nbytes = sum(gemm_bytes(Md, L2.K, L2.N) + 5 * Md * L2.K for (L2, _, _) in protos) * 24
-            # one token with K <= 32768: the GEMM launch quantises the row itself (one launch a
-            # layer); otherwise quantiser + GEMM
-            n_launch = 24 * sum(1 if Md == 1 and L2.K <= 32768 else 2 for (L2, _, _) in protos)
-            block.append(dict(M=Md, layers=24, launches=n_launch, us_per_step=t * 1e3,
-                              us_per_launch=t * 1e3 / n_launch,
-                              gbs=nbytes / (t * 1e-3) / 1e9, launch=mode))
-        decode["block_decode_1p3b"] = block
-        del sets, protos
-
-        # The same chain at the 30B shapes (with the 7168 -> 7168 output projection added), one
-        # token: eight distinct layers (0.6 GB of packed weights) in one HIP graph, one launch per
-        # projection (the GEMM kernel quantises the row itself).
-        protos3 = []
-        for li, L3 in enumerate(list(c3.layers[:1]) + [wl.Layer("o", 7168, 7168)] + list(c3.layers[1:])):
-            W3 = wl.make_weight(L3.N, L3.K, c3.w_std, wl.seed_for(3, 10 + li))
-            p3, _, b3 = bl.bitlinear_pack_weights(torch.from_numpy(W3).to(dev))
-            protos3.append((L3, p3, b3))
-            del W3
-        layers8 = [[(L3, p3.clone(), b3) for (L3, p3, b3) in protos3] for _ in range(8)]
-        h0 = torch.from_numpy(wl.make_activation(1, 7168, wl.seed_for(3, 50))).to(dev)
-        bufs3 = {L3.name: torch.empty((1, L3.N), dtype=torch.float32, device=dev) for (L3, _, _) in protos3}
-        wss3 = {L3.name: torch.empty(bl.workspace_bytes(bl.OP_FORWARD, 1, L3.N, L3.K), dtype=torch.uint8,
-                                     device=dev) for (L3, _, _) in protos3}
-
-        def run_stack3():
-            h = h0
-            for layer in layers8:
-                for (L3, p3, b3) in layer:
-                    x_in = h if h.shape[1] == L3.K else h.view(-1)[:L3.K].view(1, L3.K)
-                    h = bl.bitlinear_forward(x_in, p3, L3.N, b3, out=bufs3[L3.name], workspace=wss3[L3.name])
-            return h
-
-        ref3 = run_stack3().clone()
-        torch.cuda.synchronize()
-        timed3, mode3 = run_stack3, "eager launches"
-        try:
-            side = torch.cuda.Stream()
-            side.wait_stream(torch.cuda.current_stream())
-            with torch.cuda.stream(side):
-                run_stack3()
-            torch.cuda.current_stream().wait_stream(side)
-            g3 = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g3):
-                run_stack3()
-            g3.replay()
-            torch.cuda.synchronize()
-            if torch.equal(ref3, bufs3["down"]):
-                timed3, mode3 = g3.replay, "one HIP graph of eight layers, replayed"
-        except Exception as exc:
-            mode3 = f"eager launches (graph capture failed: {type(exc).__name__})"
-        timed3()
-        t3 = event_ms(timed3, 5, torch) / 8
-        nbytes3 = sum(gemm_bytes(1, L3.K, L3.N) + 5 * L3.K for (L3, _, _) in protos3)
-        decode["block_decode_30b"] = dict(M=1, layers=8, us_per_layer=t3 * 1e3, gbs=nbytes3 / (t3 * 1e-3) / 1e9,
-                                          launch=mode3)
-        del layers8, protos3
+        if not args.no_decode_stacks:
+            decode_stacks(bl, torch, dev, decode)
         decode["value"] = best["gbs"]
         decode["unit"] = "GB/s"
         decode["roofline"] = dict(bound="hbm", kernel="gemm_decode_kernel", achieved=best["gbs"],
                                   peak=HBM_PEAK_GBS, unit="GB/s", frac=best["gbs"] / HBM_PEAK_GBS,
                                   traffic=None,
-                                  note="events around back-to-back launches: includes dispatch gaps")
+                                  note="launches replayed back to back from one HIP graph over rotating "
+                                       "weight copies; read_floor is the same bytes only read")
 
     # ---- training-step leg: forward + STE backward (Section 2.2) at M = 8192, 4096 -> 16384 ----
     # Weights change every step, so the step starts from fp32 W: pack (Eq. 1-3), forward
@@ -460,12 +547,6 @@ def main():
     cpu = None
     if not args.no_cpu:
         threads = oracle.num_threads()
-        signs = [sign]
-        betas = [b]
-        for d in layers[1:]:
-            a_l, b_l = oracle.weight_stats(d["W"])
-            signs.append(oracle.binarize(d["W"], a_l))
-            betas.append(b_l)
         per_row = 0.0
         for d, sg in zip(layers, signs):
             xh = oracle.layernorm(d["X"][:8])
@@ -522,9 +603,13 @@ def main():
         "kernels": kern, "roofline": roof, "weight_prep": prep, "decode": decode, "training": train, "energy_model": energy_model,
         "cpu_baseline": cpu, "parity": parity,
     }
-    print(json.dumps(out))
-    if parity != "ok":
+    if parity != "ok":  # no number without parity
+        for key in ("value", "mfma_frac_of_peak"):
+            out[key] = None
+        out["roofline"] = dict(out["roofline"], achieved=None, frac=None)
+        print(json.dumps(out))
         sys.exit(1)
+    print(json.dumps(out))
 
 
 if __name__ == "__main__":

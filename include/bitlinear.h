@@ -258,11 +258,21 @@ int bitlinear_forward_nonneg(const float* X, int64_t M, int64_t K, const void* p
  *   dX       out  fp32 [M,K] or NULL; may be the same buffer as dXhat
  *   dgain, dbias  out fp32 [K] or NULL; they need the workspace
  *                 (bitlinear_workspace_bytes_grouped(BL_OP_LN_BACKWARD, M, N, K, 1, groups_k, 0))
- * K/groups_k up to 16384 (else BL_ERR_UNSUPPORTED). */
+ * Any K / groups_k that is a multiple of 32 (rows of more than 16384 elements are walked
+ * from memory in three passes instead of being held in registers). */
 int bitlinear_layernorm_backward(const float* dXhat, const float* X, int64_t M, int64_t K,
                                  int groups_k, const float* ln_gain, float ln_eps, float* dX,
                                  float* dgain, float* dbias, void* workspace,
                                  size_t workspace_bytes, void* stream);
+
+/* Measurement aid, no part of the layer: one launch that only reads `bytes` (a multiple of 16)
+ * of device memory at `src` with the access pattern of the small-batch GEMM's weight stream
+ * (16-byte streaming loads, `workgroups` x `threads` lanes sharing the range evenly) and
+ * discards them.  Its duration is the floor for any kernel that has to fetch the same bytes,
+ * which is what a decode-shape GEMM is measured against.  sink: uint32 [workgroups] or NULL,
+ * never written for real data.  threads: a multiple of 64 up to 1024. */
+int bitlinear_probe_read(const void* src, size_t bytes, int workgroups, int threads, uint32_t* sink,
+                         void* stream);
 
 /* host: launch-time switches for tests and benchmarks; results never depend on them.
  * spec = "name=value,name=value" (integers); every switch not named returns to 0 = the

@@ -12,5 +12,5 @@ from .binding import (  # noqa: F401
     workspace_bytes_grouped,
     bitlinear_forward_nonneg, bitlinear_matmul_nonneg, bitlinear_quant_act_nonneg,
     bitlinear_weight_rowsums, forward_workspace_layout, set_tuning,
-    bitlinear_forward_static,
+    bitlinear_forward_static, probe_read,
 )

@@ -29,7 +29,7 @@ EXPORTS = (
     "bitlinear_quant_act_grouped", "bitlinear_forward_grouped", "bitlinear_layernorm_backward",
     "bitlinear_weight_rowsums", "bitlinear_quant_act_nonneg", "bitlinear_matmul_nonneg",
     "bitlinear_forward_nonneg", "bitlinear_forward_workspace_layout", "bitlinear_set_tuning",
-    "bitlinear_forward_static",
+    "bitlinear_forward_static", "bitlinear_probe_read",
 )
 
 _lib = None
@@ -93,6 +93,8 @@ def load_library() -> ctypes.CDLL:
                                              vp, sz, vp]
     lib.bitlinear_forward_static.restype = ci
     lib.bitlinear_forward_static.argtypes = [vp, i64, i64, vp, i64, vp, vp, vp, cf, ci, u32, vp, vp]
+    lib.bitlinear_probe_read.restype = ci
+    lib.bitlinear_probe_read.argtypes = [vp, sz, ci, ci, vp, vp]
     lib.bitlinear_forward_workspace_layout.restype = ci
     lib.bitlinear_forward_workspace_layout.argtypes = [i64, i64, i64, ci, ctypes.POINTER(sz)]
     lib.bitlinear_set_tuning.restype = ci
@@ -251,6 +253,13 @@ def bitlinear_forward_static(X: torch.Tensor, packed: torch.Tensor, N: int, beta
         _ptr(ln_gain, torch.float32), _ptr(ln_bias, torch.float32), ln_eps, _gran(per_tensor),
         flags, _ptr(out), _stream()), "bitlinear_forward_static")
     return out
+
+
+def probe_read(buf: torch.Tensor, workgroups: int = 256, threads: int = 448) -> None:
+    """One launch that only reads `buf` (see bitlinear_probe_read): the floor a weight-streaming
+    kernel is measured against."""
+    _check(load_library().bitlinear_probe_read(_ptr(buf), buf.numel() * buf.element_size(), workgroups,
+                                               threads, None, _stream()), "bitlinear_probe_read")
 
 
 def bitlinear_backward_ste(dY: torch.Tensor, codes: torch.Tensor, gamma: torch.Tensor,

@@ -646,6 +646,15 @@ int bitlinear_layernorm_backward(const float* dXhat, const float* X, int64_t M, 
     return check_hip(launch_ln_backward(a, dgain, dbias, partials, (hipStream_t)stream));
 }
 
+int bitlinear_probe_read(const void* src, size_t bytes, int workgroups, int threads, uint32_t* sink,
+                         void* stream) {
+    if (bytes < 16 || bytes % 16 || workgroups < 1 || workgroups > 65536 || threads < 64 ||
+        threads > 1024 || threads % 64)
+        return BL_ERR_SHAPE;
+    if (!src) return BL_ERR_NULL;
+    return check_hip(launch_read_probe(src, bytes, workgroups, threads, sink, (hipStream_t)stream));
+}
+
 const char* bitlinear_status_string(int status) {
     switch (status) {
         case BL_OK: return "ok";

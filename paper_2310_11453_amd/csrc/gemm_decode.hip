@@ -495,6 +495,36 @@ size_t gemm_split_ws_bytes(int64_t M, int64_t N, int64_t K) {
     return (size_t)splits * (size_t)M * (size_t)N * 4;
 }
 
+// Measurement aid: reads `bytes` of device memory the way the small-batch kernel streams its
+// weight tiles (16-byte nontemporal loads, a wave takes 1 KiB at a time, the workgroups share the
+// range evenly, kDepth loads in flight per lane) and does nothing else.  What such a launch takes
+// is the floor for any kernel that has to bring the same bytes in from HBM.
+__global__ __launch_bounds__(1024) void read_probe_kernel(const v4i* __restrict__ src, int64_t n16,
+                                                          uint32_t* sink) {
+    constexpr int kDepth = 4;
+    const int64_t per = (n16 + gridDim.x - 1) / gridDim.x;  // 16-byte pieces per workgroup
+    const int64_t lo = per * blockIdx.x, hi = lo + per < n16 ? lo + per : n16;
+    v4i x = {0, 0, 0, 0};
+    for (int64_t i = lo + threadIdx.x; i < hi; i += (int64_t)blockDim.x * kDepth) {
+        v4i v[kDepth];
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) {
+            const int64_t j = i + (int64_t)d * blockDim.x;
+            v[d] = __builtin_nontemporal_load(src + (j < hi ? j : hi - 1));
+        }
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) x ^= v[d];
+    }
+    // never true for the all-ones pattern no weight blob holds in every lane; keeps the loads alive
+    if ((x[0] & x[1] & x[2] & x[3]) == -1 && sink) sink[blockIdx.x] = 1u;
+}
+hipError_t launch_read_probe(const void* src, size_t bytes, int workgroups, int threads,
+                             uint32_t* sink, hipStream_t s) {
+    read_probe_kernel<<<(unsigned)workgroups, (unsigned)threads, 0, s>>>(
+        reinterpret_cast<const v4i*>(src), (int64_t)(bytes / 16), sink);
+    return hipGetLastError();
+}
+
 void launch_splitk_reduce(const GemmArgs& a, int splits, hipStream_t s) {
     splitk_reduce<<<(unsigned)((a.M * a.N + 255) / 256), 256, 0, s>>>(a, splits);
 }

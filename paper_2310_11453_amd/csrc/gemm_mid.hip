@@ -1,15 +1,24 @@
 // 1-bit x 8-bit GEMM + dequantisation for a few dozen tokens (16 < M <= 64), Eq. 7 and Eq. 11
 // of arXiv 2310.11453: the batch between the weight-streaming kernel (M <= 16) and the large
 // MFMA tiles.  One 64 x 128 output tile per workgroup gives at most a few hundred workgroups,
-// each with a long serial walk over K, and a four-wave workgroup takes about 225 ns per 64-k
-// stage whatever the MFMA rate (LDS round trips, a DMA wait and a barrier per stage against
-// four MFMAs per wave).  So the walk is split INSIDE the workgroup: eight waves, four K-groups
-// of two waves (64 x 64 each), each group streaming its own quarter of K through its own LDS
-// ring exactly as the large kernel does (codes and packed bits by global_load_lds, bits
-// expanded in registers, hand-counted vmcnt; see gemm_prefill.hip), all groups meeting at the
-// same barriers: about 0.5 us for four stages.  The integer accumulators of the four groups
-// are added through LDS at the end and one epilogue dequantises: the same integers as any
-// other split of K, so the result does not depend on it.
+// each with a long serial walk over K, so the walk is split INSIDE the workgroup: eight waves,
+// four K-groups of two waves (64 x 64 each), each group streaming its own quarter of K through
+// its own LDS ring (codes and packed bits by global_load_lds, bits expanded in registers,
+// hand-counted vmcnt), all groups meeting at the same barriers.  The integer accumulators of
+// the four groups are added through LDS at the end and one epilogue dequantises: the same
+// integers as any other split of K, so the result does not depend on it.
+//
+// What bounds this shape is the stream of activation codes from L2 into LDS: every workgroup
+// reads all M x K of them (64 bytes per k against 16 bytes of packed weights), 100 MB per launch
+// at the 30B shapes.  L2 serves whole 128-byte lines, so a stage holds 128 k: a row of a stage
+// is one line, and the eight lanes that fetch it sit in one DMA instruction.  (With 64-k stages
+// every line was requested twice, half of it each time, and the kernel ran at the L2's request
+// rate: 1.79 M requests of 128 bytes per launch for 128 MB of operands.)
+//
+// A wave expands its weight bits to {0,1} operand bytes with two vector ALU operations per dword,
+// for an operand that only two MFMAs use.  That work sits between the MFMAs of the half-step
+// before (the compiler's scheduler is told so with sched_group_barrier), two half-steps ahead of
+// its use, so a wave keeps the matrix pipe fed without help from the other wave of its SIMD.
 #include "common.h"
 #include "kernels.h"
 #include "ring.h"
@@ -18,18 +27,20 @@ namespace bl {
 
 namespace mid {
 constexpr int BM = 64, BN = 128, KG = 4, WN = 2;
-constexpr int THREADS = KG * WN * kWave;  // 512
-constexpr int GT = WN * kWave;            // threads of a K-group
-constexpr int STAGE_BYTES = BM * 64;      // 64 rows x 64 k
-constexpr int P = BM * 4 / GT;            // 16-byte DMA pieces per thread and stage: 2
-constexpr int NBW = (BN / 16) / WN;       // packed tiles per wave and chunk: 4
-static_assert(P == 2 && NBW == 4, "tile shape");
+constexpr int THREADS = KG * WN * kWave;      // 512
+constexpr int GT = WN * kWave;                // threads of a K-group
+constexpr int STAGE_K = 128;                  // k per stage: a row of a stage is one 128-byte line
+constexpr int STAGE_BYTES = BM * STAGE_K;     // 8 KiB
+constexpr int P = BM * (STAGE_K / 16) / GT;   // 16-byte DMA pieces per thread and stage: 4
+constexpr int NBW = (BN / 16) / WN;           // packed tiles per wave and chunk: 4
+constexpr int SPC = kChunkK / STAGE_K;        // stages per 512-chunk: 4
+static_assert(P == 4 && NBW == 4 && SPC == 4, "tile shape");
 
 // operands of one half-step (rows j and 32 + j of the stage), complete on exit
 __device__ inline void read_a(v4i (&a)[2], uint32_t ad) {
     asm volatile(
         "ds_read_b128 %0, %2\n\t"
-        "ds_read_b128 %1, %2 offset:2048\n\t"
+        "ds_read_b128 %1, %2 offset:4096\n\t"
         "s_waitcnt lgkmcnt(0)"
         : "=&v"(a[0]), "=&v"(a[1])
         : "v"(ad));
@@ -45,29 +56,25 @@ __device__ inline void read_bits(v4i (&bw)[2][2], uint32_t ad) {
         : "=&v"(bw[0][0]), "=&v"(bw[0][1]), "=&v"(bw[1][0]), "=&v"(bw[1][1])
         : "v"(ad));
 }
-// acc[mi][s] += ac[mi] x b[s]; an = operands at `ad`, complete on exit
-__device__ inline void half_step(v16i (&acc)[2][2], const v4i (&ac)[2], const v4i (&b)[2],
-                                 v4i (&an)[2], uint32_t ad) {
+// The LDS reads stay in asm (a read the compiler can see makes it wait for every DMA in flight).
+// lds_issue starts the reads of the next half-step's operands; they become valid at lds_wait,
+// which ties the registers so that nothing the compiler schedules can use them earlier.
+__device__ inline void lds_issue(v4i (&a)[2], uint32_t ad) {
     asm volatile(
-        "ds_read_b128 %4, %10\n\t"
-        "ds_read_b128 %5, %10 offset:2048\n\t"
-        "s_nop 1\n\t"
-        "v_mfma_i32_32x32x32_i8 %0, %6, %8, %0\n\t"
-        "v_mfma_i32_32x32x32_i8 %1, %6, %9, %1\n\t"
-        "v_mfma_i32_32x32x32_i8 %2, %7, %8, %2\n\t"
-        "v_mfma_i32_32x32x32_i8 %3, %7, %9, %3\n\t"
-        "s_waitcnt lgkmcnt(0)"
-        : "+v"(acc[0][0]), "+v"(acc[0][1]), "+v"(acc[1][0]), "+v"(acc[1][1]), "=&v"(an[0]),
-          "=&v"(an[1])
-        : "v"(ac[0]), "v"(ac[1]), "v"(b[0]), "v"(b[1]), "v"(ad));
+        "ds_read_b128 %0, %2\n\t"
+        "ds_read_b128 %1, %2 offset:4096"
+        : "=&v"(a[0]), "=&v"(a[1])
+        : "v"(ad));
+}
+__device__ inline void lds_wait(v4i (&a)[2]) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a[0]), "+v"(a[1]));
 }
 }  // namespace mid
 
 // Work item = (column tile, K-slice): blockIdx.x = slice * grid_n + tile.  With a.split_k the
 // slice's partial sums 2 * sum_k q b go to a.split_ws and splitk_reduce finishes; otherwise the
 // workgroup owns all of K and writes Y.
-// NS = stages in each group's ring (six instead of four changes nothing: the pace is set by
-// each wave's own instruction chain per stage, not by the DMA latency).
+// NS = stages in each group's ring.
 template <int NS>
 __global__ __launch_bounds__(mid::THREADS) void gemm_mid_kernel(GemmArgs a, int grid_n) {
     using namespace mid;
@@ -75,6 +82,7 @@ __global__ __launch_bounds__(mid::THREADS) void gemm_mid_kernel(GemmArgs a, int 
     __shared__ __attribute__((aligned(1024))) uint8_t smA[KG * NS * STAGE_BYTES];
     __shared__ __attribute__((aligned(1024))) uint8_t smB[KG * (BN / 16) * 1024];
     static_assert(KG * NS * STAGE_BYTES >= 2 * BM * BN * 4, "room for the reduction");
+    static_assert(NS >= 4, "the wait bookkeeping below: a stage's codes are requested NS-1 >= 3 stages ahead");
 
     // wave-uniform values in scalar registers: the loop below branches on them
     const int w = __builtin_amdgcn_readfirstlane((int)threadIdx.x / kWave), l = threadIdx.x % kWave;
@@ -109,7 +117,7 @@ __global__ __launch_bounds__(mid::THREADS) void gemm_mid_kernel(GemmArgs a, int 
         const int64_t d = TKi * (g + 1) / KG - TKi * g / KG;
         TKmax = d > TKmax ? d : TKmax;
     }
-    const int nrun = (int)TKmax * 8;
+    const int nrun = (int)TKmax * SPC;
 
     // ---- epilogue operands of this thread's outputs, requested now ---------------------------
     // thread -> columns nq .. nq+3 of the tile, rows er + 16 h
@@ -135,7 +143,10 @@ __global__ __launch_bounds__(mid::THREADS) void gemm_mid_kernel(GemmArgs a, int 
         e_ws[c] = *(a.eta ? a.wsum + n : a.rowsum);
     }
 
-    // ---- DMA of this group: thread -> one 16-byte piece of a stage; wave -> two bit tiles ----
+    // ---- DMA of this group.  A stage is 64 rows of 128 bytes; thread -> four 16-byte pieces of
+    // it, piece = (row, physical segment).  The eight lanes of a row sit in one instruction, so
+    // the row's line is requested once.  Segments are XOR-swizzled with (row / 2) % 8: the
+    // 16-byte operand reads of 16 consecutive rows then touch every LDS bank exactly once.
     uint8_t* const ringA = smA + kg * (NS * STAGE_BYTES);
     uint8_t* const ringB = smB + kg * ((BN / 16) * 1024);
     const int8_t* gsrc[P];
@@ -143,8 +154,8 @@ __global__ __launch_bounds__(mid::THREADS) void gemm_mid_kernel(GemmArgs a, int 
 #pragma unroll
     for (int q = 0; q < P; ++q) {
         const int slot = q * GT + tg;
-        int row = slot >> 2;
-        gseg[q] = ((slot & 3) ^ ((row >> 2) & 3)) * 16;
+        int row = slot >> 3;
+        gseg[q] = ((slot & 7) ^ ((row >> 1) & 7)) * 16;
         if (row > M - 1) row = (int)(M - 1);
         gsrc[q] = a.codes + (int64_t)row * a.ldq + k0 + gseg[q];
     }
@@ -156,12 +167,14 @@ __global__ __launch_bounds__(mid::THREADS) void gemm_mid_kernel(GemmArgs a, int 
         bsrc[q] = a.packed + tile_dword_offset(tn, k0 / kChunkK, TKp) + l * 4;
     }
     const uint32_t lds_wave = (uint32_t)(wn * kWave * 16);
+    // clamp: a stage that may reach past the group's K re-reads the last 16 valid bytes of the
+    // row instead (the packed bits there are zero, or masked)
     auto issue = [&](int st, bool clamp) {
 #pragma unroll
         for (int q = 0; q < P; ++q) {
-            const int8_t* src = gsrc[q] + (int64_t)st * 64;
+            const int8_t* src = gsrc[q] + (int64_t)st * STAGE_K;
             if (clamp) {
-                const int64_t k = (int64_t)st * 64 + gseg[q];
+                const int64_t k = (int64_t)st * STAGE_K + gseg[q];
                 if (k > K - 16) src -= k - (K - 16);
             }
             __builtin_amdgcn_global_load_lds(
@@ -181,10 +194,13 @@ __global__ __launch_bounds__(mid::THREADS) void gemm_mid_kernel(GemmArgs a, int 
 
     const uint32_t b_lane = (uint32_t)(uintptr_t)ringB + ((wn * 64 + j) >> 4) * 1024 +
                             (g2 * 16 + (j & 15)) * 16;
-    const int sw = (j >> 2) & 3;
-    const uint32_t a_lane[2] = {(uint32_t)(uintptr_t)ringA + j * 64 + ((g2) ^ sw) * 16,
-                                (uint32_t)(uintptr_t)ringA + j * 64 + ((2 + g2) ^ sw) * 16};
-    auto a_addr = [&](int st, int h) { return a_lane[h] + (uint32_t)((st % NS) * STAGE_BYTES); };
+    // lane (j, g2) reads logical segment 2 hs + g2 of row j in half-step hs of a stage
+    const int sw = (j >> 1) & 7;
+    uint32_t a_lane[4];
+#pragma unroll
+    for (int hs = 0; hs < 4; ++hs)
+        a_lane[hs] = (uint32_t)(uintptr_t)ringA + j * STAGE_K + ((2 * hs + g2) ^ sw) * 16;
+    auto a_addr = [&](int st, int hs) { return a_lane[hs] + (uint32_t)((st % NS) * STAGE_BYTES); };
 
     v16i acc[2][2];
 #pragma unroll
@@ -193,16 +209,11 @@ __global__ __launch_bounds__(mid::THREADS) void gemm_mid_kernel(GemmArgs a, int 
         for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mi][s2][r] = 0;
-    // plane i of half h of chunk c as {0,1} bytes; nothing past the group's last chunk
-    v4i bw[2][2];
-    auto expand = [&](v4i (&b)[2], int h, int i, int64_t c) {
-        const uint32_t m01 = c < TK ? 0x01010101u : 0u;
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-            for (int d = 0; d < 4; ++d) b[s2][d] = (int)(((uint32_t)bw[s2][h][d] >> i) & m01);
-    };
-    v4i ax[2], ay[2], bx[2], by[2];
+    // Packed bits of the current chunk and of the next one; plane i of half h of a chunk as {0,1}
+    // bytes, nothing past the group's last chunk.  Half-step u of a chunk (plane u / 2, half u % 2)
+    // multiplies A[u % 2] by B[u % 4], starts the LDS reads of A[(u + 1) % 2] and builds B[(u + 2) % 4].
+    v4i bw[2][2], bwn[2][2];
+    v4i A[2][2], B[4][2];
     const bool has_k = TK > 0;  // a group without chunks requests nothing and multiplies by zero
 
     if (has_k) {
@@ -213,32 +224,74 @@ __global__ __launch_bounds__(mid::THREADS) void gemm_mid_kernel(GemmArgs a, int 
     wait_vmcnt<(NS - 2) * P>();  // younger than stage 0: stages 1 .. NS-2
     block_barrier();
     read_bits(bw, b_lane);
-    read_a(ax, a_addr(0, 0));
-    expand(bx, 0, 0, 0);
-    // Stage st = 8 c + i, bit plane i of the group's chunk c.  The asm blocks run unconditionally
-    // (a branch around one would make the compiler shuffle their registers at every join); only
-    // DMA requests and the choice of wait depend on where the group is.  DMA bookkeeping as in
-    // the large kernel: at the mid-stage wait the operations younger than stage st+1 are those of
-    // stages st+2 .. st+NS-2 and, while the bits of the next chunk (requested at i == 2, read
-    // at i == 7) are among them, those too.
+    read_a(A[0], a_addr(0, 0));
+    {
+        const uint32_t m01 = 0 < TK ? 0x01010101u : 0u;
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+                for (int d = 0; d < 4; ++d) B[h][s2][d] = (int)((uint32_t)bw[s2][h][d] & m01);
+    }
+
+    // DMA bookkeeping: at the wait of stage st the operations younger than stage st+1 are those of
+    // stages st+2 .. st+NS-2 and the bits of the next chunk while they may still be on their way:
+    // they are requested in stage 0 of a chunk BEHIND that stage's codes (the buffer is free once
+    // every wave has read the current chunk's bits, one barrier earlier), so they are younger than
+    // what the waits of stages 1 and 2 are for, and the wait of stage 3, which is for a group
+    // requested after them, covers them: three stages for a trip to HBM, then they are read.
     for (int64_t c = 0; c < TKmax; ++c) {
-        static_for<0, 8>([&](auto ic) {
-            constexpr int i = decltype(ic)::value;
-            const int st = (int)c * 8 + i;
-            const bool ahead = st + NS - 1 < nrun;
-            const bool bits_next = has_k && c + 1 < TK;
-            expand(by, 1, i, c);
-            half_step(acc, ax, bx, ay, a_addr(st, 1));
-            if (!ahead) wait_vmcnt<0>();
-            else if (bits_next && i >= 3 && i <= NS - 1 && i <= 6) wait_vmcnt<(NS - 3) * P + NBW>();
-            else wait_vmcnt<(NS - 3) * P>();
-            block_barrier();
-            if (i == 7) read_bits(bw, b_lane);
-            if (i == 2 && bits_next) issue_bits(c + 1);
-            if (ahead && has_k) issue(st + NS - 1, (int64_t)(st + NS) * 64 > K);  // clamp only past K
-            expand(bx, 0, (i + 1) & 7, i == 7 ? c + 1 : c);
-            half_step(acc, ay, by, ax, a_addr(st + 1, 0));
+        const bool bits_next = has_k && c + 1 < TK;
+        static_for<0, 16>([&](auto uc) {
+            constexpr int u = decltype(uc)::value;
+            constexpr int s = u >> 2, hs = u & 3;
+            const int st = (int)c * SPC + s;
+            if constexpr (hs == 2) {  // mid-stage: stage st+1 becomes readable, stage st-1's buffer free
+                const bool ahead = st + NS - 1 < nrun;
+                if (!ahead) wait_vmcnt<0>();
+                else if (bits_next && (s == 1 || s == 2)) wait_vmcnt<(NS - 3) * P + NBW>();
+                else wait_vmcnt<(NS - 3) * P>();
+                block_barrier();
+                if (s == 3) read_bits(bwn, b_lane);
+                if (ahead && has_k) issue(st + NS - 1, (int64_t)(st + NS) * STAGE_K > K);  // clamp only past K
+                if (s == 0 && bits_next) issue_bits(c + 1);
+            }
+            constexpr int u2 = u + 2;  // the operand built in this half-step
+            constexpr int i2 = (u2 >> 1) & 7, h2 = u2 & 1;
+            v4i(&src)[2][2] = u2 >= 16 ? bwn : bw;
+            const uint32_t m01 = (u2 >= 16 ? c + 1 : c) < TK ? 0x01010101u : 0u;
+            v4i(&an)[2] = A[(u + 1) & 1];
+            v4i(&bn)[2] = B[u2 & 3];
+            lds_issue(an, a_addr(hs == 3 ? st + 1 : st, (hs + 1) & 3));
+            // the bits pass through an (empty) asm placed after the reads, and the new operand
+            // through one at the end: the expansion can neither be moved ahead of this half-step
+            // nor be left for a later one before the scheduler sees the groups below
+            asm volatile("" : "+v"(src[0][h2]), "+v"(src[1][h2]));
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2) {
+                    acc[mi][s2] = __builtin_amdgcn_mfma_i32_32x32x32_i8(A[u & 1][mi], B[u & 3][s2],
+                                                                        acc[mi][s2], 0, 0, 0);
+                    const int q = mi * 2 + s2;  // two of the eight dwords of the new operand per MFMA
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        const int d = (q & 1) * 2 + e, sn = q >> 1;
+                        bn[sn][d] = (int)(((uint32_t)src[sn][h2][d] >> i2) & m01);
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+                }
+            asm volatile("" : "+v"(bn[0]), "+v"(bn[1]));
+            __builtin_amdgcn_sched_barrier(0);
+            lds_wait(an);
         });
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) bw[s2][h] = bwn[s2][h];
     }
     // the accumulators were last written inside an asm block: let the matrix pipeline retire
     // them before ordinary instructions read them

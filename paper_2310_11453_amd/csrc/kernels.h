@@ -111,6 +111,8 @@ bool gemm_decode_fuses_quant(int64_t M, int64_t K, int64_t N);
 size_t gemm_split_ws_bytes(int64_t M, int64_t N, int64_t K);
 int64_t prefill_split_tiles(int64_t M, int64_t N, int64_t K);
 void launch_splitk_reduce(const GemmArgs& a, int splits, hipStream_t s);
+hipError_t launch_read_probe(const void* src, size_t bytes, int workgroups, int threads,
+                             uint32_t* sink, hipStream_t s);
 hipError_t launch_gemm_decode(const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm_prefill(const GemmArgs& a, hipStream_t s);
 hipError_t launch_gemm_mid(const GemmArgs& a, hipStream_t s);  // 16 < M <= 64

@@ -144,6 +144,106 @@ __global__ __launch_bounds__((WPR < 4 ? 4 : WPR) * kWave, 4) void ln_backward_ro
     }
 }
 
+// Rows too long for registers (K / groups > 16384): one workgroup of eight waves per row walks
+// the row from memory in each of the three passes (statistics, the two means, dx), the same
+// arithmetic per element; x and g of a row stay in L2 between the passes.
+__global__ __launch_bounds__(512) void ln_backward_long(LnBackwardArgs a) {
+    constexpr int NW = 8, T = NW * kWave;
+    __shared__ double smd[4][NW];
+    const int wave = threadIdx.x / kWave, t = threadIdx.x;
+    const bool lead = (threadIdx.x & (kWave - 1)) == 0;
+    const int64_t row = blockIdx.x;
+    const int64_t K4 = a.K / 4;
+    const float4* __restrict__ x4 = reinterpret_cast<const float4*>(a.X + row * a.K);
+    const float4* g4 = reinterpret_cast<const float4*>(a.g + row * a.K);  // may alias dX
+    const int grp = a.groups > 1 ? (int)(row % a.groups) : 0;
+    const float4* __restrict__ w4 =
+        a.gain ? reinterpret_cast<const float4*>(a.gain + grp * a.K) : nullptr;
+
+    const double c = (double)a.X[row * a.K];
+    double s = 0.0, q = 0.0;
+    for (int64_t idx = t; idx < K4; idx += T) {
+        const float4 v = x4[idx];
+        const double dx = (double)v.x, dy = (double)v.y, dz = (double)v.z, dw = (double)v.w;
+        s += (dx + dy) + (dz + dw);
+        q = fma(dx - c, dx - c, q);
+        q = fma(dy - c, dy - c, q);
+        q = fma(dz - c, dz - c, q);
+        q = fma(dw - c, dw - c, q);
+    }
+    s = wave_reduce(s, OpSum{});
+    q = wave_reduce(q, OpSum{});
+    if (lead) {
+        smd[0][wave] = s;
+        smd[1][wave] = q;
+    }
+    __syncthreads();
+    s = smd[0][0];
+    q = smd[1][0];
+#pragma unroll
+    for (int i = 1; i < NW; ++i) {
+        s += smd[0][i];
+        q += smd[1][i];
+    }
+    const double mu = s / (double)a.K;
+    const double var = fmax(q / (double)a.K - (mu - c) * (mu - c), 0.0);
+    const double rstd = 1.0 / sqrt(var + (double)a.eps);
+    if (a.rowstats && t == 0) {
+        a.rowstats[2 * row] = mu;
+        a.rowstats[2 * row + 1] = rstd;
+    }
+    if (!a.dX) return;
+
+    auto load = [&](int64_t idx, float4& xn, float4& gh) {
+        const float4 v = x4[idx];
+        gh = g4[idx];
+        if (w4) {
+            const float4 w = w4[idx];
+            gh.x *= w.x; gh.y *= w.y; gh.z *= w.z; gh.w *= w.w;
+        }
+        xn.x = (float)(((double)v.x - mu) * rstd);
+        xn.y = (float)(((double)v.y - mu) * rstd);
+        xn.z = (float)(((double)v.z - mu) * rstd);
+        xn.w = (float)(((double)v.w - mu) * rstd);
+    };
+    double c1 = 0.0, c2 = 0.0;
+    for (int64_t idx = t; idx < K4; idx += T) {
+        float4 xn, gh;
+        load(idx, xn, gh);
+        c1 += ((double)gh.x + (double)gh.y) + ((double)gh.z + (double)gh.w);
+        c2 = fma((double)gh.x, (double)xn.x, c2);
+        c2 = fma((double)gh.y, (double)xn.y, c2);
+        c2 = fma((double)gh.z, (double)xn.z, c2);
+        c2 = fma((double)gh.w, (double)xn.w, c2);
+    }
+    c1 = wave_reduce(c1, OpSum{});
+    c2 = wave_reduce(c2, OpSum{});
+    if (lead) {
+        smd[2][wave] = c1;
+        smd[3][wave] = c2;
+    }
+    __syncthreads();  // also: every read of g in the pass above is done before dX (= g) is written
+    c1 = smd[2][0];
+    c2 = smd[3][0];
+#pragma unroll
+    for (int i = 1; i < NW; ++i) {
+        c1 += smd[2][i];
+        c2 += smd[3][i];
+    }
+    const float m1 = (float)(c1 / (double)a.K), m2 = (float)(c2 / (double)a.K);
+    const float r = (float)rstd;
+    float4* d4 = reinterpret_cast<float4*>(a.dX + row * a.K);
+    for (int64_t idx = t; idx < K4; idx += T) {
+        float4 xn, gh, o;
+        load(idx, xn, gh);
+        o.x = r * ((gh.x - m1) - xn.x * m2);
+        o.y = r * ((gh.y - m1) - xn.y * m2);
+        o.z = r * ((gh.z - m1) - xn.z * m2);
+        o.w = r * ((gh.w - m1) - xn.w * m2);
+        d4[idx] = o;
+    }
+}
+
 // Column sums for the gain and bias gradients: thread = one float4 of columns of the full
 // token width (groups * K), workgroup row = a chunk of tokens; fp64 partials per chunk.
 __global__ __launch_bounds__(256) void ln_backward_affine_partial(LnBackwardArgs a, int64_t tokens,
@@ -189,7 +289,8 @@ __global__ __launch_bounds__(256) void ln_backward_affine_final(const double* __
     if (dbias) dbias[k] = (float)db;
 }
 
-bool ln_backward_supported(int64_t K) { return K % 4 == 0 && K / 4 <= 8 * kWave * 8; }
+bool ln_backward_supported(int64_t K) { return K % 4 == 0; }
+static bool ln_backward_in_registers(int64_t K) { return K / 4 <= 8 * kWave * 8; }
 
 int ln_backward_chunks(int64_t tokens) {
     int64_t c = (tokens + 127) / 128;
@@ -214,6 +315,10 @@ hipError_t launch_ln_backward(const LnBackwardArgs& a, float* dgain, float* dbia
     while (nv < per_lane) nv *= 2;
     if (wpr > 1 && nv < 8) nv = 8;
     auto rows = [&](const LnBackwardArgs& r) {
+        if (!ln_backward_in_registers(r.K)) {
+            ln_backward_long<<<(unsigned)r.M, 512, 0, s>>>(r);
+            return true;
+        }
 #define BL_LNB_CASE(W, V) if (wpr == W && nv == V) launch_rows<W, V>(r, s); else
         BL_LNB_CASE(1, 1) BL_LNB_CASE(1, 2) BL_LNB_CASE(1, 4) BL_LNB_CASE(1, 8)
         BL_LNB_CASE(2, 8) BL_LNB_CASE(4, 8) BL_LNB_CASE(8, 8)

@@ -279,12 +279,201 @@ __global__ __launch_bounds__((WPR < 4 ? 4 : WPR) * kWave, 4) void ln_quant_rows(
     }
 }
 
+// Rows too long for registers (K > 32768): one workgroup of eight waves per row walks the row
+// from memory in each pass (it stays in L2 between passes): sums with minimum and maximum,
+// then - only with a gain / bias or without LayerNorm, where the largest magnitude is not at
+// the minimum or maximum of the raw row - the absmax of the normalised values, then the
+// rounding pass.  The arithmetic per element and the order of the fp32 / fp64 operations that
+// decide a code are those of ln_quant_rows; only the summation order of the statistics
+// differs (each K is served by exactly one of the two kernels, so results stay deterministic).
+template <int MODE>
+__global__ __launch_bounds__(512) void ln_quant_long(QuantArgs a) {
+    constexpr int NW = 8, T = NW * kWave;
+    __shared__ double smd[2][NW];
+    __shared__ float smf[4][NW];
+    __shared__ int smi[NW];
+    const int wave = threadIdx.x / kWave, t = threadIdx.x;
+    const bool lead = (threadIdx.x & (kWave - 1)) == 0;
+    const int64_t row = blockIdx.x;
+    const int64_t K4 = a.K / 4;
+    const float4* __restrict__ x4 = reinterpret_cast<const float4*>(a.X + row * a.K);
+    const int grp = a.groups > 1 ? (int)(row % a.groups) : 0;
+    const bool affine = a.gain != nullptr || a.bias != nullptr;
+    bool have_amax = false;
+    float amax = 0.f, lo = 0.f;
+    double mu = 0.0, rstd = 1.0;
+
+    if (!a.skip_ln) {
+        if constexpr (MODE == kApply) {
+            mu = a.rowstats[2 * row];
+            rstd = a.rowstats[2 * row + 1];
+        } else {
+            const double c = (double)a.X[row * a.K];
+            double s = 0.0, q = 0.0;
+            float mn = a.X[row * a.K], mx = mn;
+            for (int64_t idx = t; idx < K4; idx += T) {
+                const float4 v = x4[idx];
+                const double dx = (double)v.x, dy = (double)v.y, dz = (double)v.z, dw = (double)v.w;
+                s += (dx + dy) + (dz + dw);
+                q = fma(dx - c, dx - c, q);
+                q = fma(dy - c, dy - c, q);
+                q = fma(dz - c, dz - c, q);
+                q = fma(dw - c, dw - c, q);
+                mn = fminf(fminf(mn, v.x), fminf(fminf(v.y, v.z), v.w));
+                mx = fmaxf(fmaxf(mx, v.x), fmaxf(fmaxf(v.y, v.z), v.w));
+            }
+            s = wave_reduce(s, OpSum{});
+            q = wave_reduce(q, OpSum{});
+            mn = wave_reduce(mn, OpMin{});
+            mx = wave_reduce(mx, OpMax{});
+            if (lead) {
+                smd[0][wave] = s;
+                smd[1][wave] = q;
+                smf[0][wave] = mn;
+                smf[1][wave] = mx;
+            }
+            __syncthreads();
+            s = smd[0][0];
+            q = smd[1][0];
+            mn = smf[0][0];
+            mx = smf[1][0];
+#pragma unroll
+            for (int i = 1; i < NW; ++i) {
+                s += smd[0][i];
+                q += smd[1][i];
+                mn = fminf(mn, smf[0][i]);
+                mx = fmaxf(mx, smf[1][i]);
+            }
+            mu = s / (double)a.K;
+            const double var = fmax(q / (double)a.K - (mu - c) * (mu - c), 0.0);
+            rstd = 1.0 / sqrt(var + (double)a.eps);
+            if constexpr (MODE == kStats) {
+                if (t == 0) {
+                    a.rowstats[2 * row] = mu;
+                    a.rowstats[2 * row + 1] = rstd;
+                }
+            }
+            if (!affine) {
+                lo = (float)(((double)mn - mu) * rstd);
+                const float hi = (float)(((double)mx - mu) * rstd);
+                amax = a.nonneg ? hi - lo : fmaxf(fabsf(lo), fabsf(hi));
+                have_amax = true;
+            }
+        }
+    }
+    // the normalised (and scaled, shifted) values of four consecutive elements
+    auto xhat_at = [&](int64_t idx) {
+        float4 v = x4[idx];
+        if (!a.skip_ln) {
+            v.x = (float)(((double)v.x - mu) * rstd);
+            v.y = (float)(((double)v.y - mu) * rstd);
+            v.z = (float)(((double)v.z - mu) * rstd);
+            v.w = (float)(((double)v.w - mu) * rstd);
+            if (a.gain) {
+                const float4 g = reinterpret_cast<const float4*>(a.gain + grp * a.K)[idx];
+                v.x = v.x * g.x; v.y = v.y * g.y; v.z = v.z * g.z; v.w = v.w * g.w;
+            }
+            if (a.bias) {
+                const float4 b = reinterpret_cast<const float4*>(a.bias + grp * a.K)[idx];
+                v.x = v.x + b.x; v.y = v.y + b.y; v.z = v.z + b.z; v.w = v.w + b.w;
+            }
+        }
+        return v;
+    };
+    float gamma;
+    if constexpr (MODE == kApply) {
+        gamma = fmaxf(__uint_as_float(a.gmax_bits[grp]), 1e-5f);
+    } else {
+        if (!have_amax) {  // uniform: minimum and maximum of the values that get rounded
+            float mn = __builtin_inff(), mx = -__builtin_inff();
+            for (int64_t idx = t; idx < K4; idx += T) {
+                const float4 v = xhat_at(idx);
+                mn = fminf(fminf(mn, v.x), fminf(fminf(v.y, v.z), v.w));
+                mx = fmaxf(fmaxf(mx, v.x), fmaxf(fmaxf(v.y, v.z), v.w));
+            }
+            mn = wave_reduce(mn, OpMin{});
+            mx = wave_reduce(mx, OpMax{});
+            if (lead) {
+                smf[2][wave] = mn;
+                smf[3][wave] = mx;
+            }
+            __syncthreads();
+            mn = smf[2][0];
+            mx = smf[3][0];
+#pragma unroll
+            for (int i = 1; i < NW; ++i) {
+                mn = fminf(mn, smf[2][i]);
+                mx = fmaxf(mx, smf[3][i]);
+            }
+            lo = mn;
+            amax = a.nonneg ? mx - mn : fmaxf(fabsf(mn), fabsf(mx));
+        }
+        if constexpr (MODE == kStats) {
+            if (t == 0) {
+                const uint32_t bits = __float_as_uint(amax);
+                if (bits > __hip_atomic_load(a.gmax_bits + grp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+                    atomicMax(a.gmax_bits + grp, bits);
+            }
+            return;
+        }
+        gamma = fmaxf(amax, 1e-5f);
+    }
+    const float scale = 128.0f / gamma;
+    int rs = 0;
+    uint32_t* __restrict__ c4 = reinterpret_cast<uint32_t*>(a.codes + row * a.K);
+    float4* __restrict__ d4 = a.xhat_dump ? reinterpret_cast<float4*>(a.xhat_dump + row * a.K) : nullptr;
+    for (int64_t idx = t; idx < K4; idx += T) {
+        const float4 x = xhat_at(idx);
+        if (d4) d4[idx] = x;
+        uint32_t wd;
+        if (a.nonneg) {  // Eq. 6: shift by eta, clamp to [0, 127]
+            const float q0 = fminf(fmaxf(rintf((x.x - lo) * scale), 0.f), 127.f);
+            const float q1 = fminf(fmaxf(rintf((x.y - lo) * scale), 0.f), 127.f);
+            const float q2 = fminf(fmaxf(rintf((x.z - lo) * scale), 0.f), 127.f);
+            const float q3 = fminf(fmaxf(rintf((x.w - lo) * scale), 0.f), 127.f);
+            wd = __builtin_amdgcn_cvt_pk_u8_f32(q0, 0, 0u);
+            wd = __builtin_amdgcn_cvt_pk_u8_f32(q1, 1, wd);
+            wd = __builtin_amdgcn_cvt_pk_u8_f32(q2, 2, wd);
+            wd = __builtin_amdgcn_cvt_pk_u8_f32(q3, 3, wd);
+        } else {
+            const float q0 = fminf(fmaxf(rintf(x.x * scale), -128.f), 127.f) + 128.f;
+            const float q1 = fminf(fmaxf(rintf(x.y * scale), -128.f), 127.f) + 128.f;
+            const float q2 = fminf(fmaxf(rintf(x.z * scale), -128.f), 127.f) + 128.f;
+            const float q3 = fminf(fmaxf(rintf(x.w * scale), -128.f), 127.f) + 128.f;
+            wd = __builtin_amdgcn_cvt_pk_u8_f32(q0, 0, 0u);
+            wd = __builtin_amdgcn_cvt_pk_u8_f32(q1, 1, wd);
+            wd = __builtin_amdgcn_cvt_pk_u8_f32(q2, 2, wd);
+            wd = __builtin_amdgcn_cvt_pk_u8_f32(q3, 3, wd) ^ 0x80808080u;
+        }
+        rs = __builtin_amdgcn_sdot4((int)wd, 0x01010101, rs, false);
+        c4[idx] = wd;
+    }
+    if (a.rowsum) {
+        rs = wave_reduce(rs, OpSum{});
+        if (lead) smi[wave] = rs;
+        __syncthreads();
+        if (t == 0) {
+            int r = smi[0];
+#pragma unroll
+            for (int i = 1; i < NW; ++i) r += smi[i];
+            a.rowsum[row] = r;
+        }
+    }
+    if (t == 0) {
+        if (a.nonneg) a.eta[row] = lo;
+        if (MODE == kFull) a.gamma[row] = gamma;
+        else if (row < a.groups) a.gamma[row] = gamma;
+    }
+}
+
 __global__ void fill_u32(uint32_t* p, uint32_t v, int n) {
     if ((int)threadIdx.x < n) p[threadIdx.x] = v;
 }
 
-// rows of up to 32768 elements stay in registers (16 float4 per lane, up to 8 waves)
-bool quant_supported(int64_t K) { return K % 4 == 0 && K / 4 <= 8 * kWave * 16; }
+// rows of up to 32768 elements stay in registers (16 float4 per lane, up to 8 waves); longer
+// ones take ln_quant_long
+bool quant_supported(int64_t K) { return K % 4 == 0; }
+static bool quant_in_registers(int64_t K) { return K / 4 <= 8 * kWave * 16; }
 
 template <int WPR, int NV>
 static void launch_mode(const QuantArgs& a, hipStream_t s) {
@@ -304,6 +493,17 @@ static void launch_mode(const QuantArgs& a, hipStream_t s) {
 // never more than 16 float4 per lane.
 hipError_t launch_quant(const QuantArgs& a, hipStream_t s) {
     const int64_t K4 = a.K / 4;
+    if (!quant_in_registers(a.K)) {
+        const unsigned grid = (unsigned)a.M;
+        if (!a.per_tensor) {
+            ln_quant_long<kFull><<<grid, 512, 0, s>>>(a);
+        } else {
+            fill_u32<<<1, 64, 0, s>>>(a.gmax_bits, 0u, a.groups);
+            ln_quant_long<kStats><<<grid, 512, 0, s>>>(a);
+            ln_quant_long<kApply><<<grid, 512, 0, s>>>(a);
+        }
+        return hipGetLastError();
+    }
     int wpr = 1;
     while (wpr < 8 && K4 > (int64_t)wpr * kWave * 16) wpr *= 2;             // capacity
     while (wpr < 8 && a.M * wpr < 4096 && K4 >= (int64_t)wpr * 2 * kWave * 4) wpr *= 2;  // occupancy

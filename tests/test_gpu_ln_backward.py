@@ -38,7 +38,10 @@ def close(a, b, tol):
 
 
 SHAPES = [(1, 32, 1), (5, 96, 1), (33, 256, 1), (100, 2048, 1), (17, 4096, 1), (9, 8192, 1),
-          (6, 16384, 1), (40, 1024, 4), (12, 2048, 8), (3, 384, 4)]
+          (6, 16384, 1), (40, 1024, 4), (12, 2048, 8), (3, 384, 4),
+          # rows longer than the registers hold (the 30B down-projection's K and beyond), walked
+          # from memory; also as K-groups
+          (5, 28672, 1), (3, 36000, 1), (2, 65536, 1), (4, 57344, 2)]
 
 
 @pytest.mark.parametrize("M,K,groups", SHAPES)
@@ -95,7 +98,7 @@ def test_ln_backward_full_training_shape_sampled(bl):
 def test_ln_backward_errors(bl):
     lib = bl.load_library()
     assert bl.workspace_bytes_grouped(bl.OP_LN_BACKWARD, 8, 16, 2048, 1, 1) > 0
-    with pytest.raises(bl.BitLinearError):  # K/groups beyond what a row of registers holds
-        bl.bitlinear_layernorm_backward(dev(np.zeros((1, 32768), f32)), dev(np.zeros((1, 32768), f32)))
+    with pytest.raises(bl.BitLinearError):  # K/groups not a multiple of 32
+        bl.bitlinear_layernorm_backward(dev(np.zeros((1, 48), f32)), dev(np.zeros((1, 48), f32)))
     assert lib.bitlinear_layernorm_backward(None, None, 0, 64, 1, None, 1e-5, None, None, None,
                                             None, 0, None) == 0

@@ -30,7 +30,7 @@ def host(t):
 
 
 @pytest.mark.parametrize("M,K", [(1, 32), (7, 96), (33, 512), (100, 2048), (12, 4096), (5, 8192),
-                                 (3, 16384), (2, 28672)])
+                                 (3, 16384), (2, 28672), (3, 36000), (2, 65536)])
 @pytest.mark.parametrize("mode", ["ln", "noln", "affine"])
 def test_quant_nonneg(bl, M, K, mode):
     print(f"quant nonneg M={M} K={K} {mode}", flush=True)

@@ -68,7 +68,9 @@ def test_pack_deterministic(bl):
 
 # ------------------------------------------------------------------ activations (Eq. 12, 4, 5)
 QUANT_SHAPES = [(8, 256), (1, 2048), (5, 96), (3, 544), (16, 8192), (33, 4096), (7, 7168),
-                (2, 28672), (4, 16384), (64, 1024)]
+                (2, 28672), (4, 16384), (64, 1024),
+                # rows longer than the registers hold: walked from memory in passes
+                (3, 36000), (2, 65536), (5, 32800)]
 
 
 @pytest.mark.parametrize("M,K", QUANT_SHAPES)
@@ -115,6 +117,21 @@ def test_quant_skip_ln_ties_clip_zero_row_affine(bl):
     ref = oracle.layernorm(X, 1e-5, gain, bias)
     assert np.abs(host(xhat) - ref).max() <= 4e-6
     assert np.array_equal(host(codes), oracle.quantize(host(xhat), host(gamma)))
+    # the same three variants on rows walked from memory (K > 32768)
+    K = 36000
+    X = wl.make_activation(3, K, 10)
+    gain = np.linspace(0.5, 1.5, K).astype(f32)
+    bias = np.linspace(-1, 1, K).astype(f32)
+    for kw, ref in ((dict(ln_gain=dev(gain), ln_bias=dev(bias)), oracle.layernorm(X, 1e-5, gain, bias)),
+                    (dict(flags=bl.FLAG_SKIP_LN), X), (dict(per_tensor=True), oracle.layernorm(X))):
+        codes, gamma, rowsum, xhat = bl.bitlinear_quant_act(dev(X), want_xhat=True, **kw)
+        pt = bool(kw.get("per_tensor"))
+        assert np.abs(host(xhat) - ref).max() <= 4e-6 * max(1.0, np.abs(ref).max())
+        g = oracle.absmax(host(xhat), pt)
+        assert np.array_equal(host(gamma), g)
+        q = oracle.quantize(host(xhat), g, pt)
+        assert np.array_equal(host(codes), q)
+        assert np.array_equal(host(rowsum)[:3], q.astype(np.int64).sum(1))
 
 
 # ------------------------------------------------------------------ matmul (Eq. 7, 11)
@@ -214,7 +231,10 @@ def test_matmul_17_to_32_tokens(bl, M, K, N):
 @pytest.mark.parametrize("M,K,N,per_tensor", [(8, 256, 512, False), (8, 256, 512, True),
                                               (16, 2048, 2048, False), (130, 512, 272, True),
                                               (24, 1056, 300, True), (48, 1056, 300, True),
-                                              (40, 1024, 1000, False)])
+                                              (40, 1024, 1000, False),
+                                              # K beyond the register-resident quantiser
+                                              (3, 36000, 48, False), (20, 40960, 130, True),
+                                              (100, 33792, 96, False)])
 def test_forward_end_to_end(bl, M, K, N, per_tensor):
     print(f"forward M={M} K={K} N={N} per_tensor={per_tensor}", flush=True)
     sd = wl.seed_for(0, M + K + N)
