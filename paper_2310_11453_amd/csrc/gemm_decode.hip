@@ -193,7 +193,9 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
     __shared__ float smf[FUSED ? 3 : 1][16];
     __shared__ int smi[16];
     const int W = blockDim.x / kWave;
-    const int w = threadIdx.x / kWave, l = threadIdx.x % kWave;
+    // the wave's index as a scalar: which chunks and tiles it owns is then scalar arithmetic and
+    // the tile loads take a scalar base, instead of 64-bit compares and selects in every lane
+    const int w = __builtin_amdgcn_readfirstlane((int)threadIdx.x / kWave), l = threadIdx.x % kWave;
     const int m = l & 15, g = l >> 4;
     const int64_t TKp = a.tk_pitch ? a.tk_pitch : tiles_k(a.K);  // tiles per tile row in memory
     if (a.split_k) {  // this workgroup's slice of K (uniform)
@@ -249,8 +251,8 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
             for (int c = 0; c < C; ++c)
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    int64_t k = (tk0 + c) * kChunkK + 64 * i + 16 * g;
-                    if (k > a.K - 16) k = a.K - 16;
+                    int k = (int)(tk0 + c) * kChunkK + 64 * i + 16 * g;  // K < 2^22
+                    k = k > (int)a.K - 16 ? (int)a.K - 16 : k;
                     act[c][i] = *reinterpret_cast<const v4i*>(arow + k);
                 }
         };
@@ -312,12 +314,9 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
             v4i acc[8];
 #pragma unroll
             for (int i = 0; i < 8; ++i) acc[i] = (v4i){0, 0, 0, 0};
-            // chunks past the end of K are masked here, at the point of use: masking at the load
-            // would tie a wait for the whole stream to the first tile
-            v4i wv[C];
-#pragma unroll
-            for (int c = 0; c < C; ++c)
-                wv[c] = (C == 1 && ONE_ROUND) ? wt[t][c] : (wt[t][c] & livem[c]);
+            // chunks past the end of K are masked here, at the point of use (masking at the load
+            // would tie a wait for the whole stream to the first tile), and inside the plane mask,
+            // a scalar: it costs no instruction of its own
             // kActLds: an offset of zero the compiler cannot see through, so that each tile reads
             // its operands again instead of all C * 8 of them being kept in registers
             int again = 0;
@@ -326,8 +325,8 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
             for (int c = 0; c < C; ++c)
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    const int mask = (int)(0x01010101u << i);
-                    const v4i plane = wv[c] & mask;
+                    const int mask = (int)(0x01010101u << i) & livem[c];
+                    const v4i plane = wt[t][c] & mask;
                     v4i cols;
                     if constexpr (kActLds) {
                         int k = (int)(tk0 + c) * kChunkK + 64 * i + 16 * g;
