@@ -180,7 +180,8 @@ int bitlinear_forward_workspace_layout(int64_t M, int64_t N, int64_t K, int gran
  *   ln_gain/bias  fp32 [K] or NULL, applied per element after the group statistics
  * Everything else as in the functions above. */
 size_t bitlinear_packed_bytes_grouped(int64_t N, int64_t K, int groups_n, int groups_k);
-/* op = BL_OP_PACK, BL_OP_QUANT or BL_OP_FORWARD; 0 for anything invalid */
+/* op = BL_OP_PACK, BL_OP_QUANT, BL_OP_FORWARD, BL_OP_LN_BACKWARD or BL_OP_FORWARD_NONNEG; 0 for
+ * anything invalid */
 size_t bitlinear_workspace_bytes_grouped(int op, int64_t M, int64_t N, int64_t K, int groups_n,
                                          int groups_k, int granularity);
 int bitlinear_pack_weights_grouped(const float* W, int64_t N, int64_t K, int groups_n,
@@ -225,10 +226,22 @@ int bitlinear_backward_ste(const float* dY, int64_t M, int64_t N, int64_t K, con
  * Eq. 11 gives
  *   Y[m,n] = acc[m,n] * (beta * gamma_m / 128) + (beta * eta_m) * wsum[n],
  *   wsum[n] = sum_k W~[n,k]   (bitlinear_weight_rowsums, once per weight).
- * Per token only (granularity BL_GAMMA_PER_TOKEN, else BL_ERR_UNSUPPORTED).
- *   eta   out/in  fp32 [M];   wsum  out/in  int32 [N];   the rest as in the functions above.
- * bitlinear_forward_nonneg needs the workspace of
- * bitlinear_workspace_bytes(BL_OP_FORWARD_NONNEG, M, N, K, BL_GAMMA_PER_TOKEN, 0). */
+ * Per token or per tensor (one eta and one gamma for the whole tensor: the training-time
+ * granularity of the paragraph after Eq. 6; the running minimum and maximum are integer
+ * atomics on an order-preserving key, exact and order-free).
+ *   eta   out/in  fp32 [M] (per token) or [1] (per tensor), like gamma
+ *   wsum  out/in  int32 [N];   the rest as in the functions above.
+ * bitlinear_quant_act_nonneg needs a workspace only per tensor
+ * (bitlinear_workspace_bytes(BL_OP_QUANT, ...)); bitlinear_forward_nonneg needs
+ * bitlinear_workspace_bytes(BL_OP_FORWARD_NONNEG, M, N, K, granularity, 0).
+ *
+ * With K-groups (Eq. 14 gives every group its own eta_g beside gamma_g):
+ *   eta, gamma  fp32 [M][groups_k] or [groups_k];  wsum int32 [groups_k][N], wsum[g][n] the sum of
+ *   W~[n, k] over the columns of group g (bitlinear_weight_rowsums_grouped);
+ *   Y = sum_g ( acc_g * beta_g * gamma_g / 128 + (beta_g * eta_g) * wsum[g][n] ), each term two
+ *   fp32 products and one sum as above, the groups added in fp32 in the order g = 0, 1, ...
+ * bitlinear_forward_grouped_nonneg needs
+ * bitlinear_workspace_bytes_grouped(BL_OP_FORWARD_NONNEG, M, N, K, groups_n, groups_k, granularity). */
 int bitlinear_weight_rowsums(const void* packed, int64_t N, int64_t K, int32_t* wsum,
                              void* stream);
 int bitlinear_quant_act_nonneg(const float* X, int64_t M, int64_t K, const float* ln_gain,
@@ -244,6 +257,18 @@ int bitlinear_forward_nonneg(const float* X, int64_t M, int64_t K, const void* p
                              const float* beta, const int32_t* wsum, const float* ln_gain,
                              const float* ln_bias, float ln_eps, int granularity, unsigned flags,
                              float* Y, void* workspace, size_t workspace_bytes, void* stream);
+int bitlinear_weight_rowsums_grouped(const void* packed, int64_t N, int64_t K, int groups_k,
+                                     int32_t* wsum, void* stream);
+int bitlinear_quant_act_grouped_nonneg(const float* X, int64_t M, int64_t K, int groups_k,
+                                       const float* ln_gain, const float* ln_bias, float ln_eps,
+                                       int granularity, unsigned flags, int8_t* codes, float* gamma,
+                                       float* eta, int32_t* rowsum, float* xhat_dump,
+                                       void* workspace, size_t workspace_bytes, void* stream);
+int bitlinear_forward_grouped_nonneg(const float* X, int64_t M, int64_t K, const void* packed,
+                                     int64_t N, int groups_n, int groups_k, const float* beta,
+                                     const int32_t* wsum, const float* ln_gain, const float* ln_bias,
+                                     float ln_eps, int granularity, unsigned flags, float* Y,
+                                     void* workspace, size_t workspace_bytes, void* stream);
 
 /* Backward of the LayerNorm of Eq. 12 (per K-group: Eq. 15).  With the straight-through
  * estimator of Section 2.2 the dX of bitlinear_backward_ste is the gradient with respect

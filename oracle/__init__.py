@@ -357,3 +357,45 @@ def forward_nonneg(X, W, eps=1e-5, per_tensor=False, skip_ln=False, gain=None, b
     y = dequant_nonneg(acc, gamma, eta, beta, wsum, per_tensor)
     return dict(alpha=alpha, beta=beta, sign=sign, xhat=xhat, eta=eta, gamma=gamma, codes=codes,
                 acc=acc, wsum=wsum, y=y)
+
+
+def forward_grouped_nonneg(X, W, groups_n: int = 1, groups_k: int = 1, eps=1e-5, per_tensor=False,
+                           skip_ln=False, gain=None, bias=None, xhat=None):
+    """BitLinear forward with the group parameters of Eq. 13-15 and the quantiser of Eq. 6 per
+    K-group (Eq. 14 defines eta_g beside gamma_g): each K-slice of a token is normalised (group
+    LayerNorm), shifted by its own eta_g = min, scaled by its own gamma_g = max - min (per token,
+    or over all tokens per tensor), contracted on its own, dequantised as
+    acc_g * (beta_g gamma_g / 128) + (beta_g eta_g) * wsum_g[n] (the plain Eq. 6 layer's formula with
+    the slice's own sums), and the slices are added in fp64.  `xhat` as in forward_grouped."""
+    X = _f32(X)
+    W = _f32(W)
+    M, K = X.shape
+    N = W.shape[0]
+    Ng, Kg = N // groups_n, K // groups_k
+    alpha, beta = weight_stats_grouped(W, groups_n, groups_k)
+    sign = binarize_grouped(W, alpha)
+    if xhat is None:
+        xhat = X if skip_ln else layernorm(X, eps, gain, bias, groups=groups_k)
+    xhat = _f32(xhat)
+    n_par = 1 if per_tensor else M
+    eta = np.empty((n_par, groups_k), np.float32)
+    gamma = np.empty((n_par, groups_k), np.float32)
+    codes = np.empty((M, K), np.int8)
+    wsum = np.empty((groups_k, N), np.int32)
+    ysum = np.zeros((M, N), np.float64)
+    for gk in range(groups_k):
+        sl = slice(gk * Kg, (gk + 1) * Kg)
+        xs = np.ascontiguousarray(xhat[:, sl])
+        e, g = minmax_nonneg(xs, per_tensor)
+        q = quantize_nonneg(xs, e, g, per_tensor)
+        eta[:, gk], gamma[:, gk], codes[:, sl] = e, g, q
+        sg = np.ascontiguousarray(sign[:, sl])
+        acc = matmul_i32(q, sg)
+        wsum[gk] = weight_rowsum(sg)
+        for gn in range(groups_n):   # beta of the block (row group gn, column group gk)
+            rows = slice(gn * Ng, (gn + 1) * Ng)
+            part = dequant_nonneg(np.ascontiguousarray(acc[:, rows]), g, e, float(beta[gn, gk]),
+                                  np.ascontiguousarray(wsum[gk, rows]), per_tensor)
+            ysum[:, rows] += part.astype(np.float64)
+    return dict(alpha=alpha, beta=beta, sign=sign, xhat=xhat, eta=eta, gamma=gamma, codes=codes,
+                wsum=wsum, y=ysum.astype(np.float32), y64=ysum)

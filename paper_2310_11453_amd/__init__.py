@@ -11,6 +11,6 @@ from .binding import (  # noqa: F401
     bitlinear_layernorm_backward, bitlinear_quant_act_grouped, packed_bytes_grouped,
     workspace_bytes_grouped,
     bitlinear_forward_nonneg, bitlinear_matmul_nonneg, bitlinear_quant_act_nonneg,
-    bitlinear_weight_rowsums, forward_workspace_layout, set_tuning,
+    bitlinear_weight_rowsums, bitlinear_weight_rowsums_grouped, forward_workspace_layout, set_tuning,
     bitlinear_forward_static, probe_read,
 )

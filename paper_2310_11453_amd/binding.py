@@ -29,7 +29,8 @@ EXPORTS = (
     "bitlinear_quant_act_grouped", "bitlinear_forward_grouped", "bitlinear_layernorm_backward",
     "bitlinear_weight_rowsums", "bitlinear_quant_act_nonneg", "bitlinear_matmul_nonneg",
     "bitlinear_forward_nonneg", "bitlinear_forward_workspace_layout", "bitlinear_set_tuning",
-    "bitlinear_forward_static", "bitlinear_probe_read",
+    "bitlinear_forward_static", "bitlinear_probe_read", "bitlinear_weight_rowsums_grouped",
+    "bitlinear_quant_act_grouped_nonneg", "bitlinear_forward_grouped_nonneg",
 )
 
 _lib = None
@@ -93,6 +94,14 @@ def load_library() -> ctypes.CDLL:
                                              vp, sz, vp]
     lib.bitlinear_forward_static.restype = ci
     lib.bitlinear_forward_static.argtypes = [vp, i64, i64, vp, i64, vp, vp, vp, cf, ci, u32, vp, vp]
+    lib.bitlinear_weight_rowsums_grouped.restype = ci
+    lib.bitlinear_weight_rowsums_grouped.argtypes = [vp, i64, i64, ci, vp, vp]
+    lib.bitlinear_quant_act_grouped_nonneg.restype = ci
+    lib.bitlinear_quant_act_grouped_nonneg.argtypes = [vp, i64, i64, ci, vp, vp, cf, ci, u32, vp, vp, vp,
+                                                       vp, vp, vp, sz, vp]
+    lib.bitlinear_forward_grouped_nonneg.restype = ci
+    lib.bitlinear_forward_grouped_nonneg.argtypes = [vp, i64, i64, vp, i64, ci, ci, vp, vp, vp, vp, cf,
+                                                     ci, u32, vp, vp, sz, vp]
     lib.bitlinear_probe_read.restype = ci
     lib.bitlinear_probe_read.argtypes = [vp, sz, ci, ci, vp, vp]
     lib.bitlinear_forward_workspace_layout.restype = ci
@@ -380,46 +389,79 @@ def bitlinear_weight_rowsums(packed: torch.Tensor, N: int, K: int) -> torch.Tens
 
 
 def bitlinear_quant_act_nonneg(X: torch.Tensor, ln_eps: float = 1e-5, flags: int = 0, ln_gain=None,
-                               ln_bias=None, want_xhat: bool = False):
-    """Eq. 12 + Eq. 6.  Returns (codes in 0..127, gamma [M], eta [M], rowsum [M], xhat or None)."""
+                               ln_bias=None, want_xhat: bool = False, per_tensor: bool = False,
+                               groups_k: int = 1):
+    """Eq. 12 + Eq. 6 (per K-group: Eq. 14-15).  Returns (codes in 0..127, gamma, eta, rowsum, xhat or
+    None); gamma and eta are [M, groups_k] per token, [groups_k] per tensor (flat for one group)."""
     M, K = X.shape
     dev = X.device
     codes = torch.empty((M, K), dtype=torch.int8, device=dev)
-    gamma = torch.empty(max(M, 1), dtype=torch.float32, device=dev)
-    eta = torch.empty(max(M, 1), dtype=torch.float32, device=dev)
-    rowsum = torch.empty(max(M, 1), dtype=torch.int32, device=dev)
+    n_par = groups_k if per_tensor else max(M, 1) * groups_k
+    gamma = torch.empty(n_par, dtype=torch.float32, device=dev)
+    eta = torch.empty(n_par, dtype=torch.float32, device=dev)
+    rowsum = torch.empty(max(M, 1) * groups_k, dtype=torch.int32, device=dev)
     xhat = torch.empty((M, K), dtype=torch.float32, device=dev) if want_xhat else None
-    _check(load_library().bitlinear_quant_act_nonneg(
-        _ptr(X, torch.float32), M, K, _ptr(ln_gain, torch.float32), _ptr(ln_bias, torch.float32),
-        ln_eps, GAMMA_PER_TOKEN, flags, _ptr(codes), _ptr(gamma), _ptr(eta), _ptr(rowsum),
-        _ptr(xhat), None, 0, _stream()), "bitlinear_quant_act_nonneg")
+    ws = _workspace(workspace_bytes_grouped(OP_QUANT, M, 16, K, 1, groups_k, per_tensor), dev)
+    lib = load_library()
+    if groups_k == 1:
+        _check(lib.bitlinear_quant_act_nonneg(
+            _ptr(X, torch.float32), M, K, _ptr(ln_gain, torch.float32), _ptr(ln_bias, torch.float32),
+            ln_eps, _gran(per_tensor), flags, _ptr(codes), _ptr(gamma), _ptr(eta), _ptr(rowsum),
+            _ptr(xhat), _ptr(ws), ws.numel(), _stream()), "bitlinear_quant_act_nonneg")
+    else:
+        _check(lib.bitlinear_quant_act_grouped_nonneg(
+            _ptr(X, torch.float32), M, K, groups_k, _ptr(ln_gain, torch.float32),
+            _ptr(ln_bias, torch.float32), ln_eps, _gran(per_tensor), flags, _ptr(codes), _ptr(gamma),
+            _ptr(eta), _ptr(rowsum), _ptr(xhat), _ptr(ws), ws.numel(), _stream()),
+            "bitlinear_quant_act_grouped_nonneg")
+    if groups_k > 1:
+        shape = (groups_k,) if per_tensor else (max(M, 1), groups_k)
+        gamma, eta, rowsum = gamma.view(shape), eta.view(shape), rowsum.view(max(M, 1), groups_k)
     return codes, gamma, eta, rowsum, xhat
 
 
+def bitlinear_weight_rowsums_grouped(packed: torch.Tensor, N: int, K: int, groups_k: int) -> torch.Tensor:
+    """wsum[g][n] = sum of W~[n, k] over the columns of K-group g, int32 [groups_k, N]."""
+    out = torch.empty((groups_k, N), dtype=torch.int32, device=packed.device)
+    _check(load_library().bitlinear_weight_rowsums_grouped(_ptr(packed), N, K, groups_k, _ptr(out),
+                                                           _stream()), "bitlinear_weight_rowsums_grouped")
+    return out
+
+
 def bitlinear_matmul_nonneg(codes, gamma, eta, rowsum, packed, N: int, beta, wsum,
-                            out: torch.Tensor | None = None) -> torch.Tensor:
+                            out: torch.Tensor | None = None, per_tensor: bool = False) -> torch.Tensor:
     M, K = codes.shape
     if out is None:
         out = torch.empty((M, N), dtype=torch.float32, device=codes.device)
     _check(load_library().bitlinear_matmul_nonneg(
         _ptr(codes, torch.int8), _ptr(gamma, torch.float32), _ptr(eta, torch.float32),
         _ptr(rowsum, torch.int32), M, K, _ptr(packed), N, _ptr(beta, torch.float32),
-        _ptr(wsum, torch.int32), GAMMA_PER_TOKEN, 0, _ptr(out), _stream()),
+        _ptr(wsum, torch.int32), _gran(per_tensor), 0, _ptr(out), _stream()),
         "bitlinear_matmul_nonneg")
     return out
 
 
 def bitlinear_forward_nonneg(X: torch.Tensor, packed: torch.Tensor, N: int, beta: torch.Tensor,
                              wsum: torch.Tensor, ln_eps: float = 1e-5, flags: int = 0, ln_gain=None,
-                             ln_bias=None, out: torch.Tensor | None = None) -> torch.Tensor:
-    """Eq. 11 with the quantiser of Eq. 6."""
+                             ln_bias=None, out: torch.Tensor | None = None, per_tensor: bool = False,
+                             groups_n: int = 1, groups_k: int = 1) -> torch.Tensor:
+    """Eq. 11 with the quantiser of Eq. 6 (with groups: Eq. 13-15, eta_g per K-group)."""
     M, K = X.shape
     if out is None:
         out = torch.empty((M, N), dtype=torch.float32, device=X.device)
-    ws = _workspace(workspace_bytes(OP_FORWARD_NONNEG, M, N, K), X.device)
-    _check(load_library().bitlinear_forward_nonneg(
-        _ptr(X, torch.float32), M, K, _ptr(packed), N, _ptr(beta, torch.float32),
-        _ptr(wsum, torch.int32), _ptr(ln_gain, torch.float32), _ptr(ln_bias, torch.float32), ln_eps,
-        GAMMA_PER_TOKEN, flags, _ptr(out), _ptr(ws), ws.numel(), _stream()),
-        "bitlinear_forward_nonneg")
+    ws = _workspace(workspace_bytes_grouped(OP_FORWARD_NONNEG, M, N, K, groups_n, groups_k, per_tensor),
+                    X.device)
+    lib = load_library()
+    if groups_n == 1 and groups_k == 1:
+        _check(lib.bitlinear_forward_nonneg(
+            _ptr(X, torch.float32), M, K, _ptr(packed), N, _ptr(beta, torch.float32),
+            _ptr(wsum, torch.int32), _ptr(ln_gain, torch.float32), _ptr(ln_bias, torch.float32), ln_eps,
+            _gran(per_tensor), flags, _ptr(out), _ptr(ws), ws.numel(), _stream()),
+            "bitlinear_forward_nonneg")
+    else:
+        _check(lib.bitlinear_forward_grouped_nonneg(
+            _ptr(X, torch.float32), M, K, _ptr(packed), N, groups_n, groups_k,
+            _ptr(beta, torch.float32), _ptr(wsum, torch.int32), _ptr(ln_gain, torch.float32),
+            _ptr(ln_bias, torch.float32), ln_eps, _gran(per_tensor), flags, _ptr(out), _ptr(ws),
+            ws.numel(), _stream()), "bitlinear_forward_grouped_nonneg")
     return out

@@ -56,6 +56,7 @@ constexpr int64_t kMaxDim = (int64_t)1 << 30;
 // The GEMM kernels keep partial sums scaled by up to 2^14 per element of K in int32 and byte
 // offsets into a block of rows in 32 bits: both hold up to this K.
 constexpr int64_t kMaxGemmK = 65536;
+constexpr int kMaxGroups = 64;
 constexpr unsigned kKnownFlags = BL_FLAG_SKIP_LN | BL_FLAG_OUT_ACC_I32 | BL_FLAG_BETA_CENTERED;
 
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
@@ -77,8 +78,8 @@ QuantWs quant_ws(int64_t M, int granularity) {
     size_t off = 0;
     w.rowstats = off;
     off += granularity == BL_GAMMA_PER_TENSOR ? align256((size_t)M * 16) : 0;
-    w.gmax = off;
-    off += 256;
+    w.gmax = off;  // running maxima [kMaxGroups], then (Eq. 6 per tensor) running minima [kMaxGroups]
+    off += 512;
     w.total = off;
     return w;
 }
@@ -108,7 +109,6 @@ ForwardWs forward_ws(int64_t M, int64_t N, int64_t K, int granularity) {
 int check_hip(hipError_t e) { return e == hipSuccess ? BL_OK : BL_ERR_HIP; }
 
 // ---- group quantisation (Eq. 13-15) ----------------------------------------------
-constexpr int kMaxGroups = 64;
 // 0 = fine, else the status to return
 int groups_status(int64_t N, int64_t K, int groups_n, int groups_k) {
     if (groups_n < 1 || groups_k < 1 || groups_n > kMaxGroups || groups_k > kMaxGroups)
@@ -148,17 +148,20 @@ LnBackwardWs ln_backward_ws(int64_t M, int64_t K, int groups_k) {
     w.total = off;
     return w;
 }
-// codes, then gamma and eta side by side, then row sums
-ForwardWs forward_ws_nonneg(int64_t M, int64_t K) {
+// Eq. 6: codes, then gamma and (xhat field) eta, row sums, the quantiser's own scratch
+ForwardWs forward_ws_nonneg(int64_t M, int64_t K, int groups_k, int granularity) {
     ForwardWs w{};
     size_t off = 0;
     w.codes = off;
     off += align256((size_t)M * (size_t)K);
     w.gamma = off;
-    off += align256((size_t)M * 8);
+    off += align256((size_t)M * groups_k * 4);
+    w.xhat = off;  // eta, laid out like gamma
+    off += align256((size_t)M * groups_k * 4);
     w.rowsum = off;
-    off += align256((size_t)M * 4);
+    off += align256((size_t)M * groups_k * 4);
     w.quant = off;
+    off += quant_ws_grouped(M, groups_k, granularity).total;
     w.total = off;
     return w;
 }
@@ -240,7 +243,7 @@ size_t bitlinear_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int gr
             return ln_backward_ws(M, K, 1).total;
         case BL_OP_FORWARD_NONNEG:
             if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return 0;
-            return forward_ws_nonneg(M, K).total;
+            return forward_ws_nonneg(M, K, 1, granularity).total;
         case BL_OP_MATMUL:
             if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return 0;
             return gemm_split_ws_bytes(M, N, K);  // 0 for most shapes: nothing is needed
@@ -288,6 +291,7 @@ int bitlinear_quant_act(const float* X, int64_t M, int64_t K, const float* ln_ga
     a.codes = codes; a.gamma = gamma; a.rowsum = rowsum; a.xhat_dump = xhat_dump;
     a.rowstats = (double*)((char*)workspace + ws.rowstats);
     a.gmax_bits = (uint32_t*)((char*)workspace + ws.gmax);
+    a.gmin_bits = a.gmax_bits + kMaxGroups;
     a.groups = 1;
     return check_hip(launch_quant(a, (hipStream_t)stream));
 }
@@ -412,6 +416,8 @@ size_t bitlinear_workspace_bytes_grouped(int op, int64_t M, int64_t N, int64_t K
             return forward_ws_grouped(M, K, groups_k, granularity).total;
         case BL_OP_LN_BACKWARD:
             return ln_backward_ws(M, K, groups_k).total;
+        case BL_OP_FORWARD_NONNEG:
+            return forward_ws_nonneg(M, K, groups_k, granularity).total;
         default:
             return 0;
     }
@@ -459,11 +465,12 @@ int bitlinear_packed_to_canonical_grouped(const void* packed, int64_t N, int64_t
     return BL_OK;
 }
 
-int bitlinear_quant_act_grouped(const float* X, int64_t M, int64_t K, int groups_k,
-                                const float* ln_gain, const float* ln_bias, float ln_eps,
-                                int granularity, unsigned flags, int8_t* codes, float* gamma,
-                                int32_t* rowsum, float* xhat_dump, void* workspace,
-                                size_t workspace_bytes, void* stream) {
+// Eq. 14-15 for either quantiser: eta == nullptr: Eq. 4; else Eq. 6 with eta laid out like gamma
+static int quant_act_grouped_impl(const float* X, int64_t M, int64_t K, int groups_k,
+                                  const float* ln_gain, const float* ln_bias, float ln_eps,
+                                  int granularity, unsigned flags, bool nonneg, int8_t* codes,
+                                  float* gamma, float* eta, int32_t* rowsum, float* xhat_dump,
+                                  void* workspace, size_t workspace_bytes, void* stream) {
     if (M < 0 || M > kMaxDim || K <= 0 || K > kMaxDim || K % 32) return BL_ERR_SHAPE;
     if (groups_k < 1 || groups_k > kMaxGroups || K % groups_k || (K / groups_k) % 32)
         return BL_ERR_SHAPE;
@@ -471,56 +478,126 @@ int bitlinear_quant_act_grouped(const float* X, int64_t M, int64_t K, int groups
     const int64_t Kg = K / groups_k;
     if (!quant_supported(Kg) || M * groups_k > kMaxDim) return BL_ERR_UNSUPPORTED;
     if (M == 0) return BL_OK;
-    if (!X || !codes || !gamma) return BL_ERR_NULL;
+    if (!X || !codes || !gamma || (nonneg && !eta)) return BL_ERR_NULL;
     const QuantWs ws = quant_ws_grouped(M, groups_k, granularity);
-    if (!workspace || workspace_bytes < ws.total) return BL_ERR_WORKSPACE;
+    const bool need_ws = granularity == BL_GAMMA_PER_TENSOR;
+    if (need_ws && (!workspace || workspace_bytes < ws.total)) return BL_ERR_WORKSPACE;
     // a token's K-groups are consecutive rows of a [M * groups_k, Kg] matrix
     QuantArgs a{};
     a.X = X; a.M = M * groups_k; a.K = Kg; a.gain = ln_gain; a.bias = ln_bias; a.eps = ln_eps;
     a.skip_ln = (flags & BL_FLAG_SKIP_LN) != 0;
     a.per_tensor = granularity == BL_GAMMA_PER_TENSOR;
     a.codes = codes; a.gamma = gamma; a.rowsum = rowsum; a.xhat_dump = xhat_dump;
-    a.rowstats = (double*)((char*)workspace + ws.rowstats);
-    a.gmax_bits = (uint32_t*)((char*)workspace + ws.gmax);
+    if (need_ws) {
+        a.rowstats = (double*)((char*)workspace + ws.rowstats);
+        a.gmax_bits = (uint32_t*)((char*)workspace + ws.gmax);
+        a.gmin_bits = a.gmax_bits + kMaxGroups;
+    }
     a.groups = groups_k;
+    a.nonneg = nonneg;
+    a.eta = eta;
     return check_hip(launch_quant(a, (hipStream_t)stream));
+}
+
+int bitlinear_quant_act_grouped(const float* X, int64_t M, int64_t K, int groups_k,
+                                const float* ln_gain, const float* ln_bias, float ln_eps,
+                                int granularity, unsigned flags, int8_t* codes, float* gamma,
+                                int32_t* rowsum, float* xhat_dump, void* workspace,
+                                size_t workspace_bytes, void* stream) {
+    return quant_act_grouped_impl(X, M, K, groups_k, ln_gain, ln_bias, ln_eps, granularity, flags,
+                                  false, codes, gamma, nullptr, rowsum, xhat_dump, workspace,
+                                  workspace_bytes, stream);
+}
+
+int bitlinear_quant_act_grouped_nonneg(const float* X, int64_t M, int64_t K, int groups_k,
+                                       const float* ln_gain, const float* ln_bias, float ln_eps,
+                                       int granularity, unsigned flags, int8_t* codes, float* gamma,
+                                       float* eta, int32_t* rowsum, float* xhat_dump,
+                                       void* workspace, size_t workspace_bytes, void* stream) {
+    return quant_act_grouped_impl(X, M, K, groups_k, ln_gain, ln_bias, ln_eps, granularity, flags,
+                                  true, codes, gamma, eta, rowsum, xhat_dump, workspace,
+                                  workspace_bytes, stream);
+}
+
+// Eq. 13-15 for either quantiser: wsum == nullptr: Eq. 4; else Eq. 6 with wsum [groups_k][N]
+static int forward_grouped_impl(const float* X, int64_t M, int64_t K, const void* packed, int64_t N,
+                                int groups_n, int groups_k, const float* beta, const int32_t* wsum,
+                                bool nonneg, const float* ln_gain, const float* ln_bias,
+                                float ln_eps, int granularity, unsigned flags, float* Y,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+    if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return BL_ERR_SHAPE;
+    if (int st = groups_status(N, K, groups_n, groups_k)) return st;
+    if (!gran_ok(granularity) || (flags & ~BL_FLAG_SKIP_LN)) return BL_ERR_UNSUPPORTED;
+    if (K / groups_k > kMaxGemmK) return BL_ERR_UNSUPPORTED;
+    if (M == 0) return BL_OK;
+    if (!X || !packed || !beta || !Y || (nonneg && !wsum)) return BL_ERR_NULL;
+    const ForwardWs ws = nonneg ? forward_ws_nonneg(M, K, groups_k, granularity)
+                                : forward_ws_grouped(M, K, groups_k, granularity);
+    if (!workspace || workspace_bytes < ws.total) return BL_ERR_WORKSPACE;
+    char* base = (char*)workspace;
+    int8_t* codes = (int8_t*)(base + ws.codes);
+    float* gamma = (float*)(base + ws.gamma);
+    float* eta = nonneg ? (float*)(base + ws.xhat) : nullptr;
+    int32_t* rowsum = (int32_t*)(base + ws.rowsum);
+    int rc = quant_act_grouped_impl(X, M, K, groups_k, ln_gain, ln_bias, ln_eps, granularity,
+                                    flags & BL_FLAG_SKIP_LN, nonneg, codes, gamma, eta, rowsum,
+                                    nullptr, base + ws.quant, workspace_bytes - ws.quant, stream);
+    if (rc != BL_OK) return rc;
+    // one GEMM per K-group, each dequantised with its own beta_g * gamma_g (and shifted by its own
+    // eta_g, Eq. 14) and added (Eq. 13-14)
+    const int64_t Kg = K / groups_k;
+    const size_t blob_dwords = tiles_bytes(N, Kg) / 4;
+    const bool per_tensor = granularity == BL_GAMMA_PER_TENSOR;
+    for (int gk = 0; gk < groups_k; ++gk) {
+        GemmArgs a{};
+        a.codes = codes + gk * Kg; a.gamma = gamma + gk; a.rowsum = rowsum + gk;
+        a.M = M; a.K = Kg; a.N = N;
+        a.packed = (const uint32_t*)packed + gk * blob_dwords; a.beta = beta + gk;
+        a.per_tensor = per_tensor;
+        a.out_acc = false;
+        a.Y = Y;
+        a.ldq = K; a.gstride = groups_k; a.beta_rows = N / groups_n; a.beta_stride = groups_k;
+        a.accumulate = gk > 0;
+        if (nonneg) {
+            a.eta = eta + gk;
+            a.wsum = wsum + (int64_t)gk * N;
+        }
+        const hipError_t e = M <= 16 ? launch_gemm_decode(a, (hipStream_t)stream)
+                                     : launch_gemm_prefill(a, (hipStream_t)stream);
+        if (e != hipSuccess) return BL_ERR_HIP;
+    }
+    return BL_OK;
 }
 
 int bitlinear_forward_grouped(const float* X, int64_t M, int64_t K, const void* packed, int64_t N,
                               int groups_n, int groups_k, const float* beta, const float* ln_gain,
                               const float* ln_bias, float ln_eps, int granularity, unsigned flags,
                               float* Y, void* workspace, size_t workspace_bytes, void* stream) {
-    if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return BL_ERR_SHAPE;
-    if (int st = groups_status(N, K, groups_n, groups_k)) return st;
-    if (!gran_ok(granularity) || (flags & ~BL_FLAG_SKIP_LN)) return BL_ERR_UNSUPPORTED;
-    if (K / groups_k > kMaxGemmK) return BL_ERR_UNSUPPORTED;
-    if (M == 0) return BL_OK;
-    if (!X || !packed || !beta || !Y) return BL_ERR_NULL;
-    const ForwardWs ws = forward_ws_grouped(M, K, groups_k, granularity);
-    if (!workspace || workspace_bytes < ws.total) return BL_ERR_WORKSPACE;
-    char* base = (char*)workspace;
-    int8_t* codes = (int8_t*)(base + ws.codes);
-    float* gamma = (float*)(base + ws.gamma);
-    int32_t* rowsum = (int32_t*)(base + ws.rowsum);
-    int rc = bitlinear_quant_act_grouped(X, M, K, groups_k, ln_gain, ln_bias, ln_eps, granularity,
-                                         flags & BL_FLAG_SKIP_LN, codes, gamma, rowsum, nullptr,
-                                         base + ws.quant, workspace_bytes - ws.quant, stream);
-    if (rc != BL_OK) return rc;
-    // one GEMM per K-group, each dequantised with its own beta_g * gamma_g and added (Eq. 13-14)
+    return forward_grouped_impl(X, M, K, packed, N, groups_n, groups_k, beta, nullptr, false, ln_gain,
+                                ln_bias, ln_eps, granularity, flags, Y, workspace, workspace_bytes,
+                                stream);
+}
+
+int bitlinear_forward_grouped_nonneg(const float* X, int64_t M, int64_t K, const void* packed,
+                                     int64_t N, int groups_n, int groups_k, const float* beta,
+                                     const int32_t* wsum, const float* ln_gain, const float* ln_bias,
+                                     float ln_eps, int granularity, unsigned flags, float* Y,
+                                     void* workspace, size_t workspace_bytes, void* stream) {
+    return forward_grouped_impl(X, M, K, packed, N, groups_n, groups_k, beta, wsum, true, ln_gain,
+                                ln_bias, ln_eps, granularity, flags, Y, workspace, workspace_bytes,
+                                stream);
+}
+
+int bitlinear_weight_rowsums_grouped(const void* packed, int64_t N, int64_t K, int groups_k,
+                                     int32_t* wsum, void* stream) {
+    if (!shape_ok(N, K)) return BL_ERR_SHAPE;
+    if (int st = groups_status(N, K, 1, groups_k)) return st;
+    if (!packed || !wsum) return BL_ERR_NULL;
     const int64_t Kg = K / groups_k;
     const size_t blob_dwords = tiles_bytes(N, Kg) / 4;
     for (int gk = 0; gk < groups_k; ++gk) {
-        GemmArgs a{};
-        a.codes = codes + gk * Kg; a.gamma = gamma + gk; a.rowsum = rowsum + gk;
-        a.M = M; a.K = Kg; a.N = N;
-        a.packed = (const uint32_t*)packed + gk * blob_dwords; a.beta = beta + gk;
-        a.per_tensor = granularity == BL_GAMMA_PER_TENSOR;
-        a.out_acc = false;
-        a.Y = Y;
-        a.ldq = K; a.gstride = groups_k; a.beta_rows = N / groups_n; a.beta_stride = groups_k;
-        a.accumulate = gk > 0;
-        const hipError_t e = M <= 16 ? launch_gemm_decode(a, (hipStream_t)stream)
-                                     : launch_gemm_prefill(a, (hipStream_t)stream);
+        const hipError_t e = launch_weight_rowsums((const uint32_t*)packed + gk * blob_dwords, N, Kg,
+                                                   wsum + (int64_t)gk * N, (hipStream_t)stream);
         if (e != hipSuccess) return BL_ERR_HIP;
     }
     return BL_OK;
@@ -561,22 +638,9 @@ int bitlinear_quant_act_nonneg(const float* X, int64_t M, int64_t K, const float
                                unsigned flags, int8_t* codes, float* gamma, float* eta,
                                int32_t* rowsum, float* xhat_dump, void* workspace,
                                size_t workspace_bytes, void* stream) {
-    (void)workspace;
-    (void)workspace_bytes;
-    if (M < 0 || M > kMaxDim || K <= 0 || K > kMaxDim || K % 32) return BL_ERR_SHAPE;
-    if (granularity != BL_GAMMA_PER_TOKEN || (flags & ~BL_FLAG_SKIP_LN)) return BL_ERR_UNSUPPORTED;
-    if (!quant_supported(K)) return BL_ERR_UNSUPPORTED;
-    if (M == 0) return BL_OK;
-    if (!X || !codes || !gamma || !eta) return BL_ERR_NULL;
-    QuantArgs a{};
-    a.X = X; a.M = M; a.K = K; a.gain = ln_gain; a.bias = ln_bias; a.eps = ln_eps;
-    a.skip_ln = (flags & BL_FLAG_SKIP_LN) != 0;
-    a.per_tensor = false;
-    a.codes = codes; a.gamma = gamma; a.rowsum = rowsum; a.xhat_dump = xhat_dump;
-    a.groups = 1;
-    a.nonneg = true;
-    a.eta = eta;
-    return check_hip(launch_quant(a, (hipStream_t)stream));
+    return quant_act_grouped_impl(X, M, K, 1, ln_gain, ln_bias, ln_eps, granularity, flags, true,
+                                  codes, gamma, eta, rowsum, xhat_dump, workspace, workspace_bytes,
+                                  stream);
 }
 
 int bitlinear_matmul_nonneg(const int8_t* codes, const float* gamma, const float* eta,
@@ -584,13 +648,13 @@ int bitlinear_matmul_nonneg(const int8_t* codes, const float* gamma, const float
                             int64_t N, const float* beta, const int32_t* wsum, int granularity,
                             unsigned flags, float* Y, void* stream) {
     if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return BL_ERR_SHAPE;
-    if (granularity != BL_GAMMA_PER_TOKEN || flags || K > kMaxGemmK) return BL_ERR_UNSUPPORTED;
+    if (!gran_ok(granularity) || flags || K > kMaxGemmK) return BL_ERR_UNSUPPORTED;
     if (M == 0) return BL_OK;
     if (!codes || !gamma || !eta || !rowsum || !packed || !beta || !wsum || !Y) return BL_ERR_NULL;
     GemmArgs a{};
     a.codes = codes; a.gamma = gamma; a.rowsum = rowsum; a.M = M; a.K = K; a.N = N;
     a.packed = (const uint32_t*)packed; a.beta = beta;
-    a.per_tensor = false;
+    a.per_tensor = granularity == BL_GAMMA_PER_TENSOR;
     a.out_acc = false;
     a.Y = Y;
     plain_fields(a);
@@ -604,24 +668,8 @@ int bitlinear_forward_nonneg(const float* X, int64_t M, int64_t K, const void* p
                              const float* beta, const int32_t* wsum, const float* ln_gain,
                              const float* ln_bias, float ln_eps, int granularity, unsigned flags,
                              float* Y, void* workspace, size_t workspace_bytes, void* stream) {
-    if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return BL_ERR_SHAPE;
-    if (granularity != BL_GAMMA_PER_TOKEN || (flags & ~BL_FLAG_SKIP_LN)) return BL_ERR_UNSUPPORTED;
-    if (K > kMaxGemmK) return BL_ERR_UNSUPPORTED;
-    if (M == 0) return BL_OK;
-    if (!X || !packed || !beta || !wsum || !Y) return BL_ERR_NULL;
-    const ForwardWs ws = forward_ws_nonneg(M, K);
-    if (!workspace || workspace_bytes < ws.total) return BL_ERR_WORKSPACE;
-    char* base = (char*)workspace;
-    int8_t* codes = (int8_t*)(base + ws.codes);
-    float* gamma = (float*)(base + ws.gamma);
-    float* eta = gamma + M;
-    int32_t* rowsum = (int32_t*)(base + ws.rowsum);
-    int rc = bitlinear_quant_act_nonneg(X, M, K, ln_gain, ln_bias, ln_eps, granularity,
-                                        flags & BL_FLAG_SKIP_LN, codes, gamma, eta, rowsum, nullptr,
-                                        nullptr, 0, stream);
-    if (rc != BL_OK) return rc;
-    return bitlinear_matmul_nonneg(codes, gamma, eta, rowsum, M, K, packed, N, beta, wsum,
-                                   granularity, 0, Y, stream);
+    return forward_grouped_impl(X, M, K, packed, N, 1, 1, beta, wsum, true, ln_gain, ln_bias, ln_eps,
+                                granularity, flags, Y, workspace, workspace_bytes, stream);
 }
 
 int bitlinear_layernorm_backward(const float* dXhat, const float* X, int64_t M, int64_t K,

@@ -222,7 +222,7 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
         rs = a.rowsum[mc * a.gstride];
         gm = a.per_tensor ? a.gamma[0] : a.gamma[mc * a.gstride];
         // Eq. 6 only; without it the load goes to gamma (always valid) and the value is not used
-        eta = *(a.eta ? a.eta + mc * a.gstride : a.gamma);
+        eta = *(a.eta ? a.eta + (a.per_tensor ? 0 : mc * a.gstride) : a.gamma);
     }
 
     int part[ONE_ROUND ? 1 : T][4];
@@ -425,7 +425,7 @@ __global__ __launch_bounds__(256) void splitk_reduce(GemmArgs a, int splits) {
     const float beta = a.beta[((uint32_t)n / (uint32_t)a.beta_rows) * a.beta_stride];
     const float gm = a.per_tensor ? a.gamma[0] : a.gamma[m * a.gstride];
     float y = (float)pm * ((beta * gm) / 128.0f);
-    if (a.eta) y = y + (beta * a.eta[m * a.gstride]) * (float)a.wsum[n];
+    if (a.eta) y = y + (beta * a.eta[a.per_tensor ? 0 : m * a.gstride]) * (float)a.wsum[n];
     if (a.accumulate) y += a.Y[idx];
     a.Y[idx] = y;
 }

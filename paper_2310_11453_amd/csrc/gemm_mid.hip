@@ -132,7 +132,7 @@ __global__ __launch_bounds__(mid::THREADS) void gemm_mid_kernel(GemmArgs a, int 
         const int64_t m = er + ER * h < M ? er + ER * h : M - 1;
         e_gamma[h] = a.gamma[a.per_tensor ? 0 : m * a.gstride];
         e_rs[h] = a.rowsum[m * a.gstride];
-        e_eta[h] = *(a.eta ? a.eta + m * a.gstride : a.gamma);
+        e_eta[h] = *(a.eta ? a.eta + (a.per_tensor ? 0 : m * a.gstride) : a.gamma);
     }
     float e_beta[4];
     int e_ws[4];

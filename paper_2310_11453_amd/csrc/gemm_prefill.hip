@@ -318,7 +318,7 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
                 const float gm = a.gamma[a.per_tensor ? 0 : m * a.gstride];
                 const int rs = a.rowsum[m * a.gstride];
                 const float b = a.beta[bg * a.beta_stride];
-                const float e = *(a.eta ? a.eta + m * a.gstride : a.gamma);
+                const float e = *(a.eta ? a.eta + (a.per_tensor ? 0 : m * a.gstride) : a.gamma);
                 const int ws = *(a.eta ? a.wsum + n : a.rowsum);
                 if (i < BM) {
                     // gamma / 128 is exact, so beta * (gamma / 128) has the bits of (beta * gamma) / 128

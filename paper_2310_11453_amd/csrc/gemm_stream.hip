@@ -74,7 +74,7 @@ __global__ __launch_bounds__(stream::kMaxWaves* kWave) void gemm_stream_kernel(G
         tok_sum[m] = a.rowsum[m * a.gstride];
         // gamma / 128 is exact
         tok_sc[m] = a.out_acc ? 0.f : a.gamma[a.per_tensor ? 0 : m * a.gstride] * 0.0078125f;
-        tok_eta[m] = a.eta && !a.out_acc ? a.eta[m * a.gstride] : 0.f;
+        tok_eta[m] = a.eta && !a.out_acc ? a.eta[a.per_tensor ? 0 : m * a.gstride] : 0.f;
     }
     __syncthreads();
 

@@ -51,12 +51,15 @@ struct QuantArgs {
     float* xhat_dump;
     double* rowstats;   // per-tensor only: [M][2] = (mean, rstd)
     uint32_t* gmax_bits; // per-tensor only: [groups], bit pattern of the running max
+    uint32_t* gmin_bits; // per-tensor Eq. 6 only: [groups], ordered key of the running minimum
+                         // (gmax_bits then holds the ordered key of the running maximum)
     // Group normalisation / quantisation (Eq. 14-15): a token of `groups` * K elements is
     // handled as `groups` consecutive rows of K; row r belongs to group r % groups.  M counts
     // those rows.  gain/bias hold groups * K entries.  groups = 1: the plain layer.
     int groups;
-    // Eq. 6 (per token only): codes = clamp(rne((x^ - eta) * 128 / gamma), 0, 127) with
-    // eta = min x^, gamma = max(x^ - eta); eta[M] receives the minima.
+    // Eq. 6: codes = clamp(rne((x^ - eta) * 128 / gamma), 0, 127) with eta = min x^,
+    // gamma = max(x^ - eta); eta receives the minima, laid out like gamma ([M] rows per token,
+    // [groups] per tensor).
     bool nonneg;
     float* eta;
 };
@@ -80,7 +83,8 @@ struct GemmArgs {
     int64_t beta_rows;    // output columns n per beta group (a multiple of 16, or N)
     int64_t beta_stride;  // beta[(n / beta_rows) * beta_stride] scales column n
     bool accumulate;      // Y += result (a later K-group) instead of Y = result
-    // Eq. 6: Y += (beta * eta[m * gstride]) * wsum[n], wsum[n] = sum_k s[n,k]; nullptr otherwise
+    // Eq. 6: Y += (beta * eta[m * gstride]) * wsum[n] (eta[0] per tensor), wsum[n] = sum_k s[n,k];
+    // nullptr otherwise
     const float* eta;
     const int32_t* wsum;
     // Packed tiles of one tile row are tk_pitch KiB apart (0: tiles_k(K), the whole matrix).

@@ -17,6 +17,25 @@ namespace bl {
 
 enum QuantMode { kFull = 0, kStats = 1, kApply = 2 };
 
+// Order-preserving map of floats (any sign) onto unsigned integers and back, so that a running
+// minimum / maximum over the whole tensor can be an integer atomic: exact and order-free.
+__device__ inline uint32_t float_key(float v) {
+    const uint32_t b = __float_as_uint(v);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ inline float key_float(uint32_t k) {
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+// Eq. 6 per tensor: the row's extremes join the running minimum (gmin_bits) and maximum
+// (gmax_bits) of its K-group; a look first spares the atomic when there is nothing to add.
+__device__ inline void offer_extremes(const QuantArgs& a, int g, float lo, float hi) {
+    const uint32_t kl = float_key(lo), kh = float_key(hi);
+    if (kl < __hip_atomic_load(a.gmin_bits + g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+        atomicMin(a.gmin_bits + g, kl);
+    if (kh > __hip_atomic_load(a.gmax_bits + g, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+        atomicMax(a.gmax_bits + g, kh);
+}
+
 // WPR waves share one token (row); a lane holds NV float4 of it.  Workgroups have at least
 // four waves, so short rows are handled four (or two) to a workgroup, one per wave, with no
 // barrier at all.
@@ -66,7 +85,7 @@ __global__ __launch_bounds__((WPR < 4 ? 4 : WPR) * kWave, 4) void ln_quant_rows(
     const bool affine = a.gain != nullptr || a.bias != nullptr;
     bool have_amax = false;
     float amax = 0.f;
-    float lo = 0.f;  // Eq. 6 only: the row's minimum (eta); amax then holds max - min
+    float lo = 0.f, hi_row = 0.f;  // Eq. 6 only: the row's minimum (eta) and maximum; amax = max - min
 
     if (!a.skip_ln) {
         double mu, rstd;
@@ -134,6 +153,7 @@ __global__ __launch_bounds__((WPR < 4 ? 4 : WPR) * kWave, 4) void ln_quant_rows(
                 // normalised row is reached at the row's minimum or maximum.
                 lo = (float)(((double)mn - mu) * rstd);
                 const float hi = (float)(((double)mx - mu) * rstd);
+                hi_row = hi;
                 amax = a.nonneg ? hi - lo : fmaxf(fabsf(lo), fabsf(hi));
                 have_amax = true;
             }
@@ -176,7 +196,12 @@ __global__ __launch_bounds__((WPR < 4 ? 4 : WPR) * kWave, 4) void ln_quant_rows(
 
     float gamma;
     if constexpr (MODE == kApply) {
-        gamma = fmaxf(__uint_as_float(a.gmax_bits[grp]), 1e-5f);
+        if (a.nonneg) {  // Eq. 6 per tensor: eta and gamma from the tensor's extremes
+            lo = key_float(a.gmin_bits[grp]);
+            gamma = fmaxf(key_float(a.gmax_bits[grp]) - lo, 1e-5f);
+        } else {
+            gamma = fmaxf(__uint_as_float(a.gmax_bits[grp]), 1e-5f);
+        }
     } else {
         if (!have_amax && !a.nonneg) {  // uniform: no LayerNorm, or a gain/bias after it
             float m = 0.f;
@@ -201,9 +226,14 @@ __global__ __launch_bounds__((WPR < 4 ? 4 : WPR) * kWave, 4) void ln_quant_rows(
                 mx = -__builtin_inff();
             }
             lo = row_reduce<WPR>(mn, OpMin{}, smf[2], rw, wr);
-            amax = row_reduce<WPR>(mx, OpMax{}, smf[3], rw, wr) - lo;
+            hi_row = row_reduce<WPR>(mx, OpMax{}, smf[3], rw, wr);
+            amax = hi_row - lo;
         }
         if constexpr (MODE == kStats) {
+            if (a.nonneg) {  // uniform
+                if (t == 0 && live) offer_extremes(a, grp, lo, hi_row);
+                return;
+            }
             // non-negative floats order like their bit patterns: integer max is exact
             // The running maximum only grows, so whoever does not exceed what is there already
             // has nothing to add: the look first keeps thousands of rows from queueing on one
@@ -272,10 +302,9 @@ __global__ __launch_bounds__((WPR < 4 ? 4 : WPR) * kWave, 4) void ln_quant_rows(
         rs = row_reduce<WPR>(rs, OpSum{}, smi, rw, wr);
         if (t == 0 && live) a.rowsum[row] = rs;
     }
-    if (t == 0 && live) {
+    if (t == 0 && live && (MODE == kFull || row < a.groups)) {  // rows 0 .. groups-1 cover every group
+        a.gamma[row] = gamma;
         if (a.nonneg) a.eta[row] = lo;
-        if (MODE == kFull) a.gamma[row] = gamma;
-        else if (row < a.groups) a.gamma[row] = gamma;  // rows 0 .. groups-1 cover every group
     }
 }
 
@@ -300,7 +329,7 @@ __global__ __launch_bounds__(512) void ln_quant_long(QuantArgs a) {
     const int grp = a.groups > 1 ? (int)(row % a.groups) : 0;
     const bool affine = a.gain != nullptr || a.bias != nullptr;
     bool have_amax = false;
-    float amax = 0.f, lo = 0.f;
+    float amax = 0.f, lo = 0.f, hi_row = 0.f;
     double mu = 0.0, rstd = 1.0;
 
     if (!a.skip_ln) {
@@ -356,6 +385,7 @@ __global__ __launch_bounds__(512) void ln_quant_long(QuantArgs a) {
             if (!affine) {
                 lo = (float)(((double)mn - mu) * rstd);
                 const float hi = (float)(((double)mx - mu) * rstd);
+                hi_row = hi;
                 amax = a.nonneg ? hi - lo : fmaxf(fabsf(lo), fabsf(hi));
                 have_amax = true;
             }
@@ -382,7 +412,12 @@ __global__ __launch_bounds__(512) void ln_quant_long(QuantArgs a) {
     };
     float gamma;
     if constexpr (MODE == kApply) {
-        gamma = fmaxf(__uint_as_float(a.gmax_bits[grp]), 1e-5f);
+        if (a.nonneg) {
+            lo = key_float(a.gmin_bits[grp]);
+            gamma = fmaxf(key_float(a.gmax_bits[grp]) - lo, 1e-5f);
+        } else {
+            gamma = fmaxf(__uint_as_float(a.gmax_bits[grp]), 1e-5f);
+        }
     } else {
         if (!have_amax) {  // uniform: minimum and maximum of the values that get rounded
             float mn = __builtin_inff(), mx = -__builtin_inff();
@@ -406,9 +441,14 @@ __global__ __launch_bounds__(512) void ln_quant_long(QuantArgs a) {
                 mx = fmaxf(mx, smf[3][i]);
             }
             lo = mn;
+            hi_row = mx;
             amax = a.nonneg ? mx - mn : fmaxf(fabsf(mn), fabsf(mx));
         }
         if constexpr (MODE == kStats) {
+            if (a.nonneg) {
+                if (t == 0) offer_extremes(a, grp, lo, hi_row);
+                return;
+            }
             if (t == 0) {
                 const uint32_t bits = __float_as_uint(amax);
                 if (bits > __hip_atomic_load(a.gmax_bits + grp, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
@@ -459,15 +499,18 @@ __global__ __launch_bounds__(512) void ln_quant_long(QuantArgs a) {
             a.rowsum[row] = r;
         }
     }
-    if (t == 0) {
+    if (t == 0 && (MODE == kFull || row < a.groups)) {
+        a.gamma[row] = gamma;
         if (a.nonneg) a.eta[row] = lo;
-        if (MODE == kFull) a.gamma[row] = gamma;
-        else if (row < a.groups) a.gamma[row] = gamma;
     }
 }
 
-__global__ void fill_u32(uint32_t* p, uint32_t v, int n) {
-    if ((int)threadIdx.x < n) p[threadIdx.x] = v;
+// running maxima start at 0 (below every key and every non-negative float), minima at all ones
+__global__ void fill_extremes(uint32_t* gmax, uint32_t* gmin, int n) {
+    if ((int)threadIdx.x < n) {
+        gmax[threadIdx.x] = 0u;
+        if (gmin) gmin[threadIdx.x] = 0xFFFFFFFFu;
+    }
 }
 
 // rows of up to 32768 elements stay in registers (16 float4 per lane, up to 8 waves); longer
@@ -482,7 +525,7 @@ static void launch_mode(const QuantArgs& a, hipStream_t s) {
     if (!a.per_tensor) {
         ln_quant_rows<WPR, NV, kFull><<<grid, NW * kWave, 0, s>>>(a);
     } else {
-        fill_u32<<<1, 64, 0, s>>>(a.gmax_bits, 0u, a.groups);
+        fill_extremes<<<1, 64, 0, s>>>(a.gmax_bits, a.nonneg ? a.gmin_bits : nullptr, a.groups);
         ln_quant_rows<WPR, NV, kStats><<<grid, NW * kWave, 0, s>>>(a);
         ln_quant_rows<WPR, NV, kApply><<<grid, NW * kWave, 0, s>>>(a);
     }
@@ -498,7 +541,7 @@ hipError_t launch_quant(const QuantArgs& a, hipStream_t s) {
         if (!a.per_tensor) {
             ln_quant_long<kFull><<<grid, 512, 0, s>>>(a);
         } else {
-            fill_u32<<<1, 64, 0, s>>>(a.gmax_bits, 0u, a.groups);
+            fill_extremes<<<1, 64, 0, s>>>(a.gmax_bits, a.nonneg ? a.gmin_bits : nullptr, a.groups);
             ln_quant_long<kStats><<<grid, 512, 0, s>>>(a);
             ln_quant_long<kApply><<<grid, 512, 0, s>>>(a);
         }

@@ -620,3 +620,47 @@ def test_eq6_per_tensor_branches():
     rec = r["codes"].astype(np.float64) * float(r["gamma"][0]) / 128.0 + float(r["eta"][0])
     y = float(r["beta"]) * rec @ r["sign"].astype(np.float64).T
     assert np.abs(r["y"] - y).max() <= 1e-5 * np.abs(y).max()
+
+
+def test_eq6_grouped_forward_composition():
+    """Eq. 14 gives every K-group its own eta_g and gamma_g.  One group is the plain Eq. 6 layer
+    bit for bit; column groups equal the sum of independent Eq. 6 layers on the column slices;
+    row groups equal independent layers on the row slices bit for bit; and the whole thing against
+    a brute-force Python evaluation of y = sum_g beta_g W~_g (x~_g gamma_g / Q_b + eta_g)."""
+    rng = np.random.default_rng(36)
+    M, K, N = 5, 192, 48
+    X = (rng.standard_normal((M, K)) * 1.2 + 0.3).astype(f32)
+    X[:, :64] += 2.0
+    W = (rng.standard_normal((N, K)) * 0.02).astype(f32)
+    W[:24] += 0.01
+    for pt in (False, True):
+        one = oracle.forward_grouped_nonneg(X, W, 1, 1, per_tensor=pt)
+        plain = oracle.forward_nonneg(X, W, per_tensor=pt)
+        assert np.array_equal(one["y"], plain["y"]) and np.array_equal(one["codes"], plain["codes"])
+        # three column groups: the sum of three independent layers, each on its slice of LN'd input
+        r = oracle.forward_grouped_nonneg(X, W, 1, 3, per_tensor=pt)
+        tot = np.zeros((M, N))
+        for g in range(3):
+            sl = slice(64 * g, 64 * (g + 1))
+            part = oracle.forward_nonneg(X[:, sl], W[:, sl], per_tensor=pt)  # LN over the slice = group LN
+            tot += part["y"].astype(np.float64)
+            assert np.array_equal(r["codes"][:, sl], part["codes"])
+            assert np.array_equal(r["eta"][:, g], part["eta"]) and np.array_equal(r["gamma"][:, g], part["gamma"])
+        assert np.array_equal(r["y64"], tot)
+        # two row groups: independent layers on the row slices
+        r2 = oracle.forward_grouped_nonneg(X, W, 2, 1, per_tensor=pt)
+        for g in range(2):
+            rows = slice(24 * g, 24 * (g + 1))
+            assert np.array_equal(r2["y"][:, rows], oracle.forward_nonneg(X, W[rows], per_tensor=pt)["y"])
+        # brute force with Python floats on the 2 x 3 grouping
+        r3 = oracle.forward_grouped_nonneg(X, W, 2, 3, per_tensor=pt)
+        for m in (0, M - 1):
+            for n in (0, 23, 24, N - 1):
+                y = 0.0
+                for g in range(3):
+                    bg = float(r3["beta"][n // 24, g])
+                    e = float(r3["eta"][0 if pt else m, g])
+                    ga = float(r3["gamma"][0 if pt else m, g])
+                    for k in range(64 * g, 64 * (g + 1)):
+                        y += bg * int(r3["sign"][n, k]) * (int(r3["codes"][m, k]) * ga / 128.0 + e)
+                assert abs(r3["y64"][m, n] - y) <= 1e-5 * max(1.0, abs(y))
