@@ -293,9 +293,6 @@ __global__ __launch_bounds__(mid::THREADS) void gemm_mid_kernel(GemmArgs a, int 
 #pragma unroll
             for (int h = 0; h < 2; ++h) bw[s2][h] = bwn[s2][h];
     }
-    // the accumulators were last written inside an asm block: let the matrix pipeline retire
-    // them before ordinary instructions read them
-    asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
     wait_vmcnt<0>();
     __syncthreads();  // every group is done with its ring
 

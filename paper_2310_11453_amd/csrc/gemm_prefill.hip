@@ -25,12 +25,13 @@
 //    the whole chip needs ~5 TB/s of it at half the MFMA peak, and with a latency of about
 //    2 us that is ~40 KiB in flight per CU, hence the deep ring (NS = 8 stages of 16 KiB).
 //
-// Schedule.  The unit of work is a half-step: 32 k of a stage, MI*NI MFMAs.  One asm block
-// issues the LDS reads of the NEXT half-step's activation operand, then the MFMAs of the
-// current one, then waits for the reads: the LDS latency hides under the MFMAs and every
-// register the block defines is valid when it ends.  (An LDS read the compiler can see
-// makes it drain the whole DMA queue first, because it cannot tell the read from the DMA's
-// target; reads whose completion the compiler cannot see must not escape an asm block.)
+// Schedule.  The unit of work is a half-step: 32 k of a stage, MI*NI MFMAs.  It starts the LDS
+// reads of the NEXT half-step's activation operand (asm), issues the MFMAs of the current one
+// with the expansion of the next weight operand scheduled between them, then waits for the
+// reads (asm): LDS latency and expansion both hide under the MFMAs.  (An LDS read the compiler
+// can see makes it drain the whole DMA queue first, because it cannot tell the read from the
+// DMA's target; the registers of a read in flight are tied to the asm that waits for it, so
+// nothing can use them earlier.)
 // Between the two half-steps of stage st every wave waits for its own DMA of stage st+1
 // (s_waitcnt vmcnt(n), n counted by hand) and meets the others at a bare s_barrier (no
 // fence: a fence would drain every DMA in flight).  After that barrier stage st+1 is
@@ -75,45 +76,29 @@ __device__ inline void lds_read_bits(v4i (&bw)[2][2], uint32_t ad) {
         : "v"(ad));
 }
 
-// Half-step, 4 x 2 sub-tiles: prefetch an[] from LDS address `ad`, acc[mi][s] += ac[mi] x b[s].
-// The four reads ahead of the first MFMA also separate it from whatever VALU instruction
-// the compiler placed last.
-__device__ inline void half_step(v16i (&acc)[4][2], const v4i (&ac)[4], const v4i (&b)[2],
-                                 v4i (&an)[4], uint32_t ad) {
+// The LDS reads of the next half-step's operands, started here and valid at lds_wait, which ties
+// the registers so that nothing the compiler schedules in between can use them earlier.
+__device__ inline void lds_issue(v4i (&a)[4], uint32_t ad) {
     asm volatile(
-        "ds_read_b128 %8, %18\n\t"
-        "ds_read_b128 %9, %18 offset:2048\n\t"
-        "ds_read_b128 %10, %18 offset:4096\n\t"
-        "ds_read_b128 %11, %18 offset:6144\n\t"
-        "v_mfma_i32_32x32x32_i8 %0, %12, %16, %0\n\t"
-        "v_mfma_i32_32x32x32_i8 %1, %12, %17, %1\n\t"
-        "v_mfma_i32_32x32x32_i8 %2, %13, %16, %2\n\t"
-        "v_mfma_i32_32x32x32_i8 %3, %13, %17, %3\n\t"
-        "v_mfma_i32_32x32x32_i8 %4, %14, %16, %4\n\t"
-        "v_mfma_i32_32x32x32_i8 %5, %14, %17, %5\n\t"
-        "v_mfma_i32_32x32x32_i8 %6, %15, %16, %6\n\t"
-        "v_mfma_i32_32x32x32_i8 %7, %15, %17, %7\n\t"
-        "s_waitcnt lgkmcnt(0)"
-        : "+v"(acc[0][0]), "+v"(acc[0][1]), "+v"(acc[1][0]), "+v"(acc[1][1]), "+v"(acc[2][0]),
-          "+v"(acc[2][1]), "+v"(acc[3][0]), "+v"(acc[3][1]), "=&v"(an[0]), "=&v"(an[1]),
-          "=&v"(an[2]), "=&v"(an[3])
-        : "v"(ac[0]), "v"(ac[1]), "v"(ac[2]), "v"(ac[3]), "v"(b[0]), "v"(b[1]), "v"(ad));
+        "ds_read_b128 %0, %4\n\t"
+        "ds_read_b128 %1, %4 offset:2048\n\t"
+        "ds_read_b128 %2, %4 offset:4096\n\t"
+        "ds_read_b128 %3, %4 offset:6144"
+        : "=&v"(a[0]), "=&v"(a[1]), "=&v"(a[2]), "=&v"(a[3])
+        : "v"(ad));
 }
-// Half-step, 2 x 2 sub-tiles.
-__device__ inline void half_step(v16i (&acc)[2][2], const v4i (&ac)[2], const v4i (&b)[2],
-                                 v4i (&an)[2], uint32_t ad) {
+__device__ inline void lds_issue(v4i (&a)[2], uint32_t ad) {
     asm volatile(
-        "ds_read_b128 %4, %10\n\t"
-        "ds_read_b128 %5, %10 offset:2048\n\t"
-        "s_nop 1\n\t"
-        "v_mfma_i32_32x32x32_i8 %0, %6, %8, %0\n\t"
-        "v_mfma_i32_32x32x32_i8 %1, %6, %9, %1\n\t"
-        "v_mfma_i32_32x32x32_i8 %2, %7, %8, %2\n\t"
-        "v_mfma_i32_32x32x32_i8 %3, %7, %9, %3\n\t"
-        "s_waitcnt lgkmcnt(0)"
-        : "+v"(acc[0][0]), "+v"(acc[0][1]), "+v"(acc[1][0]), "+v"(acc[1][1]), "=&v"(an[0]),
-          "=&v"(an[1])
-        : "v"(ac[0]), "v"(ac[1]), "v"(b[0]), "v"(b[1]), "v"(ad));
+        "ds_read_b128 %0, %2\n\t"
+        "ds_read_b128 %1, %2 offset:2048"
+        : "=&v"(a[0]), "=&v"(a[1])
+        : "v"(ad));
+}
+__device__ inline void lds_wait(v4i (&a)[4]) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]));
+}
+__device__ inline void lds_wait(v4i (&a)[2]) {
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a[0]), "+v"(a[1]));
 }
 // Row scale and row sum of four consecutive rows (epilogue), complete on exit.
 __device__ inline void lds_read_rows(v4f& sc, v4i& rs, uint32_t ad_sc, uint32_t ad_rs) {
@@ -149,7 +134,7 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
     constexpr int NBW = (BN / 16) / NWAVES;  // packed-weight tiles (DMA pieces) per wave per chunk
     constexpr int STAGE_BYTES = BM * kStageK;
     static_assert(BM * 4 % THREADS == 0, "tile shape");
-    static_assert((MI == 4 && NI == 2) || (MI == 2 && NI == 2), "wave tiles with an asm block");
+    static_assert((MI == 4 && NI == 2) || (MI == 2 && NI == 2), "wave tiles with LDS-read asm blocks");
     static_assert(NS == 4 || NS == 8, "ring size");
     static_assert((BN / 16) % NWAVES == 0 && (NS - 2) * P + NBW < 64, "tile shape");
 
@@ -268,6 +253,39 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
             for (int d = 0; d < 4; ++d) b[s][d] = (int)(((uint32_t)bw[s][h][d] >> i) & 0x01010101u);
     };
     v4i ax[MI], ay[MI], bx[NI], by[NI];
+    // One half-step (32 k of a stage): acc += ac x b, MI * NI MFMAs, with the next half-step's
+    // weight operand bn = plane i of half h expanded BETWEEN them (the compiler's scheduler is told
+    // so with sched_group_barrier: one MFMA, then the two vector ALU operations of a dword, ...), so
+    // that a wave expands under its own MFMAs instead of ahead of them; the operands at `ad` are
+    // read into an meanwhile (valid on return).  Against an asm block of the MFMAs with the
+    // expansion ahead of it: 117 against 129 us on 2048 x 4096 x 16384, 1-2 % on the longer K.
+    auto half_step = [&](const v4i(&ac)[MI], const v4i(&b)[NI], v4i(&bn)[NI], int h, int i,
+                          v4i(&an)[MI], uint32_t ad) {
+        lds_issue(an, ad);
+        // the bits pass through an (empty) asm placed after the reads, and the new operand through
+        // one at the end: the expansion can neither be moved ahead of this half-step nor be left
+        // for a later one before the scheduler sees the groups below
+        asm volatile("" : "+v"(bw[0][h]), "+v"(bw[1][h]));
+        __builtin_amdgcn_sched_barrier(0);
+        constexpr int DW = NI * 4 / (MI * NI);  // dwords of the new operand per MFMA: 1 or 2
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+#pragma unroll
+            for (int s = 0; s < NI; ++s) {
+                acc[mi][s] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ac[mi], b[s], acc[mi][s], 0, 0, 0);
+                const int q = mi * NI + s;
+#pragma unroll
+                for (int e = 0; e < DW; ++e) {
+                    const int idx = q * DW + e;  // 0 .. NI*4-1
+                    bn[idx >> 2][idx & 3] = (int)(((uint32_t)bw[idx >> 2][h][idx & 3] >> i) & 0x01010101u);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 2 * DW, 0);
+            }
+        asm volatile("" : "+v"(bn[0]), "+v"(bn[1]));
+        __builtin_amdgcn_sched_barrier(0);
+        lds_wait(an);
+    };
 
     // Stage st, bit plane i = st % 8.  In: ax/bx = operands of (st, h=0).  Out: ax/bx =
     // operands of (st+1, h=0).  DMA bookkeeping at the mid-stage point, while the look-ahead
@@ -278,8 +296,7 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
     // right after that barrier.  Near the end of K nothing more is issued and the wait is for
     // everything outstanding (all of it is needed within the next NS-2 stages).
     auto stage = [&](int st, int i, bool clamp, bool half, bool ahead, bool bits_in_flight) {
-        expand(by, 1, i);
-        half_step(acc, ax, bx, ay, a_addr(st, 1));
+        half_step(ax, bx, by, 1, i, ay, a_addr(st, 1));
         if (!ahead) wait_vmcnt<0>();
         else if (bits_in_flight && i >= 3 && i <= NS - 1 && i <= 6) wait_vmcnt<(NS - 3) * P + NBW>();
         else wait_vmcnt<(NS - 3) * P>();
@@ -288,8 +305,7 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
         if (i == 2 && (st >> 3) + 1 < TK) issue_bits((st >> 3) + 1);
         if (ahead) issue(st + NS - 1, clamp);
         if (!half) {
-            expand(bx, 0, (i + 1) & 7);
-            half_step(acc, ay, by, ax, a_addr(st + 1, 0));
+            half_step(ay, by, bx, 0, (i + 1) & 7, ax, a_addr(st + 1, 0));
         }
     };
 
@@ -370,10 +386,6 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
         for (int st = (int)main_chunks * 8; st < nst; ++st)
             stage(st, st & 7, true, (int64_t)st * kStageK + 32 >= K, st + NS - 1 < nst,
                   (st >> 3) + 1 < TK);
-
-        // The accumulators were last written by MFMAs inside an asm block: give the matrix
-        // pipeline time to retire them before ordinary instructions read them.
-        asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory");
 
         // Every wave is done with the LDS ring: start the next tile's stream, then store.
         block_barrier();
