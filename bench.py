@@ -34,7 +34,7 @@ I8_MFMA_PEAK_TOPS = 5000.0
 # HBM bytes per launch of the dominant kernel (the 4096->16384 GEMM at M=2048) measured with
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the same counter reads for a
 # plain 256 MiB device copy (x2.000 and x1.000): profiles/gemm_prefill_6p7b_counters.txt.
-TRAFFIC_BYTES = {"gemm_prefill_up": int((41328 * 2.000 + 131072 * 1.000) * 1024)}
+TRAFFIC_BYTES = {"gemm_prefill_up": int((41190 * 2.000 + 131073 * 1.000) * 1024)}
 
 
 def gemm_bytes(M, K, N):
@@ -483,6 +483,27 @@ def main():
                      frac_i8_mfma_peak=tops_p / I8_MFMA_PEAK_TOPS))
             del cp, Yp, p3
 
+        # Group Quantization and Normalization (Eq. 13-15) at a 30B shape, eight groups on each axis:
+        # what a tensor-parallel layer computes, all shards on this one GPU (a shard would run one of
+        # the groups_k GEMM launches; here they follow each other, adding into Y).
+        Lg, G = c3.layers[1], 8
+        Wg = wl.make_weight(Lg.N, Lg.K, c3.w_std, wl.seed_for(3, 30))
+        pg, ag, bg = bl.bitlinear_pack_weights_grouped(torch.from_numpy(Wg).to(dev), G, G)
+        del Wg
+        grouped = []
+        for Mg in (16, 4096):
+            Xg = torch.from_numpy(wl.make_activation(Mg, Lg.K, wl.seed_for(3, 31))).to(dev)
+            Yg = torch.empty((Mg, Lg.N), dtype=torch.float32, device=dev)
+            fg = lambda: bl.bitlinear_forward_grouped(Xg, pg, Lg.N, bg, G, G, out=Yg)
+            for _ in range(20):
+                fg()
+            tg = event_ms(fg, 20, torch)
+            grouped.append(dict(layer=Lg.name, K=Lg.K, N=Lg.N, M=Mg, groups_n=G, groups_k=G, us=tg * 1e3,
+                                tops=2 * Mg * Lg.K * Lg.N / (tg * 1e-3) / 1e12,
+                                note="LN + quantiser per K-group, then one GEMM launch per K-group"))
+            del Xg, Yg
+        decode["grouped_30b"] = grouped
+        del pg
         if not args.no_decode_stacks:
             decode_stacks(bl, torch, dev, decode)
         decode["value"] = best["gbs"]

@@ -130,6 +130,47 @@ def test_grouped_forward_ragged(bl):
     _check_forward(bl, 33, 384, 240, 3, 4, False, 503)
 
 
+def test_grouped_forward_full_size_30b(bl):
+    """A 30B-shaped layer (7168 -> 28672) with eight groups on each axis, decode and prefill batch:
+    alpha_g, beta_g and all bits; codes and gamma_g given the normalised input the GPU dumped;
+    outputs on a stratified sample against the oracle's per-group sums."""
+    K, N, G = 7168, 28672, 8
+    W = wl.make_weight(N, K, 0.01, seed=wl.seed_for(3, 40))
+    W[: N // 2] += f32(0.003)
+    a, b = oracle.weight_stats_grouped(W, G, G)
+    sign = oracle.binarize_grouped(W, a)
+    packed, alpha, beta = bl.bitlinear_pack_weights_grouped(dev(W), G, G)
+    del W
+    assert np.array_equal(host(alpha), a) and np.array_equal(host(beta), b)
+    canon = host(bl.bitlinear_packed_to_canonical_grouped(packed, N, K, G)).view(np.uint32)
+    assert np.array_equal(canon, oracle.pack_canonical(sign))
+    del canon
+    Kg, Ng = K // G, N // G
+    for M in (16, 300):
+        print(f"grouped full size M={M}", flush=True)
+        X = wl.make_activation(M, K, seed=wl.seed_for(3, 41 + M))
+        X[:, : K // 4] += f32(1.0)
+        y = host(bl.bitlinear_forward_grouped(dev(X), packed, N, beta, G, G))
+        codes, gamma, rowsum, xhat = bl.bitlinear_quant_act_grouped(dev(X), G, want_xhat=True)
+        xh = host(xhat)
+        g_ref = oracle.absmax(xh, False, groups=G)
+        q_ref = oracle.quantize(xh, g_ref, False, groups=G)
+        assert np.array_equal(host(gamma).reshape(-1), g_ref) and np.array_equal(host(codes), q_ref)
+        rng = np.random.default_rng(M)
+        gm, gn = (M + 63) // 64, N // 64
+        rows = np.minimum((np.arange(gm) * 64)[:, None] + rng.integers(0, 64, (gm, gn)), M - 1).ravel()
+        cols = ((np.arange(gn) * 64)[None, :] + rng.integers(0, 64, (gm, gn))).ravel()
+        gam = g_ref.reshape(M, G)
+        ysum = np.zeros(rows.size)
+        for g in range(G):  # each K-group dequantised with its own beta_g gamma_g, added in fp64
+            acc = oracle.matmul_i32_sampled(np.ascontiguousarray(q_ref[:, g * Kg:(g + 1) * Kg]),
+                                            np.ascontiguousarray(sign[:, g * Kg:(g + 1) * Kg]), rows, cols)
+            sc = (b[cols // Ng, g] * gam[rows, g]) / f32(128.0)
+            ysum += (acc.astype(f32) * sc).astype(np.float64)
+        got = y[rows, cols].astype(np.float64)
+        assert np.abs(got - ysum).max() <= 1e-5 * np.sqrt(np.mean(ysum ** 2))
+
+
 def test_groups_of_one_match_the_plain_entry_points(bl):
     M, K, N = 50, 512, 256
     X, W = layer(M, K, N, 600)
