@@ -23,6 +23,7 @@ const TuningField kTuningFields[] = {
     {"decode_tiles", &Tuning::decode_tiles},     {"mid_nosplit", &Tuning::mid_nosplit},
     {"mid_split_tiles", &Tuning::mid_split_tiles}, {"mid_only", &Tuning::mid_only},
     {"prefill_tile", &Tuning::prefill_tile},     {"prefill_grid", &Tuning::prefill_grid},
+    {"prefill_xbm", &Tuning::prefill_xbm},
     {"quant_wpr", &Tuning::quant_wpr},           {"bwd_ring", &Tuning::bwd_ring},
     {"bwd_grid", &Tuning::bwd_grid},             {"bwd_rowmajor", &Tuning::bwd_rowmajor},
     {"mid_kernel", &Tuning::mid_kernel},
@@ -121,7 +122,12 @@ int groups_status(int64_t N, int64_t K, int groups_n, int groups_k) {
 QuantWs quant_ws_grouped(int64_t M, int groups_k, int granularity) {
     return quant_ws(M * groups_k, granularity);
 }
-ForwardWs forward_ws_grouped(int64_t M, int64_t K, int groups_k, int granularity) {
+// Up to 64 tokens all K-groups run in one launch, each group's int32 sums in a slice of its own
+// that a second kernel dequantises and adds (Eq. 13-14).
+size_t group_slices_bytes(int64_t M, int64_t N, int groups_k) {
+    return groups_k > 1 && M <= 64 ? (size_t)groups_k * (size_t)M * (size_t)N * 4 : 0;
+}
+ForwardWs forward_ws_grouped(int64_t M, int64_t N, int64_t K, int groups_k, int granularity) {
     ForwardWs w{};
     size_t off = 0;
     w.codes = off;
@@ -132,6 +138,9 @@ ForwardWs forward_ws_grouped(int64_t M, int64_t K, int groups_k, int granularity
     off += align256((size_t)M * groups_k * 4);
     w.quant = off;
     off += quant_ws_grouped(M, groups_k, granularity).total;
+    w.split = off;
+    w.split_bytes = group_slices_bytes(M, N, groups_k);
+    off += align256(w.split_bytes);
     w.total = off;
     return w;
 }
@@ -149,7 +158,7 @@ LnBackwardWs ln_backward_ws(int64_t M, int64_t K, int groups_k) {
     return w;
 }
 // Eq. 6: codes, then gamma and (xhat field) eta, row sums, the quantiser's own scratch
-ForwardWs forward_ws_nonneg(int64_t M, int64_t K, int groups_k, int granularity) {
+ForwardWs forward_ws_nonneg(int64_t M, int64_t N, int64_t K, int groups_k, int granularity) {
     ForwardWs w{};
     size_t off = 0;
     w.codes = off;
@@ -162,6 +171,9 @@ ForwardWs forward_ws_nonneg(int64_t M, int64_t K, int groups_k, int granularity)
     off += align256((size_t)M * groups_k * 4);
     w.quant = off;
     off += quant_ws_grouped(M, groups_k, granularity).total;
+    w.split = off;
+    w.split_bytes = group_slices_bytes(M, N, groups_k);
+    off += align256(w.split_bytes);
     w.total = off;
     return w;
 }
@@ -243,7 +255,7 @@ size_t bitlinear_workspace_bytes(int op, int64_t M, int64_t N, int64_t K, int gr
             return ln_backward_ws(M, K, 1).total;
         case BL_OP_FORWARD_NONNEG:
             if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return 0;
-            return forward_ws_nonneg(M, K, 1, granularity).total;
+            return forward_ws_nonneg(M, N, K, 1, granularity).total;
         case BL_OP_MATMUL:
             if (M < 0 || M > kMaxDim || !shape_ok(N, K)) return 0;
             return gemm_split_ws_bytes(M, N, K);  // 0 for most shapes: nothing is needed
@@ -413,11 +425,11 @@ size_t bitlinear_workspace_bytes_grouped(int op, int64_t M, int64_t N, int64_t K
         case BL_OP_QUANT:
             return quant_ws_grouped(M, groups_k, granularity).total;
         case BL_OP_FORWARD:
-            return forward_ws_grouped(M, K, groups_k, granularity).total;
+            return forward_ws_grouped(M, N, K, groups_k, granularity).total;
         case BL_OP_LN_BACKWARD:
             return ln_backward_ws(M, K, groups_k).total;
         case BL_OP_FORWARD_NONNEG:
-            return forward_ws_nonneg(M, K, groups_k, granularity).total;
+            return forward_ws_nonneg(M, N, K, groups_k, granularity).total;
         default:
             return 0;
     }
@@ -531,8 +543,8 @@ static int forward_grouped_impl(const float* X, int64_t M, int64_t K, const void
     if (K / groups_k > kMaxGemmK) return BL_ERR_UNSUPPORTED;
     if (M == 0) return BL_OK;
     if (!X || !packed || !beta || !Y || (nonneg && !wsum)) return BL_ERR_NULL;
-    const ForwardWs ws = nonneg ? forward_ws_nonneg(M, K, groups_k, granularity)
-                                : forward_ws_grouped(M, K, groups_k, granularity);
+    const ForwardWs ws = nonneg ? forward_ws_nonneg(M, N, K, groups_k, granularity)
+                                : forward_ws_grouped(M, N, K, groups_k, granularity);
     if (!workspace || workspace_bytes < ws.total) return BL_ERR_WORKSPACE;
     char* base = (char*)workspace;
     int8_t* codes = (int8_t*)(base + ws.codes);
@@ -548,6 +560,27 @@ static int forward_grouped_impl(const float* X, int64_t M, int64_t K, const void
     const int64_t Kg = K / groups_k;
     const size_t blob_dwords = tiles_bytes(N, Kg) / 4;
     const bool per_tensor = granularity == BL_GAMMA_PER_TENSOR;
+    if (groups_k > 1) {
+        // One launch for all K-groups.  Up to 64 tokens every K-group is a slice of the launch,
+        // and the fold that follows dequantises each group's sums with its own scales and adds
+        // them in the order 0, 1, ...; above that the large-tile kernel walks a tile's groups
+        // itself and keeps the fp32 sum in registers.  Y is written once.
+        GemmArgs a{};
+        a.codes = codes; a.gamma = gamma; a.rowsum = rowsum;
+        a.M = M; a.K = Kg; a.N = N;
+        a.packed = (const uint32_t*)packed; a.beta = beta;
+        a.per_tensor = per_tensor;
+        a.Y = Y;
+        a.ldq = K; a.gstride = groups_k; a.beta_rows = N / groups_n; a.beta_stride = groups_k;
+        if (nonneg) {
+            a.eta = eta;
+            a.wsum = wsum;
+        }
+        a.kgroups = groups_k; a.group_packed = (int64_t)blob_dwords;
+        a.split_ws = (int32_t*)(base + ws.split); a.split_ws_bytes = ws.split_bytes;
+        return check_hip(M <= 16 ? launch_gemm_decode(a, (hipStream_t)stream)
+                                 : launch_gemm_prefill(a, (hipStream_t)stream));
+    }
     for (int gk = 0; gk < groups_k; ++gk) {
         GemmArgs a{};
         a.codes = codes + gk * Kg; a.gamma = gamma + gk; a.rowsum = rowsum + gk;

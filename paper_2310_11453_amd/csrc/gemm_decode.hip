@@ -198,7 +198,11 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
     const int w = __builtin_amdgcn_readfirstlane((int)threadIdx.x / kWave), l = threadIdx.x % kWave;
     const int m = l & 15, g = l >> 4;
     const int64_t TKp = a.tk_pitch ? a.tk_pitch : tiles_k(a.K);  // tiles per tile row in memory
-    if (a.split_k) {  // this workgroup's slice of K (uniform)
+    const bool to_slices = a.split_k || a.kgroups > 1;  // partial sums go to split_ws
+    if (a.kgroups > 1) {  // this workgroup's K-group (uniform)
+        a.codes += (int64_t)blockIdx.y * a.K;
+        a.packed += (int64_t)blockIdx.y * a.group_packed;
+    } else if (a.split_k) {  // this workgroup's slice of K (uniform)
         const int64_t k0 = (int64_t)blockIdx.y * a.split_k;
         a.codes += k0;
         a.packed += (k0 / kChunkK) * 256;
@@ -373,7 +377,7 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
         const int64_t tn = tn0 + t;
         const int64_t n = tn * kTileN + 4 * g;
         if (tn >= TN || m >= M || n >= a.N) continue;
-        if (a.split_k) {  // partial sum of this K-slice: 2 * sum_k q b, folded by splitk_reduce
+        if (to_slices) {  // partial sum of this K-slice: 2 * sum_k q b, folded by splitk_reduce
             int* p = a.split_ws + ((int64_t)blockIdx.y * M + m) * a.N + n;
             const v4i h = sum >> 6;
             if ((a.N & 3) == 0) *reinterpret_cast<v4i*>(p) = h;
@@ -415,6 +419,25 @@ __global__ __launch_bounds__(256) void splitk_reduce(GemmArgs a, int splits) {
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= a.M * a.N) return;
     const int64_t m = idx / a.N, n = idx % a.N;
+    if (a.kgroups > 1) {
+        // slices are K-groups (Eq. 13-15): each is dequantised with its own beta_g gamma_g / 128
+        // (and shifted by its own eta_g, Eq. 14); the groups are added in the order 0, 1, ...
+        const int G = a.kgroups;
+        const uint32_t bg = ((uint32_t)n / (uint32_t)a.beta_rows) * (uint32_t)a.beta_stride;
+        float y = 0.f;
+        for (int g = 0; g < G; ++g) {
+            const int pm = a.split_ws[((int64_t)g * a.M + m) * a.N + n] - a.rowsum[m * a.gstride + g];
+            const float beta = a.beta[bg + g];
+            const float gm = a.gamma[a.per_tensor ? g : m * a.gstride + g];
+            float yg = (float)pm * ((beta * gm) / 128.0f);
+            if (a.eta)
+                yg = yg + (beta * a.eta[a.per_tensor ? g : m * a.gstride + g]) *
+                              (float)a.wsum[(int64_t)g * a.N + n];
+            y = g ? yg + y : yg;
+        }
+        a.Y[idx] = y;
+        return;
+    }
     int sum = 0;
     for (int sp = 0; sp < splits; ++sp) sum += a.split_ws[((int64_t)sp * a.M + m) * a.N + n];
     const int pm = sum - a.rowsum[m * a.gstride];
@@ -445,7 +468,8 @@ static int num_cus() {
 template <int C, int T, int MAXT, bool ONE_ROUND, int FUSED = 0>
 static void launch_one(const GemmArgs& a, int W, int tpb, hipStream_t s) {
     const int64_t TN = tiles_n(a.N);
-    const unsigned splits = a.split_k ? (unsigned)((a.K + a.split_k - 1) / a.split_k) : 1u;
+    const unsigned splits = a.kgroups > 1 ? (unsigned)a.kgroups
+                            : a.split_k ? (unsigned)((a.K + a.split_k - 1) / a.split_k) : 1u;
     const dim3 grid((unsigned)((TN + tpb - 1) / tpb), splits);
     gemm_decode_kernel<C, T, MAXT, ONE_ROUND, FUSED><<<grid, W * kWave, 0, s>>>(a, tpb);
 }
@@ -535,7 +559,12 @@ hipError_t launch_gemm_decode(const GemmArgs& a_in, hipStream_t s) {
     int splits = 1;
     const bool fused = a.x_row != nullptr;  // the caller asked gemm_decode_fuses_quant
     const size_t need = gemm_split_ws_bytes(a.M, a.N, a.K);
-    if (need && !fused && a.split_ws && a.split_ws_bytes >= need && !tuning().decode_nosplit) {
+    if (a.kgroups > 1) {  // one slice per K-group; the caller sized split_ws for it
+        if (fused || !a.split_ws || a.split_ws_bytes < (size_t)a.kgroups * a.M * a.N * 4)
+            return hipErrorInvalidValue;
+        splits = a.kgroups;
+        a.split_k = 0;
+    } else if (need && !fused && a.split_ws && a.split_ws_bytes >= need && !tuning().decode_nosplit) {
         splits = (int)((TK + 15) / 16);
         const int64_t per = (TK + splits - 1) / splits;  // tiles per slice, evenly
         splits = (int)((TK + per - 1) / per);            // slices that actually hold tiles

@@ -97,7 +97,11 @@ __global__ __launch_bounds__(mid::THREADS) void gemm_mid_kernel(GemmArgs a, int 
 
     // ---- this item's slice of K, then this group's chunks of it ----------------------------
     int64_t ki0 = 0, Ki = a.K;
-    if (a.split_k) {
+    const bool to_slices = a.split_k || a.kgroups > 1;  // partial sums go to split_ws
+    if (a.kgroups > 1) {  // the slice is a K-group of a grouped layer: its own codes columns and blob
+        a.codes += (int64_t)sp * a.K;
+        a.packed += (int64_t)sp * a.group_packed;
+    } else if (a.split_k) {
         ki0 = (int64_t)sp * a.split_k;
         Ki = a.K - ki0 < a.split_k ? a.K - ki0 : a.split_k;
     }
@@ -331,7 +335,7 @@ __global__ __launch_bounds__(mid::THREADS) void gemm_mid_kernel(GemmArgs a, int 
         const int* p0 = red + (er + ER * h) * BN + (threadIdx.x & 31) * 4;
         const v4i s4 = *reinterpret_cast<const v4i*>(p0) + *reinterpret_cast<const v4i*>(p0 + BM * BN);
         const bool vec = (N & 3) == 0;  // then nq + 3 < N and the row starts 16-byte aligned
-        if (a.split_k) {
+        if (to_slices) {
             int* o = a.split_ws + ((int64_t)sp * M + m) * N + nq;
             const v4i t = s4 * 2;
             if (vec) *reinterpret_cast<v4i*>(o) = t;
@@ -399,7 +403,11 @@ hipError_t launch_gemm_mid(const GemmArgs& a_in, hipStream_t s) {
     int splits = 1;
     const int64_t per = prefill_split_tiles(a.M, a.N, a.K);
     const size_t need = gemm_split_ws_bytes(a.M, a.N, a.K);
-    if (per && a.split_ws && a.split_ws_bytes >= need && !tuning().mid_nosplit) {
+    if (a.kgroups > 1) {  // one slice per K-group; the caller sized split_ws for it
+        if (!a.split_ws || a.split_ws_bytes < (size_t)a.kgroups * a.M * a.N * 4)
+            return hipErrorInvalidValue;
+        splits = a.kgroups;
+    } else if (per && a.split_ws && a.split_ws_bytes >= need && !tuning().mid_nosplit) {
         splits = (int)((tiles_k(a.K) + per - 1) / per);
         a.tk_pitch = a.tk_pitch ? a.tk_pitch : tiles_k(a.K);
         a.split_k = per * kChunkK;

@@ -123,9 +123,13 @@ __device__ inline void lds_write_b32(uint32_t ad, uint32_t v) {
 // GEN = false: the plain layer (one beta, Y = result): nothing of what follows costs anything.
 // GEN = true adds beta per column group (Eq. 13), accumulation over K-groups, the shift term of
 // Eq. 6.
-template <int BM, int BN, int WM, int WN, int NS, bool GEN>
+// KGRP = true (with GEN): all a.kgroups K-groups of a grouped layer (Eq. 13-15) in this launch.  A
+// work item is (tile, group), the groups of a tile following each other on the same workgroup:
+// each group's int32 sums are dequantised with that group's beta_g gamma_g / 128 (and shifted by
+// its eta_g) into an fp32 register copy of the tile, which is stored once, after the last group.
+template <int BM, int BN, int WM, int WN, int NS, bool GEN, bool KGRP = false>
 __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs a, int grid_m,
-                                                                        int grid_n) {
+                                                                        int grid_n, int xbm) {
     constexpr int THREADS = WM * WN * kWave;
     constexpr int WTM = BM / WM, WTN = BN / WN;
     constexpr int MI = WTM / 32, NI = WTN / 32;
@@ -160,9 +164,11 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
     const int ntiles = grid_m * grid_n;
 
     // Tile order.  Workgroups are dealt round-robin to the 8 XCDs, each with its own L2; give
-    // each XCD one contiguous range of tiles, N fastest, so that the tiles running together
-    // on an XCD read the same rows of codes (the large operand: 16 KiB per stage against 2 KiB
-    // of packed weights) and those rows come out of HBM once per XCD.
+    // each XCD one contiguous range of the tile sequence, so that the tiles running together on
+    // an XCD share operands in its L2.  The sequence walks bands of xbm rows of tiles, inside a
+    // band the rows fastest: an XCD's range is then a block of xbm x (range / xbm) tiles and it
+    // fetches xbm row blocks of codes (BM x K bytes each) and range / xbm column blocks of packed
+    // weights (BN x K / 8 bytes each); the host picks the xbm that makes the sum smallest.
     auto tile_origin = [&](int t, int64_t& m0, int64_t& n0) {
         int logical = t;
         const int G = (int)gridDim.x;
@@ -172,8 +178,15 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
             // the XCD's range may end before the last round does
             if (q >= (ntiles >> 3)) logical = -1;
         }
-        m0 = logical < 0 ? -1 : (int64_t)(logical / grid_n) * BM;
-        n0 = logical < 0 ? -1 : (int64_t)(logical % grid_n) * BN;
+        int tm = logical / grid_n, tn = logical % grid_n;
+        if (xbm > 1 && logical >= 0) {
+            const int band = logical / (xbm * grid_n), rem = logical - band * xbm * grid_n;
+            const int rows = min(xbm, grid_m - band * xbm);  // the last band may be lower
+            tm = band * xbm + rem % rows;
+            tn = rem / rows;
+        }
+        m0 = logical < 0 ? -1 : (int64_t)tm * BM;
+        n0 = logical < 0 ? -1 : (int64_t)tn * BN;
     };
 
     // ---- DMA of one stage: thread -> P pieces; piece = (row, swizzled 16-byte segment) ----
@@ -184,7 +197,7 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
     int gseg[P];
     const int8_t* gbase = a.codes;
     const uint32_t* bsrc[NBW];
-    auto setup_dma = [&](int64_t m0, int64_t n0) {
+    auto setup_dma = [&](int64_t m0, int64_t n0, int grp) {
 #pragma unroll
         for (int q = 0; q < P; ++q) {
             const int slot = q * THREADS + threadIdx.x;
@@ -193,14 +206,15 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
             if (m0 + row > M - 1) row = (int)(M - 1 - m0);
             goff[q] = (uint32_t)row * (uint32_t)a.ldq + gseg[q];
         }
-        gbase = a.codes + m0 * a.ldq;
+        gbase = a.codes + m0 * a.ldq + (KGRP ? (int64_t)grp * K : 0);
         // packed weights: tile t of the block goes to smB + t KiB, lane for lane as it lies in
         // memory; wave w moves tiles w, w + NWAVES, ...  Columns past N read a valid tile.
 #pragma unroll
         for (int q = 0; q < NBW; ++q) {
             int64_t tn = (n0 >> 4) + w + q * NWAVES;
             if (tn > TN - 1) tn = TN - 1;
-            bsrc[q] = a.packed + tile_dword_offset(tn, 0, TKp) + l * 4;
+            bsrc[q] = a.packed + (KGRP ? (int64_t)grp * a.group_packed : 0) +
+                      tile_dword_offset(tn, 0, TKp) + l * 4;
         }
     };
     const uint32_t lds_wave = (uint32_t)(w * kWave * 16);
@@ -310,11 +324,14 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
     };
 
     int t = (int)blockIdx.x, parity = 0;
+    int grp = 0;  // KGRP: the K-group of the current work item
+    const int ngroups = KGRP ? a.kgroups : 1;
     int64_t m0, n0;
     tile_origin(t, m0, n0);
     if (m0 < 0) return;  // uniform for the whole workgroup
-    setup_dma(m0, n0);
+    setup_dma(m0, n0, 0);
     issue_tile_start();
+    float side[KGRP ? MI : 1][KGRP ? NI : 1][16];  // KGRP: the tile's sum over the groups so far
 
     while (true) {
         if constexpr (GEN) {
@@ -331,11 +348,14 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
                 // with one beta for the matrix the quotient is 0 by itself; the Eq. 6 operands are
                 // read from a valid stand-in address when they are not in use
                 const uint32_t bg = (uint32_t)n / (uint32_t)a.beta_rows;
-                const float gm = a.gamma[a.per_tensor ? 0 : m * a.gstride];
-                const int rs = a.rowsum[m * a.gstride];
-                const float b = a.beta[bg * a.beta_stride];
-                const float e = *(a.eta ? a.eta + (a.per_tensor ? 0 : m * a.gstride) : a.gamma);
-                const int ws = *(a.eta ? a.wsum + n : a.rowsum);
+                // KGRP: group grp's entries lie grp further on (gamma, rowsum, eta: [M][groups] or
+                // [groups] per tensor; beta: [row groups][groups]); wsum: [groups][N]
+                const int64_t go = KGRP ? grp : 0;
+                const float gm = a.gamma[(a.per_tensor ? 0 : m * a.gstride) + go];
+                const int rs = a.rowsum[m * a.gstride + go];
+                const float b = a.beta[bg * a.beta_stride + go];
+                const float e = *(a.eta ? a.eta + (a.per_tensor ? 0 : m * a.gstride) + go : a.gamma);
+                const int ws = *(a.eta ? a.wsum + go * a.N + n : a.rowsum);
                 if (i < BM) {
                     // gamma / 128 is exact, so beta * (gamma / 128) has the bits of (beta * gamma) / 128
                     lds_write_b32((uint32_t)(uintptr_t)&smScale[parity][i], __float_as_uint(gm * 0.0078125f));
@@ -389,11 +409,15 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
 
         // Every wave is done with the LDS ring: start the next tile's stream, then store.
         block_barrier();
-        const int t_next = t + (int)gridDim.x;
+        // the next work item: the tile's next K-group, else the workgroup's next tile
+        const bool last_group = !KGRP || grp + 1 == ngroups;
+        const int grp_next = last_group ? 0 : grp + 1;
+        const int t_next = last_group ? t + (int)gridDim.x : t;
         int64_t m0n = -1, n0n = -1;
-        if (t_next < ntiles) tile_origin(t_next, m0n, n0n);
+        if (!last_group) m0n = m0, n0n = n0;
+        else if (t_next < ntiles) tile_origin(t_next, m0n, n0n);
         if (m0n >= 0) {
-            setup_dma(m0n, n0n);
+            setup_dma(m0n, n0n, grp_next);
             issue_tile_start();
         }
 
@@ -437,6 +461,19 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
                         // y = acc * ((beta * gamma) / 128)
                         // (GEN: sc4 holds gamma / 128, else the whole scale)
                         float y = GEN ? (float)pm * (bcol[s] * sc4[rr]) : (float)pm * sc4[rr];
+                        if constexpr (KGRP) {
+                            if (a.eta) {  // Eq. 6 / Eq. 14: + (beta_g * eta_g) * sum_{k in g} s[n,k]
+                                const float e = lds_read_f32(
+                                    (uint32_t)(uintptr_t)&smEta[parity][wm * WTM + 32 * mi + 8 * rq + 4 * g2 + rr]);
+                                y = y + (bcol[s] * e) * wcol[s];
+                            }
+                            // groups are added in the order 0, 1, ... (as launches per group would)
+                            if (grp) y = y + side[mi][s][r];
+                            side[mi][s][r] = y;
+                            if (!last_group) continue;
+                            __builtin_nontemporal_store(y, &a.Y[m * a.N + n]);
+                            continue;
+                        }
                         if (special) {  // uniform
                             if (a.out_acc) {
                                 reinterpret_cast<int*>(a.Y)[m * a.N + n] = pm;
@@ -457,6 +494,7 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
             }
         if (m0n < 0) break;
         t = t_next;
+        grp = grp_next;
         m0 = m0n;
         n0 = n0n;
         parity ^= 1;
@@ -483,12 +521,31 @@ static void launch_tile(const GemmArgs& a, hipStream_t s) {
     int grid = num_cus();  // one workgroup per CU
     if (tuning().prefill_grid > 0) grid = tuning().prefill_grid;
     if (grid > ntiles) grid = ntiles;
+    // rows of tiles in an XCD's block: fewest operand bytes fetched per XCD (a row block of codes
+    // is BM x K bytes, a column block of packed weights BN x K / 8)
+    int xbm = 1;
+    if ((ntiles & 7) == 0 && (grid & 7) == 0) {
+        const int range = ntiles / 8;
+        int64_t best = -1;
+        for (int r = 1; r <= 8 && r <= grid_m; r *= 2) {
+            const int64_t bytes = (int64_t)r * BM * 8 + (int64_t)((range + r - 1) / r) * BN;
+            if (best < 0 || bytes < best) best = bytes, xbm = r;
+        }
+        if (tuning().prefill_xbm > 0) xbm = tuning().prefill_xbm < grid_m ? tuning().prefill_xbm : grid_m;
+    }
+    if constexpr (BM == 128) {
+        if (a.kgroups > 1) {  // all K-groups of a grouped layer in this launch
+            gemm_prefill_kernel<BM, BN, WM, WN, NS, true, true>
+                <<<(unsigned)grid, WM * WN * kWave, 0, s>>>(a, grid_m, grid_n, xbm);
+            return;
+        }
+    }
     if (plain)
         gemm_prefill_kernel<BM, BN, WM, WN, NS, false>
-            <<<(unsigned)grid, WM * WN * kWave, 0, s>>>(a, grid_m, grid_n);
+            <<<(unsigned)grid, WM * WN * kWave, 0, s>>>(a, grid_m, grid_n, xbm);
     else
         gemm_prefill_kernel<BM, BN, WM, WN, NS, true>
-            <<<(unsigned)grid, WM * WN * kWave, 0, s>>>(a, grid_m, grid_n);
+            <<<(unsigned)grid, WM * WN * kWave, 0, s>>>(a, grid_m, grid_n, xbm);
 }
 
 // K < 2^22 is required (the per-lane offset into a block of 256 rows is kept in 32 bits).
@@ -512,9 +569,11 @@ hipError_t launch_gemm_prefill(const GemmArgs& a_in, hipStream_t s) {
         pick = cost(128, 256) < cost(256, 256) ? 1 : 2;
     }
     if (a.M <= 64) {  // up to 32 tokens: gemm_stream.hip where it takes the shape; else gemm_mid.hip
-        if (!tuning().mid_only && launch_gemm_stream(a_in, s)) return hipGetLastError();
+        if (!tuning().mid_only && a_in.kgroups <= 1 && launch_gemm_stream(a_in, s)) return hipGetLastError();
         return launch_gemm_mid(a_in, s);
     }
+    // K-groups in one launch: the 128-row tile, whose accumulators leave room for the fp32 copy
+    if (a.kgroups > 1) pick = 1;
     if (pick == 1) launch_tile<128, 256, 2, 4, 8>(a, s);
     else launch_tile<256, 256, 2, 4, 8>(a, s);
     return hipGetLastError();

@@ -16,6 +16,7 @@ struct Tuning {
     int mid_only;          // 16 < M <= 32: skip the register-streaming kernel
     int prefill_tile;      // M > 64: 1 = 128 x 256 tiles, 2 = 256 x 256
     int prefill_grid;      // M > 64: workgroups of the persistent kernel
+    int prefill_xbm;       // M > 64: tile rows in the block of tiles an XCD owns (0: chosen per shape)
     int quant_wpr;         // quantiser: waves per row (1, 2, 4, 8)
     int bwd_ring;          // backward GEMM: 1 = ring kernel, 2 = small kernel
     int bwd_grid;          // backward ring kernel: workgroups
@@ -95,6 +96,14 @@ struct GemmArgs {
     int64_t split_k;
     int32_t* split_ws;
     size_t split_ws_bytes;  // what the caller offers; too small or nullptr: no split
+    // All K-groups of a grouped layer (Eq. 13-15) in one launch, M <= 64 (set by the caller
+    // together with split_ws of kgroups * M * N * 4 bytes): slice g of the launch is K-group g.
+    // codes, packed, K, gamma, rowsum, beta, eta, wsum describe group 0; group g reads codes + g * K,
+    // packed + g * group_packed dwords, and the fold applies gamma[.. + g], rowsum[.. + g], beta[.. + g],
+    // eta[.. + g], wsum[g * N + n] to its partial sums and adds the groups in the order 0, 1, ...
+    // 0 or 1: off.
+    int kgroups;
+    int64_t group_packed;
     // One token (M = 1, K <= 32768) straight from fp32, small-batch kernel only: every workgroup
     // normalises and quantises the row for itself (Eq. 12, Eq. 4-5) while its first weight tiles
     // are on their way, instead of reading codes / gamma / rowsum, so the layer is one launch.
