@@ -210,8 +210,10 @@ int bitlinear_forward_grouped(const float* X, int64_t M, int64_t K, const void* 
  *   dX     out  fp32 [M,K] = beta * dY W~           (gradient w.r.t. LN(x)), or NULL
  *   dW     out  fp32 [N,K] = dY^T (codes * gamma/128), or NULL; with a per-token gamma
  *               the factor gamma_m/128 is folded into row m of dY before the bf16 rounding
- * The workspace (bitlinear_workspace_bytes(BL_OP_BACKWARD, ...)) holds the bf16 operand
- * copies: about 2*(2*M*N + K*N + K*M) bytes. */
+ * The workspace (bitlinear_workspace_bytes(BL_OP_BACKWARD, ...)) holds the operand copies:
+ * dY as bf16 twice (rows and transposed), the codes transposed as bf16 and the weight signs
+ * regrouped (one bit each for large operands, bf16 for small ones): about 2*(2*M*N + K*M)
+ * + K*N/8 bytes for large operands, 2*(2*M*N + K*N + K*M) at most. */
 int bitlinear_backward_ste(const float* dY, int64_t M, int64_t N, int64_t K, const int8_t* codes,
                            const float* gamma, int granularity, const void* packed,
                            const float* beta, float* dX, float* dW, void* workspace,
