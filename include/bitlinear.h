@@ -315,6 +315,8 @@ int bitlinear_probe_read(const void* src, size_t bytes, int workgroups, int thre
  *   mid_kernel=1        32 < M <= 64: the LDS-tiled kernel with the K split inside the workgroup
  *   prefill_tile=1|2    M > 64: 128 x 256 or 256 x 256 output tiles
  *   prefill_grid=g      M > 64: workgroups of the persistent kernel
+ *   group_slices=1      grouped layers up to 64 tokens: every K-group a work item of its own instead of
+ *                       several K-groups inside one workgroup
  *   prefill_xbm=r       M > 64: rows of tiles in the block of tiles an XCD owns (1, 2, 4, 8; 0 = chosen per shape)
  *   quant_wpr=w         quantiser: waves per row (1, 2, 4, 8)
  *   bwd_ring=1|2        backward GEMMs: the ring kernel / the small kernel

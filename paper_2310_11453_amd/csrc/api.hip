@@ -24,6 +24,7 @@ const TuningField kTuningFields[] = {
     {"mid_split_tiles", &Tuning::mid_split_tiles}, {"mid_only", &Tuning::mid_only},
     {"prefill_tile", &Tuning::prefill_tile},     {"prefill_grid", &Tuning::prefill_grid},
     {"prefill_xbm", &Tuning::prefill_xbm},
+    {"group_slices", &Tuning::group_slices},
     {"quant_wpr", &Tuning::quant_wpr},           {"bwd_ring", &Tuning::bwd_ring},
     {"bwd_grid", &Tuning::bwd_grid},             {"bwd_rowmajor", &Tuning::bwd_rowmajor},
     {"mid_kernel", &Tuning::mid_kernel},

@@ -182,9 +182,15 @@ __device__ inline TokenQuant quant_token(const GemmArgs& a, uint32_t* lds_codes,
 // FUSED (one round, M = 1): the codes come from quant_token, not from memory.  1: a wave keeps
 // its slice of them in registers like codes read from memory; 2 (long K, many chunks per wave):
 // every MFMA takes its operand from LDS.
-template <int C, int T, int MAXT, bool ONE_ROUND, int FUSED = 0>
+// KGRP (one round, codes from memory): the a.kgroups K-groups of a grouped layer (Eq. 13-15) inside
+// one workgroup.  a.K is one group's K; the waves are dealt to the groups (W / kgroups consecutive
+// waves each, C chunks of the group's K per wave), every group reads its own columns of the codes
+// and its own blob of tiles, and a tile's sums are added per group and written to the group's slice
+// of split_ws (2 * sum_k q b, as a K split does), for splitk_reduce to dequantise group by group.
+template <int C, int T, int MAXT, bool ONE_ROUND, int FUSED = 0, bool KGRP = false>
 __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) {
     static_assert(!FUSED || ONE_ROUND, "the fused quantiser covers K in one round");
+    static_assert(!KGRP || (ONE_ROUND && !FUSED), "K-groups inside the workgroup: one round, codes from memory");
     constexpr bool kActLds = FUSED == 2;
     constexpr int kRowBytes = FUSED == 2 ? 32768 : 16384;  // longest row the fused kernels take
     __shared__ __attribute__((aligned(16))) int red[(MAXT / kWave) * T * 256];  // [W][T][64][4]
@@ -199,7 +205,13 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
     const int m = l & 15, g = l >> 4;
     const int64_t TKp = a.tk_pitch ? a.tk_pitch : tiles_k(a.K);  // tiles per tile row in memory
     const bool to_slices = a.split_k || a.kgroups > 1;  // partial sums go to split_ws
-    if (a.kgroups > 1) {  // this workgroup's K-group (uniform)
+    // KGRP: waves per K-group, this wave's group and its index inside the group
+    const int wpg = KGRP ? W / a.kgroups : W;
+    const int gw = KGRP ? w / wpg : 0, wg = KGRP ? w % wpg : w;
+    if constexpr (KGRP) {  // this wave's K-group (wave-uniform)
+        a.codes += (int64_t)gw * a.K;
+        a.packed += (int64_t)gw * a.group_packed;
+    } else if (a.kgroups > 1) {  // this workgroup's K-group (uniform)
         a.codes += (int64_t)blockIdx.y * a.K;
         a.packed += (int64_t)blockIdx.y * a.group_packed;
     } else if (a.split_k) {  // this workgroup's slice of K (uniform)
@@ -222,7 +234,7 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
     const int mc = m < M ? m : M - 1;
     int rs = 0;
     float gm = 0.f, eta = 0.f;
-    if constexpr (!FUSED) {
+    if constexpr (!FUSED && !KGRP) {
         rs = a.rowsum[mc * a.gstride];
         gm = a.per_tensor ? a.gamma[0] : a.gamma[mc * a.gstride];
         // Eq. 6 only; without it the load goes to gamma (always valid) and the value is not used
@@ -239,7 +251,7 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
 
     const int64_t rounds = ONE_ROUND ? 1 : (TK + (int64_t)W * C - 1) / ((int64_t)W * C);
     for (int64_t rd = 0; rd < rounds; ++rd) {
-        const int64_t tk0 = (rd * W + w) * C;
+        const int64_t tk0 = (rd * W + wg) * C;
 
         // Every load below is unconditional (addresses are clamped instead of guarded): with
         // no branches around them the loads complete in issue order and the MFMAs of tile t
@@ -370,6 +382,25 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
                 (v4i){part[t][0], part[t][1], part[t][2], part[t][3]};
     }
     __syncthreads();
+    if constexpr (KGRP) {
+        // (tile, group) pairs are dealt to the waves; a pair's sum runs over the group's waves
+        for (int item = w; item < tpb * a.kgroups; item += W) {
+            const int t = item % tpb, grp = item / tpb;
+            v4i sum = (v4i){0, 0, 0, 0};
+            for (int ww = grp * wpg; ww < (grp + 1) * wpg; ++ww)
+                sum += *reinterpret_cast<const v4i*>(&red[((ww * T + t) * kWave + l) * 4]);
+            const int64_t tn = tn0 + t;
+            const int64_t n = tn * kTileN + 4 * g;
+            if (tn >= TN || m >= M || n >= a.N) continue;
+            int* p = a.split_ws + ((int64_t)grp * M + m) * a.N + n;
+            const v4i h = sum >> 6;
+            if ((a.N & 3) == 0) *reinterpret_cast<v4i*>(p) = h;
+            else
+                for (int r = 0; r < 4; ++r)
+                    if (n + r < a.N) p[r] = h[r];
+        }
+        return;
+    }
     for (int t = w; t < tpb; t += W) {
         v4i sum = (v4i){0, 0, 0, 0};
         for (int ww = 0; ww < W; ++ww)
@@ -412,6 +443,36 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
             }
         }
     }
+}
+
+// Fold of a grouped layer's slices (Eq. 13-15), four consecutive columns per thread (N % 4 == 0):
+// each K-group's sums are dequantised with its own beta_g gamma_g / 128 (and shifted by its own
+// eta_g, Eq. 14) and the groups are added in the order 0, 1, ...
+__global__ __launch_bounds__(256) void groups_reduce4(GemmArgs a) {
+    const int64_t N4 = a.N >> 2;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= a.M * N4) return;
+    const int64_t m = idx / N4, n = (idx % N4) * 4;
+    const int G = a.kgroups;
+    uint32_t bg[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+        bg[c] = ((uint32_t)(n + c) / (uint32_t)a.beta_rows) * (uint32_t)a.beta_stride;
+    v4f y = {0.f, 0.f, 0.f, 0.f};
+    for (int g = 0; g < G; ++g) {
+        const v4i part = *reinterpret_cast<const v4i*>(a.split_ws + ((int64_t)g * a.M + m) * a.N + n);
+        const int rs = a.rowsum[m * a.gstride + g];
+        const float gm = a.gamma[a.per_tensor ? g : m * a.gstride + g];
+        const float eta = a.eta ? a.eta[a.per_tensor ? g : m * a.gstride + g] : 0.f;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const float beta = a.beta[bg[c] + g];
+            float yg = (float)(part[c] - rs) * ((beta * gm) / 128.0f);
+            if (a.eta) yg = yg + (beta * eta) * (float)a.wsum[(int64_t)g * a.N + n + c];
+            y[c] = g ? yg + y[c] : yg;
+        }
+    }
+    *reinterpret_cast<v4f*>(a.Y + m * a.N + n) = y;
 }
 
 // Second step of a K split: Y[m,n] = epilogue(sum_s partial[s][m][n] - rowsum[m]).
@@ -465,27 +526,27 @@ static int num_cus() {
     return n;
 }
 
-template <int C, int T, int MAXT, bool ONE_ROUND, int FUSED = 0>
+template <int C, int T, int MAXT, bool ONE_ROUND, int FUSED = 0, bool KGRP = false>
 static void launch_one(const GemmArgs& a, int W, int tpb, hipStream_t s) {
     const int64_t TN = tiles_n(a.N);
-    const unsigned splits = a.kgroups > 1 ? (unsigned)a.kgroups
+    const unsigned splits = KGRP ? 1u : a.kgroups > 1 ? (unsigned)a.kgroups
                             : a.split_k ? (unsigned)((a.K + a.split_k - 1) / a.split_k) : 1u;
     const dim3 grid((unsigned)((TN + tpb - 1) / tpb), splits);
-    gemm_decode_kernel<C, T, MAXT, ONE_ROUND, FUSED><<<grid, W * kWave, 0, s>>>(a, tpb);
+    gemm_decode_kernel<C, T, MAXT, ONE_ROUND, FUSED, KGRP><<<grid, W * kWave, 0, s>>>(a, tpb);
 }
 
 // one round, up to 8 waves, exactly tpb = 1..8 tiles per group
-template <int C, int FUSED>
+template <int C, int FUSED, bool KGRP = false>
 static void launch_tiles(const GemmArgs& a, int W, int tpb, hipStream_t s) {
     switch (tpb) {
-        case 1: launch_one<C, 1, 512, true, FUSED>(a, W, 1, s); break;
-        case 2: launch_one<C, 2, 512, true, FUSED>(a, W, 2, s); break;
-        case 3: launch_one<C, 3, 512, true, FUSED>(a, W, 3, s); break;
-        case 4: launch_one<C, 4, 512, true, FUSED>(a, W, 4, s); break;
-        case 5: launch_one<C, 5, 512, true, FUSED>(a, W, 5, s); break;
-        case 6: launch_one<C, 6, 512, true, FUSED>(a, W, 6, s); break;
-        case 7: launch_one<C, 7, 512, true, FUSED>(a, W, 7, s); break;
-        default: launch_one<C, 8, 512, true, FUSED>(a, W, 8, s); break;
+        case 1: launch_one<C, 1, 512, true, FUSED, KGRP>(a, W, 1, s); break;
+        case 2: launch_one<C, 2, 512, true, FUSED, KGRP>(a, W, 2, s); break;
+        case 3: launch_one<C, 3, 512, true, FUSED, KGRP>(a, W, 3, s); break;
+        case 4: launch_one<C, 4, 512, true, FUSED, KGRP>(a, W, 4, s); break;
+        case 5: launch_one<C, 5, 512, true, FUSED, KGRP>(a, W, 5, s); break;
+        case 6: launch_one<C, 6, 512, true, FUSED, KGRP>(a, W, 6, s); break;
+        case 7: launch_one<C, 7, 512, true, FUSED, KGRP>(a, W, 7, s); break;
+        default: launch_one<C, 8, 512, true, FUSED, KGRP>(a, W, 8, s); break;
     }
 }
 
@@ -549,6 +610,10 @@ hipError_t launch_read_probe(const void* src, size_t bytes, int workgroups, int 
 }
 
 void launch_splitk_reduce(const GemmArgs& a, int splits, hipStream_t s) {
+    if (a.kgroups > 1 && (a.N & 3) == 0 && ((uintptr_t)a.Y & 15) == 0) {
+        groups_reduce4<<<(unsigned)((a.M * (a.N >> 2) + 255) / 256), 256, 0, s>>>(a);
+        return;
+    }
     splitk_reduce<<<(unsigned)((a.M * a.N + 255) / 256), 256, 0, s>>>(a, splits);
 }
 
@@ -562,8 +627,35 @@ hipError_t launch_gemm_decode(const GemmArgs& a_in, hipStream_t s) {
     if (a.kgroups > 1) {  // one slice per K-group; the caller sized split_ws for it
         if (fused || !a.split_ws || a.split_ws_bytes < (size_t)a.kgroups * a.M * a.N * 4)
             return hipErrorInvalidValue;
-        splits = a.kgroups;
         a.split_k = 0;
+        // All groups inside a workgroup when their chunks fit the waves of one (up to 8 waves of
+        // one or two chunks, or 16 waves with at most two tiles a group); a wave's chunks must
+        // lie in one group.  One round of workgroups then covers N as in the plain layer.
+        const int64_t V = TK * a.kgroups;  // chunks of all groups
+        auto tiles_for = [&](int cap) {
+            int tpb = (int)((TN + num_cus() - 1) / num_cus());
+            tpb = tpb > cap ? cap : tpb < 1 ? 1 : tpb;
+            const int t = tuning().decode_tiles;
+            return t >= 1 && t <= cap ? t : tpb;
+        };
+        bool done = true;
+        if (tuning().group_slices) done = false;  // (tests: the K-groups as slices of the grid)
+        else if (TK % 2 == 0 && V / 2 <= 8) launch_tiles<2, 0, true>(a, (int)(V / 2), tiles_for(8), s);
+        else if (V <= 8) launch_tiles<1, 0, true>(a, (int)V, tiles_for(8), s);
+        else if (TK % 2 == 0 && V / 2 <= 16) {
+            if (tiles_for(2) <= 1) launch_one<2, 1, 1024, true, 0, true>(a, (int)(V / 2), 1, s);
+            else launch_one<2, 2, 1024, true, 0, true>(a, (int)(V / 2), 2, s);
+        } else if (V <= 16) {
+            if (tiles_for(2) <= 1) launch_one<1, 1, 1024, true, 0, true>(a, (int)V, 1, s);
+            else launch_one<1, 2, 1024, true, 0, true>(a, (int)V, 2, s);
+        } else {
+            done = false;
+        }
+        if (done) {
+            launch_splitk_reduce(a, a.kgroups, s);
+            return hipGetLastError();
+        }
+        splits = a.kgroups;  // else: the K-groups as slices of the grid
     } else if (need && !fused && a.split_ws && a.split_ws_bytes >= need && !tuning().decode_nosplit) {
         splits = (int)((TK + 15) / 16);
         const int64_t per = (TK + splits - 1) / splits;  // tiles per slice, evenly

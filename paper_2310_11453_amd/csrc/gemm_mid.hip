@@ -74,9 +74,13 @@ __device__ inline void lds_wait(v4i (&a)[2]) {
 // Work item = (column tile, K-slice): blockIdx.x = slice * grid_n + tile.  With a.split_k the
 // slice's partial sums 2 * sum_k q b go to a.split_ws and splitk_reduce finishes; otherwise the
 // workgroup owns all of K and writes Y.
+// gmode 2 (a grouped layer, Eq. 13-15): a work item is (column tile, four K-groups of the layer), one
+// per K-group of the workgroup: each walks its own layer group's K (its own columns of the codes,
+// its own blob) and its sums go, without being added, to that group's slice of a.split_ws.
+// gmode 1: a work item is (column tile, one K-group of the layer), split over the workgroup's four.
 // NS = stages in each group's ring.
 template <int NS>
-__global__ __launch_bounds__(mid::THREADS) void gemm_mid_kernel(GemmArgs a, int grid_n) {
+__global__ __launch_bounds__(mid::THREADS) void gemm_mid_kernel(GemmArgs a, int grid_n, int gmode) {
     using namespace mid;
     // rings of the four K-groups; after the walk the same bytes hold two 64 x 128 int32 sums
     __shared__ __attribute__((aligned(1024))) uint8_t smA[KG * NS * STAGE_BYTES];
@@ -98,15 +102,19 @@ __global__ __launch_bounds__(mid::THREADS) void gemm_mid_kernel(GemmArgs a, int 
     // ---- this item's slice of K, then this group's chunks of it ----------------------------
     int64_t ki0 = 0, Ki = a.K;
     const bool to_slices = a.split_k || a.kgroups > 1;  // partial sums go to split_ws
-    if (a.kgroups > 1) {  // the slice is a K-group of a grouped layer: its own codes columns and blob
-        a.codes += (int64_t)sp * a.K;
-        a.packed += (int64_t)sp * a.group_packed;
+    const int lgrp = gmode == 2 ? sp * KG + kg : sp;  // gmode 1, 2: the layer's K-group walked here
+    if (gmode) {  // a K-group of a grouped layer: its own codes columns and blob
+        const int gi = lgrp < a.kgroups ? lgrp : a.kgroups - 1;
+        a.codes += (int64_t)gi * a.K;
+        a.packed += (int64_t)gi * a.group_packed;
     } else if (a.split_k) {
         ki0 = (int64_t)sp * a.split_k;
         Ki = a.K - ki0 < a.split_k ? a.K - ki0 : a.split_k;
     }
     const int64_t TKi = tiles_k(Ki);
-    const int64_t c0 = TKi * kg / KG, c1 = TKi * (kg + 1) / KG;
+    // gmode 2: the whole group (nothing for a group past the layer's last)
+    const int64_t c0 = gmode == 2 ? 0 : TKi * kg / KG;
+    const int64_t c1 = gmode == 2 ? (lgrp < a.kgroups ? TKi : 0) : TKi * (kg + 1) / KG;
     const int64_t k0 = ki0 + c0 * kChunkK;
     int64_t K = Ki - c0 * kChunkK;  // this group's K
     if (K > (c1 - c0) * kChunkK) K = (c1 - c0) * kChunkK;
@@ -121,6 +129,7 @@ __global__ __launch_bounds__(mid::THREADS) void gemm_mid_kernel(GemmArgs a, int 
         const int64_t d = TKi * (g + 1) / KG - TKi * g / KG;
         TKmax = d > TKmax ? d : TKmax;
     }
+    if (gmode == 2) TKmax = TKi;
     const int nrun = (int)TKmax * SPC;
 
     // ---- epilogue operands of this thread's outputs, requested now ---------------------------
@@ -308,6 +317,32 @@ __global__ __launch_bounds__(mid::THREADS) void gemm_mid_kernel(GemmArgs a, int 
         return red + region * (BM * BN) + (32 * mi + 8 * (r >> 2) + 4 * g2 + (r & 3)) * BN + wn * 64 +
                32 * s2 + j;
     };
+    if (gmode == 2) {  // four K-groups of the layer: each group's sums to its own slice
+        static_assert(KG * NS * STAGE_BYTES >= KG * BM * BN * 4, "room for the four groups' sums");
+#pragma unroll
+        for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) *red_at(kg, mi, s2, r) = acc[mi][s2][r];
+        __syncthreads();
+        const bool vec = (N & 3) == 0;
+#pragma unroll
+        for (int h = 0; h < BM * (BN / 4) / THREADS; ++h) {
+            const int64_t m = er + (THREADS / (BN / 4)) * h;
+            if (m >= M || nq >= N) continue;
+            for (int rg = 0; rg < KG && sp * KG + rg < a.kgroups; ++rg) {
+                const v4i t = *reinterpret_cast<const v4i*>(red + rg * (BM * BN) + (int)m * BN +
+                                                             (threadIdx.x & 31) * 4) * 2;
+                int* o = a.split_ws + ((int64_t)(sp * KG + rg) * M + m) * N + nq;
+                if (vec) *reinterpret_cast<v4i*>(o) = t;
+                else
+                    for (int c = 0; c < 4; ++c)
+                        if (nq + c < N) o[c] = t[c];
+            }
+        }
+        return;
+    }
     if (kg >= 2) {
 #pragma unroll
         for (int mi = 0; mi < 2; ++mi)
@@ -403,17 +438,21 @@ hipError_t launch_gemm_mid(const GemmArgs& a_in, hipStream_t s) {
     int splits = 1;
     const int64_t per = prefill_split_tiles(a.M, a.N, a.K);
     const size_t need = gemm_split_ws_bytes(a.M, a.N, a.K);
-    if (a.kgroups > 1) {  // one slice per K-group; the caller sized split_ws for it
+    int gmode = 0;
+    if (a.kgroups > 1) {  // the caller sized split_ws for one slice per K-group
         if (!a.split_ws || a.split_ws_bytes < (size_t)a.kgroups * a.M * a.N * 4)
             return hipErrorInvalidValue;
-        splits = a.kgroups;
+        // four K-groups per work item, one per K-group of the workgroup, unless the layer's groups
+        // are long enough to be worth splitting over the workgroup's four themselves
+        gmode = tuning().group_slices || tiles_k(a.K) >= 8 ? 1 : 2;
+        splits = gmode == 2 ? (a.kgroups + mid::KG - 1) / mid::KG : a.kgroups;
     } else if (per && a.split_ws && a.split_ws_bytes >= need && !tuning().mid_nosplit) {
         splits = (int)((tiles_k(a.K) + per - 1) / per);
         a.tk_pitch = a.tk_pitch ? a.tk_pitch : tiles_k(a.K);
         a.split_k = per * kChunkK;
     }
-    gemm_mid_kernel<4><<<(unsigned)(grid_n * splits), mid::THREADS, 0, s>>>(a, grid_n);
-    if (splits > 1) launch_splitk_reduce(a, splits, s);
+    gemm_mid_kernel<4><<<(unsigned)(grid_n * splits), mid::THREADS, 0, s>>>(a, grid_n, gmode);
+    if (splits > 1 || gmode) launch_splitk_reduce(a, gmode ? a.kgroups : splits, s);
     return hipGetLastError();
 }
 

@@ -21,6 +21,7 @@ struct Tuning {
     int bwd_ring;          // backward GEMM: 1 = ring kernel, 2 = small kernel
     int bwd_grid;          // backward ring kernel: workgroups
     int bwd_rowmajor;      // backward ring kernel: plain row-major tile order
+    int group_slices;      // grouped layer, M <= 64: every K-group a slice of the grid (work item) of its own
     int mid_kernel;        // 32 < M <= 64: 1 = LDS-tiled kernel with the in-workgroup K split
 };
 const Tuning& tuning();

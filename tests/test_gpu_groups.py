@@ -130,6 +130,25 @@ def test_grouped_forward_ragged(bl):
     _check_forward(bl, 33, 384, 240, 3, 4, False, 503)
 
 
+@pytest.mark.parametrize("M,K,N,gn,gk", [(5, 16384, 256, 1, 8),   # 16 waves of two chunks
+                                         (9, 6144, 256, 2, 4),    # 12 waves of one chunk
+                                         (3, 32768, 128, 1, 8),   # too many chunks for one workgroup
+                                         (40, 8192, 384, 1, 2),   # 33-64 tokens, long K-groups
+                                         (64, 3072, 256, 2, 6)])  # 33-64 tokens, six groups in two items
+def test_grouped_forward_group_placement(bl, tuning, M, K, N, gn, gk):
+    """Up to 64 tokens the K-groups share workgroups where they fit (waves dealt to the groups in
+    the small-batch kernel, one K-group of the workgroup per layer group in the mid-batch one) and
+    are work items of their own otherwise; both placements give the same bits."""
+    print(f"grouped placement M={M} K={K} N={N} gn={gn} gk={gk}", flush=True)
+    _check_forward(bl, M, K, N, gn, gk, False, 600 + M)
+    X, W = layer(M, K, N, 600 + M)
+    packed, alpha, beta = bl.bitlinear_pack_weights_grouped(dev(W), gn, gk)
+    y0 = host(bl.bitlinear_forward_grouped(dev(X), packed, N, beta, gn, gk))
+    tuning("group_slices=1")
+    y1 = host(bl.bitlinear_forward_grouped(dev(X), packed, N, beta, gn, gk))
+    assert np.array_equal(y0, y1)
+
+
 def test_grouped_forward_full_size_30b(bl):
     """A 30B-shaped layer (7168 -> 28672) with eight groups on each axis, decode and prefill batch:
     alpha_g, beta_g and all bits; codes and gamma_g given the normalised input the GPU dumped;
