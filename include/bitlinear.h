@@ -317,7 +317,7 @@ int bitlinear_probe_read(const void* src, size_t bytes, int workgroups, int thre
  *   prefill_grid=g      M > 64: workgroups of the persistent kernel
  *   group_slices=1      grouped layers up to 64 tokens: every K-group a work item of its own instead of
  *                       several K-groups inside one workgroup
- *   prefill_xbm=r       M > 64: rows of tiles in the block of tiles an XCD owns (1, 2, 4, 8; 0 = chosen per shape)
+ *   prefill_xbm=r       M > 64: rows of tiles in the block of tiles an XCD owns (1, 2, 4, 8; 0 = 1, the fastest measured; more rows fetch fewer bytes)
  *   quant_wpr=w         quantiser: waves per row (1, 2, 4, 8)
  *   bwd_ring=1|2        backward GEMMs: the ring kernel / the small kernel
  *   bwd_grid=g, bwd_rowmajor=1   backward ring kernel: workgroups, plain tile order

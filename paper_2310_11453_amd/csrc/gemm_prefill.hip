@@ -168,7 +168,7 @@ __global__ __launch_bounds__(WM * WN * 64, 2) void gemm_prefill_kernel(GemmArgs 
     // an XCD share operands in its L2.  The sequence walks bands of xbm rows of tiles, inside a
     // band the rows fastest: an XCD's range is then a block of xbm x (range / xbm) tiles and it
     // fetches xbm row blocks of codes (BM x K bytes each) and range / xbm column blocks of packed
-    // weights (BN x K / 8 bytes each); the host picks the xbm that makes the sum smallest.
+    // weights (BN x K / 8 bytes each).  xbm = 1 unless the host asks otherwise (see launch_tile).
     auto tile_origin = [&](int t, int64_t& m0, int64_t& n0) {
         int logical = t;
         const int G = (int)gridDim.x;
@@ -521,18 +521,14 @@ static void launch_tile(const GemmArgs& a, hipStream_t s) {
     int grid = num_cus();  // one workgroup per CU
     if (tuning().prefill_grid > 0) grid = tuning().prefill_grid;
     if (grid > ntiles) grid = ntiles;
-    // rows of tiles in an XCD's block: fewest operand bytes fetched per XCD (a row block of codes
-    // is BM x K bytes, a column block of packed weights BN x K / 8)
+    // Rows of tiles in an XCD's block.  One row (the XCD's tiles share their codes and stream all
+    // the packed weights) is the fastest on every shape measured, although two or four rows fetch
+    // fewer bytes: 2048 x 4096 x 16384 takes 115.2 us with 1 (84 MB fetched per launch), 117.5 us
+    // with 2 (55 MB), 124.1 us with 4 (medians of 12 alternating runs); the kernel is not bound by
+    // HBM.  prefill_xbm overrides.
     int xbm = 1;
-    if ((ntiles & 7) == 0 && (grid & 7) == 0) {
-        const int range = ntiles / 8;
-        int64_t best = -1;
-        for (int r = 1; r <= 8 && r <= grid_m; r *= 2) {
-            const int64_t bytes = (int64_t)r * BM * 8 + (int64_t)((range + r - 1) / r) * BN;
-            if (best < 0 || bytes < best) best = bytes, xbm = r;
-        }
-        if (tuning().prefill_xbm > 0) xbm = tuning().prefill_xbm < grid_m ? tuning().prefill_xbm : grid_m;
-    }
+    if ((ntiles & 7) == 0 && (grid & 7) == 0 && tuning().prefill_xbm > 0)
+        xbm = tuning().prefill_xbm < grid_m ? tuning().prefill_xbm : grid_m;
     if constexpr (BM == 128) {
         if (a.kgroups > 1) {  // all K-groups of a grouped layer in this launch
             gemm_prefill_kernel<BM, BN, WM, WN, NS, true, true>

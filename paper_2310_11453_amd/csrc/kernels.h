@@ -16,7 +16,7 @@ struct Tuning {
     int mid_only;          // 16 < M <= 32: skip the register-streaming kernel
     int prefill_tile;      // M > 64: 1 = 128 x 256 tiles, 2 = 256 x 256
     int prefill_grid;      // M > 64: workgroups of the persistent kernel
-    int prefill_xbm;       // M > 64: tile rows in the block of tiles an XCD owns (0: chosen per shape)
+    int prefill_xbm;       // M > 64: tile rows in the block of tiles an XCD owns (0: one)
     int quant_wpr;         // quantiser: waves per row (1, 2, 4, 8)
     int bwd_ring;          // backward GEMM: 1 = ring kernel, 2 = small kernel
     int bwd_grid;          // backward ring kernel: workgroups
