@@ -351,6 +351,29 @@ def test_empty_batch_and_errors(bl):
                              workspace=torch.empty(16, dtype=torch.uint8, device="cuda"))
 
 
+def test_read_probe_reads_only(bl):
+    """The measurement aid: any launch shape within its limits runs, leaves the buffer and a sink as
+    they were (real data never trips its all-ones test), and bad shapes are host errors."""
+    import ctypes
+    lib = bl.load_library()
+    rng = np.random.default_rng(7)
+    words = rng.integers(0, 2**31, size=(1 << 20) + 12, dtype=np.int64).astype(np.uint32)
+    buf = dev(words.view(np.int32))
+    sink = torch.zeros(1024, dtype=torch.int32, device="cuda")
+    for wgs, threads in [(1, 64), (256, 448), (1000, 1024), (37, 192)]:
+        rc = lib.bitlinear_probe_read(ctypes.c_void_p(buf.data_ptr()), buf.numel() * 4, wgs, threads,
+                                      ctypes.c_void_p(sink.data_ptr()), None)
+        assert rc == 0
+    torch.cuda.synchronize()
+    assert np.array_equal(host(buf).view(np.uint32), words)
+    assert int(sink.abs().sum()) == 0
+    p = ctypes.c_void_p(buf.data_ptr())
+    assert lib.bitlinear_probe_read(p, 24, 1, 64, None, None) == -2      # bytes % 16
+    assert lib.bitlinear_probe_read(p, 1024, 1, 96, None, None) == -2    # threads % 64
+    assert lib.bitlinear_probe_read(p, 1024, 0, 64, None, None) == -2
+    assert lib.bitlinear_probe_read(None, 1024, 1, 64, None, None) == -1
+
+
 # ------------------------------------------------------------------ full benchmark sizes
 def _stratified_samples(M, N, seed, bm=64, bn=64, lines=3):
     """(rows, cols) of the outputs to check: one seeded position inside every bm x bn block of the
