@@ -272,7 +272,28 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
                     act[c][i] = *reinterpret_cast<const v4i*>(arow + k);
                 }
         };
-        if constexpr (!FUSED) load_act(a.codes + (int64_t)(m < M ? m : M - 1) * a.ldq);
+        // Few tokens: the wave's slice of the codes is M rows of C * 512 bytes, and fetching it in
+        // operand layout costs C * 8 load instructions whatever M is (at one token as much time on
+        // the load path as a seventh of the weight stream).  Instead each row is fetched with one
+        // instruction, 16 consecutive bytes a lane, and (below, once the first weight tiles have
+        // been requested behind it) parked in the wave's own part of `red`, which holds nothing
+        // before the wave's first tile is done, and read from there in operand layout.
+        constexpr int kStageRows = T < 8 ? T : 8;
+        const bool staged = !FUSED && ONE_ROUND && M <= kStageRows;
+        const bool stage_lane = l < C * 32;
+        v4i rowv[kStageRows];
+        if constexpr (!FUSED) {
+            if (staged) {
+                int kl = (int)tk0 * kChunkK + 16 * l;  // this lane's 16 bytes of a row slice
+                kl = kl > (int)a.K - 16 ? (int)a.K - 16 : kl;
+#pragma unroll
+                for (int r = 0; r < kStageRows; ++r)
+                    if (r < M && stage_lane)
+                        rowv[r] = *reinterpret_cast<const v4i*>(a.codes + (int64_t)r * a.ldq + kl);
+            } else {
+                load_act(a.codes + (int64_t)(m < M ? m : M - 1) * a.ldq);
+            }
+        }
 
         // Weight tiles: a software pipeline of depth kDepth per wave.  Asking for everything at
         // once looks attractive for a 4-microsecond stream, but the memory system then returns
@@ -321,6 +342,18 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
         } else {
 #pragma unroll
             for (int t = 0; t < kDepth; ++t) load_tile(t);
+            if (staged) {  // rows past M repeat row M-1 (never stored)
+                int* stage = &red[w * T * 256];
+#pragma unroll
+                for (int r = 0; r < kStageRows; ++r)
+                    if (r < M && stage_lane) *reinterpret_cast<v4i*>(&stage[r * 256 + l * 4]) = rowv[r];
+                const int mr = m < M ? m : M - 1;
+#pragma unroll
+                for (int c = 0; c < C; ++c)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+                        act[c][i] = *reinterpret_cast<const v4i*>(&stage[mr * 256 + c * 128 + 16 * i + 4 * g]);
+            }
         }
 
 #pragma unroll
