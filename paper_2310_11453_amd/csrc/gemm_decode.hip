@@ -278,16 +278,19 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
         // instruction, 16 consecutive bytes a lane, and (below, once the first weight tiles have
         // been requested behind it) parked in the wave's own part of `red`, which holds nothing
         // before the wave's first tile is done, and read from there in operand layout.
+        // More tokens than the region has rows: the rows go through it in passes (the lanes of a
+        // pass's rows read their operands, then the next rows are parked).
         constexpr int kStageRows = T < 8 ? T : 8;
-        const bool staged = !FUSED && ONE_ROUND && M <= kStageRows;
+        constexpr int kStagePasses = (16 + kStageRows - 1) / kStageRows;
+        const bool staged = !FUSED && ONE_ROUND && (M <= kStageRows || T >= 4);
         const bool stage_lane = l < C * 32;
-        v4i rowv[kStageRows];
+        v4i rowv[16];
         if constexpr (!FUSED) {
             if (staged) {
                 int kl = (int)tk0 * kChunkK + 16 * l;  // this lane's 16 bytes of a row slice
                 kl = kl > (int)a.K - 16 ? (int)a.K - 16 : kl;
 #pragma unroll
-                for (int r = 0; r < kStageRows; ++r)
+                for (int r = 0; r < 16; ++r)
                     if (r < M && stage_lane)
                         rowv[r] = *reinterpret_cast<const v4i*>(a.codes + (int64_t)r * a.ldq + kl);
             } else {
@@ -344,15 +347,26 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
             for (int t = 0; t < kDepth; ++t) load_tile(t);
             if (staged) {  // rows past M repeat row M-1 (never stored)
                 int* stage = &red[w * T * 256];
-#pragma unroll
-                for (int r = 0; r < kStageRows; ++r)
-                    if (r < M && stage_lane) *reinterpret_cast<v4i*>(&stage[r * 256 + l * 4]) = rowv[r];
                 const int mr = m < M ? m : M - 1;
 #pragma unroll
-                for (int c = 0; c < C; ++c)
+                for (int p = 0; p < kStagePasses; ++p) {
+                    if (p * kStageRows < M) {  // uniform
 #pragma unroll
-                    for (int i = 0; i < 8; ++i)
-                        act[c][i] = *reinterpret_cast<const v4i*>(&stage[mr * 256 + c * 128 + 16 * i + 4 * g]);
+                        for (int r = 0; r < kStageRows; ++r)
+                            if (p * kStageRows + r < 16 && p * kStageRows + r < M && stage_lane)
+                                *reinterpret_cast<v4i*>(&stage[r * 256 + l * 4]) =
+                                    rowv[p * kStageRows + r < 16 ? p * kStageRows + r : 15];
+                        if (mr / kStageRows == p) {
+                            const int rr = mr - p * kStageRows;
+#pragma unroll
+                            for (int c = 0; c < C; ++c)
+#pragma unroll
+                                for (int i = 0; i < 8; ++i)
+                                    act[c][i] = *reinterpret_cast<const v4i*>(
+                                        &stage[rr * 256 + c * 128 + 16 * i + 4 * g]);
+                        }
+                    }
+                }
             }
         }
 
