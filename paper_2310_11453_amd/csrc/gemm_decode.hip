@@ -279,7 +279,9 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
         // been requested behind it) parked in the wave's own part of `red`, which holds nothing
         // before the wave's first tile is done, and read from there in operand layout.
         // More tokens than the region has rows: the rows go through it in passes (the lanes of a
-        // pass's rows read their operands, then the next rows are parked).
+        // pass's rows read their operands, then the next rows are parked).  A row is 1 KiB, so the
+        // same 16 bytes of every row would share their banks: the 16-byte slots of row r are stored
+        // at slot ^ (r % 16).
         constexpr int kStageRows = T < 8 ? T : 8;
         constexpr int kStagePasses = (16 + kStageRows - 1) / kStageRows;
         const bool staged = !FUSED && ONE_ROUND && (M <= kStageRows || T >= 4);
@@ -354,7 +356,7 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
 #pragma unroll
                         for (int r = 0; r < kStageRows; ++r)
                             if (p * kStageRows + r < 16 && p * kStageRows + r < M && stage_lane)
-                                *reinterpret_cast<v4i*>(&stage[r * 256 + l * 4]) =
+                                *reinterpret_cast<v4i*>(&stage[r * 256 + (l ^ (r & 15)) * 4]) =
                                     rowv[p * kStageRows + r < 16 ? p * kStageRows + r : 15];
                         if (mr / kStageRows == p) {
                             const int rr = mr - p * kStageRows;
@@ -363,7 +365,7 @@ __global__ __launch_bounds__(MAXT) void gemm_decode_kernel(GemmArgs a, int tpb) 
 #pragma unroll
                                 for (int i = 0; i < 8; ++i)
                                     act[c][i] = *reinterpret_cast<const v4i*>(
-                                        &stage[rr * 256 + c * 128 + 16 * i + 4 * g]);
+                                        &stage[rr * 256 + ((c * 32 + 4 * i + g) ^ (rr & 15)) * 4]);
                         }
                     }
                 }
